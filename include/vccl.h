@@ -1,0 +1,184 @@
+/*
+ * vccl.h - C boundary of the MI355X-native P2P data-movement library.
+ *
+ * The library moves the bytes behind the reduction-free P2P primitives SendRecv
+ * and AlltoAll(v) (paper Section 1, Challenge 1; Section 2.1) for P virtual
+ * ranks whose buffers all live in ONE device's HBM:
+ *
+ *     recv[r][rdispls[r][s] + i] = send[s][sdispls[s][r] + i]   for i < count(s -> r)
+ *
+ * Two data paths exist for every primitive:
+ *   VCCL_MODE_CU  a compute-unit copy kernel on the caller's stream (the kind of
+ *                 SM-consuming P2P kernel the paper sets out to remove, Section 2.2);
+ *   VCCL_MODE_CE  copy engines driven by a host proxy thread, with no kernel
+ *                 launched and stream order kept by events (the paper's SM-free
+ *                 P2P, Section 3.2 items 1-3).
+ *
+ * Conventions
+ *   - Every pointer named *_dev / every element of a buffer-pointer array is a
+ *     DEVICE address on the device given to vccl_init.  The pointer arrays
+ *     themselves, and all count / displacement / peer arrays, are HOST memory;
+ *     they are read during the call only (the library copies what it needs).
+ *   - Counts and displacements are BYTES (uint64_t).  Any byte alignment is
+ *     handled; 16-byte aligned addresses and lengths take the fast path.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     are asynchronous to the host, start after all work already enqueued on
+ *     `stream`, and work enqueued on `stream` afterwards sees the completed
+ *     receive buffers (the ordering contract of Section 3.2 item 3).
+ *   - The caller owns all data buffers.  Bytes of a receive buffer that no
+ *     segment covers are never written.  Send and receive regions must not
+ *     overlap (in-place exchange is not supported); receive segments must not
+ *     overlap each other.  With option "check"="1" the library verifies this
+ *     and returns VCCL_ERR_OVERLAP.
+ *   - Every function returns VCCL_OK (0) or a negative vccl_status.  On error
+ *     nothing has been enqueued, and vccl_last_error() describes the cause.
+ *   - Calls may be made from several host threads; calls on different streams
+ *     may overlap on the device.
+ */
+#ifndef VCCL_H
+#define VCCL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    VCCL_MODE_CU = 0,        /* compute-unit copy kernel, application buffer to application buffer */
+    VCCL_MODE_CE = 1,        /* copy engines + host proxy thread, no kernel */
+    VCCL_MODE_CU_STAGED = 2  /* vccl_sendrecv only: two-step copy through the chunk FIFO */
+} vccl_mode;
+
+typedef enum {
+    VCCL_OK = 0,
+    VCCL_ERR_ARG = -1,            /* null pointer with non-zero size, P out of range, bad mode/peer table */
+    VCCL_ERR_COUNT_MISMATCH = -2, /* sender's and receiver's byte counts disagree */
+    VCCL_ERR_OVERLAP = -3,        /* overlapping receive segments or send/recv aliasing ("check"="1") */
+    VCCL_ERR_HIP = -4,            /* a HIP runtime call failed; message holds hipGetErrorString */
+    VCCL_ERR_NOT_INIT = -5,       /* vccl_init has not been called (or vccl_finalize has) */
+    VCCL_ERR_UNSUPPORTED = -6,    /* mode not available for this primitive / device */
+    VCCL_ERR_TIMEOUT = -7         /* a bounded device-side wait of the staged FIFO gave up */
+} vccl_status;
+
+/* Largest number of virtual ranks vccl_init accepts. */
+#define VCCL_MAX_RANKS 256
+
+/* Create the library context on `device`: internal copy streams and events, the
+ * descriptor staging ring and the host proxy thread of the copy-engine path
+ * (the CPU proxy of Section 3.2).  max_ranks bounds P of later calls
+ * (1 .. VCCL_MAX_RANKS).  Calling it again after vccl_finalize is allowed;
+ * calling it twice without is VCCL_ERR_ARG. */
+int vccl_init(int device, int max_ranks);
+
+/* Wait for every operation handed to the library, stop the proxy thread and free
+ * everything the library owns.  Caller buffers are untouched. */
+int vccl_finalize(void);
+
+/* Message of the last failing call made by THIS thread (library-owned storage,
+ * valid until the thread's next failing call).  Never NULL. */
+const char *vccl_last_error(void);
+
+/* Tuning and test knobs; unknown keys or unparsable values give VCCL_ERR_ARG
+ * (silently ignored settings are the configuration hazard of Section 5).
+ * Keys: "cu_unroll" (16-byte vectors per lane per tile: 1,2,4,8),
+ *       "cu_wg_per_cu" (persistent workgroups per compute unit, 1..16),
+ *       "cu_max_wg" (cap on the copy grid, 0 = none; the co-run study sweeps it),
+ *       "cu_nontemporal" (0/1), "ce_streams" (1..8 internal copy streams),
+ *       "ce_kind" ("nocu" | "default": hipMemcpyKind of copy-engine copies),
+ *       "check" (0/1 overlap validation),
+ *       "fifo_chunk_bytes", "fifo_slots", "fifo_wg_per_conn",
+ *       "fifo_spin_limit" (polls before a staged wait gives up).
+ * vccl_get_option writes the current value as text into out[0..cap). */
+int vccl_set_option(const char *key, const char *value);
+int vccl_get_option(const char *key, char *out, int cap);
+
+/* SendRecv (pipeline-parallel activations, Section 3.2 "Improve overlaps in PP";
+ * the zero-copy application-buffer transfer of Section 3.2 item 1).
+ * Rank s sends sendbytes[s] bytes from sendbuf[s] to rank send_to[s]; rank r
+ * receives recvbytes[r] bytes into recvbuf[r] from rank recv_from[r].  send_to
+ * must be a permutation of 0..P-1 and recv_from its inverse (VCCL_ERR_ARG), and
+ * sendbytes[s] must equal recvbytes[send_to[s]] (VCCL_ERR_COUNT_MISMATCH).
+ * VCCL_MODE_CU / VCCL_MODE_CE copy directly; VCCL_MODE_CU_STAGED models NCCL's
+ * intra-node two-step path (Section 2.2): sender workgroups copy chunks into a
+ * library-owned FIFO of "fifo_slots" slots of "fifo_chunk_bytes", receiver
+ * workgroups copy them out, the sender never running more than the slot count
+ * ahead.  The FIFO is allocated on first use. */
+int vccl_sendrecv(void *const *sendbuf, const uint64_t *sendbytes, const int *send_to,
+                  void *const *recvbuf, const uint64_t *recvbytes, const int *recv_from,
+                  int P, vccl_mode mode, void *stream);
+
+/* Waits (on the host) for the most recent VCCL_MODE_CU_STAGED operation and returns
+ * VCCL_ERR_TIMEOUT if one of its bounded device-side FIFO waits gave up (the data
+ * is then incomplete), VCCL_OK otherwise. */
+int vccl_sendrecv_staged_status(void);
+
+/* The receiver-owned handshake record of a SendRecv connection in copy-engine mode
+ * (Section 3.2: receiverRegAddr, receiverReady, copyStarted, copyDone).  The
+ * paper's 1-bit flags are kept as sequence numbers that only grow: operation n on
+ * the connection is ready / started / done once the field has reached n.  Any
+ * output pointer may be NULL. */
+int vccl_p2p_reginfo(int receiver_rank, uint64_t *receiver_ready, uint64_t *copy_started,
+                     uint64_t *copy_done, void **receiver_reg_addr);
+
+/* AlltoAll with equal blocks (MoE token routing, Section 2.1): block r
+ * (bytes_per_peer bytes at offset r*bytes_per_peer) of sendbuf[s] becomes block s
+ * of recvbuf[r].  Every buffer holds at least P*bytes_per_peer bytes. */
+int vccl_alltoall(void *const *sendbuf, void *const *recvbuf, uint64_t bytes_per_peer,
+                  int P, vccl_mode mode, void *stream);
+
+/* AlltoAllv (the dispatch / combine exchange of Section 6).  sendcounts and
+ * sdispls are [P][P] row-major indexed [s][r]; recvcounts and rdispls are [P][P]
+ * indexed [r][s].  sendcounts[s][r] must equal recvcounts[r][s]
+ * (VCCL_ERR_COUNT_MISMATCH - a distributed library would hang instead).
+ * Zero-length segments are legal and their displacements are ignored. */
+int vccl_alltoallv(void *const *sendbuf, const uint64_t *sendcounts, const uint64_t *sdispls,
+                   void *const *recvbuf, const uint64_t *recvcounts, const uint64_t *rdispls,
+                   int P, vccl_mode mode, void *stream);
+
+/* MoE dispatch pack (Section 2.1 token routing; Section 6 dispatch phase) for all
+ * P source ranks in one call.  For rank s, x[s] holds `tokens` rows of row_bytes
+ * bytes (row_bytes a multiple of 16, rows 16-byte aligned) and expert_ids[s] holds
+ * tokens*topk int32 expert ids in [0, num_experts), row-major [token][slot].  The
+ * tokens*topk (token, slot) pairs are stably sorted by expert id (ties keep
+ * token-then-slot order) and packed[s] receives one copy of the token's row per
+ * pair, in that order, so that the rows for each destination rank are contiguous.
+ * counts_dev (device, uint64 [P][num_experts]) receives the number of pairs per
+ * expert; if counts_host is not NULL it must be pinned host memory of the same
+ * shape and an asynchronous copy of the counts is enqueued after the kernels
+ * (synchronise `stream` before reading it).  Ids outside the range are counted
+ * in *bad_ids_dev (device uint32, may be NULL) and their pairs are dropped.
+ * Runs on compute units only (it is index arithmetic plus a gather). */
+int vccl_moe_pack(const void *const *x, const int32_t *const *expert_ids, int P, int tokens,
+                  int topk, uint64_t row_bytes, int num_experts, void *const *packed,
+                  uint64_t *counts_dev, uint64_t *counts_host, uint32_t *bad_ids_dev, void *stream);
+
+/* Host-side planner step between pack and exchange: from counts [P][num_experts]
+ * (host) build the four [P][P] byte matrices for vccl_alltoallv.  Expert e lives on
+ * rank e / experts_per_rank; sdispls / rdispls are exclusive prefix sums (packed
+ * rows are already in destination order; received segments land in source-rank
+ * order).  num_experts must equal P*experts_per_rank. */
+int vccl_moe_exchange_layout(const uint64_t *counts, int P, int num_experts, int experts_per_rank,
+                             uint64_t row_bytes, uint64_t *sendcounts, uint64_t *sdispls,
+                             uint64_t *recvcounts, uint64_t *rdispls);
+
+/* Co-run probe (Appendix E: a compute kernel forming one wave of workgroups over
+ * all compute units, slowed by co-resident communication warps).  Launches a
+ * register-only FP32 FMA kernel of `workgroups` x `threads` (threads a multiple of
+ * 64, at most 1024) running `iters` dependent FMA rounds per lane; out_dev (device,
+ * workgroups*threads floats) receives one value per lane so the work cannot be
+ * elided.  workgroups = 0 selects one workgroup per compute unit. */
+int vccl_fma_probe(float *out_dev, uint32_t workgroups, uint32_t threads, uint64_t iters,
+                   void *stream);
+
+/* Counters of the copy-engine proxy since vccl_init: operations, copies issued,
+ * bytes, and nanoseconds the proxy spent issuing.  Any pointer may be NULL. */
+int vccl_proxy_stats(uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t *issue_ns);
+
+/* Number of compute units of the initialised device (for sizing probes). */
+int vccl_device_cu_count(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VCCL_H */

@@ -1,0 +1,18 @@
+"""MI355X-native P2P data movement behind SendRecv and AlltoAll(v).
+
+A thin ctypes binding over ``libvccl.so`` (hand-written HIP kernels and a
+copy-engine proxy behind a C boundary, see ``include/vccl.h``).  The binding
+only marshals arguments: every step of the path runs inside the library.
+There is no CPU fallback - if the library has not been built, importing the
+binding's functions raises.
+"""
+from .binding import (  # noqa: F401
+    MODE_CU, MODE_CE, MODE_CU_STAGED,
+    VcclError,
+    lib_path, load,
+    vccl_init, vccl_finalize, vccl_last_error, vccl_set_option, vccl_get_option,
+    vccl_sendrecv, vccl_sendrecv_staged_status, vccl_p2p_reginfo,
+    vccl_alltoall, vccl_alltoallv,
+    vccl_moe_pack, vccl_moe_exchange_layout,
+    vccl_fma_probe, vccl_proxy_stats, vccl_device_cu_count,
+)

@@ -1,0 +1,212 @@
+"""ctypes binding with the same names as the C boundary in ``include/vccl.h``.
+
+Buffers are passed as sequences of device addresses (``int``) or of objects with
+a ``data_ptr()`` method (torch tensors); count tables as anything NumPy can turn
+into ``uint64``; streams as an ``int`` handle (``torch.cuda.current_stream().cuda_stream``)
+or ``None`` for the null stream.  Nothing is computed here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+MODE_CU = 0
+MODE_CE = 1
+MODE_CU_STAGED = 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libvccl.so")
+_lib: Optional[ctypes.CDLL] = None
+
+_u64p = ctypes.POINTER(ctypes.c_uint64)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_vpp = ctypes.POINTER(ctypes.c_void_p)
+
+EXPORTS = {
+    "vccl_init": (ctypes.c_int, [ctypes.c_int, ctypes.c_int]),
+    "vccl_finalize": (ctypes.c_int, []),
+    "vccl_last_error": (ctypes.c_char_p, []),
+    "vccl_set_option": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_char_p]),
+    "vccl_get_option": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_char_p, ctypes.c_int]),
+    "vccl_sendrecv": (ctypes.c_int, [_vpp, _u64p, _i32p, _vpp, _u64p, _i32p, ctypes.c_int,
+                                     ctypes.c_int, ctypes.c_void_p]),
+    "vccl_sendrecv_staged_status": (ctypes.c_int, []),
+    "vccl_p2p_reginfo": (ctypes.c_int, [ctypes.c_int, _u64p, _u64p, _u64p, _vpp]),
+    "vccl_alltoall": (ctypes.c_int, [_vpp, _vpp, ctypes.c_uint64, ctypes.c_int, ctypes.c_int,
+                                     ctypes.c_void_p]),
+    "vccl_alltoallv": (ctypes.c_int, [_vpp, _u64p, _u64p, _vpp, _u64p, _u64p, ctypes.c_int,
+                                      ctypes.c_int, ctypes.c_void_p]),
+    "vccl_moe_pack": (ctypes.c_int, [_vpp, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                     ctypes.c_uint64, ctypes.c_int, _vpp, ctypes.c_void_p,
+                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+    "vccl_moe_exchange_layout": (ctypes.c_int, [_u64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                ctypes.c_uint64, _u64p, _u64p, _u64p, _u64p]),
+    "vccl_fma_probe": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32,
+                                      ctypes.c_uint64, ctypes.c_void_p]),
+    "vccl_proxy_stats": (ctypes.c_int, [_u64p, _u64p, _u64p, _u64p]),
+    "vccl_device_cu_count": (ctypes.c_int, []),
+}
+
+
+class VcclError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"vccl status {code}: {message}")
+        self.code = code
+        self.message = message
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load libvccl.so (built in-tree by ``paper_2510_00991_amd/build.py``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2510_00991_amd.build` "
+                "(there is no fallback path)")
+        lib = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _check(rv: int) -> int:
+    if rv < 0:
+        raise VcclError(rv, vccl_last_error())
+    return rv
+
+
+def _addr(b) -> int:
+    if b is None:
+        return 0
+    if hasattr(b, "data_ptr"):
+        return int(b.data_ptr())
+    return int(b)
+
+
+def _ptrs(bufs: Sequence):
+    arr = (ctypes.c_void_p * len(bufs))()
+    for i, b in enumerate(bufs):
+        arr[i] = _addr(b)
+    return arr
+
+
+def _u64(a, shape=None) -> np.ndarray:
+    m = np.ascontiguousarray(a, dtype=np.uint64)
+    if shape is not None and m.shape != shape:
+        raise ValueError(f"expected shape {shape}, got {m.shape}")
+    return m
+
+
+def _p64(a: np.ndarray):
+    return a.ctypes.data_as(_u64p)
+
+
+def _stream(s) -> ctypes.c_void_p:
+    return ctypes.c_void_p(int(s) if s else 0)
+
+
+def vccl_last_error() -> str:
+    return load().vccl_last_error().decode("utf-8", "replace")
+
+
+def vccl_init(device: int = 0, max_ranks: int = 64) -> None:
+    _check(load().vccl_init(device, max_ranks))
+
+
+def vccl_finalize() -> None:
+    _check(load().vccl_finalize())
+
+
+def vccl_set_option(key: str, value) -> None:
+    _check(load().vccl_set_option(key.encode(), str(value).encode()))
+
+
+def vccl_get_option(key: str) -> str:
+    buf = ctypes.create_string_buffer(64)
+    _check(load().vccl_get_option(key.encode(), buf, 64))
+    return buf.value.decode()
+
+
+def vccl_device_cu_count() -> int:
+    return _check(load().vccl_device_cu_count())
+
+
+def vccl_sendrecv(sendbuf, sendbytes, send_to, recvbuf, recvbytes, recv_from, P: int, mode: int,
+                  stream=None) -> None:
+    sb, rb = _u64(sendbytes, (P,)), _u64(recvbytes, (P,))
+    st = np.ascontiguousarray(send_to, dtype=np.int32)
+    rf = np.ascontiguousarray(recv_from, dtype=np.int32)
+    if st.shape != (P,) or rf.shape != (P,) or len(sendbuf) != P or len(recvbuf) != P:
+        raise ValueError("per-rank arrays must have P entries")
+    _check(load().vccl_sendrecv(_ptrs(sendbuf), _p64(sb), st.ctypes.data_as(_i32p), _ptrs(recvbuf),
+                                _p64(rb), rf.ctypes.data_as(_i32p), P, mode, _stream(stream)))
+
+
+def vccl_sendrecv_staged_status() -> None:
+    _check(load().vccl_sendrecv_staged_status())
+
+
+def vccl_p2p_reginfo(receiver_rank: int):
+    """(receiverReady, copyStarted, copyDone, receiverRegAddr) of one connection."""
+    a, b, c = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_uint64()
+    p = ctypes.c_void_p()
+    _check(load().vccl_p2p_reginfo(receiver_rank, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
+                                   ctypes.byref(p)))
+    return a.value, b.value, c.value, p.value or 0
+
+
+def vccl_alltoall(sendbuf, recvbuf, bytes_per_peer: int, P: int, mode: int, stream=None) -> None:
+    if len(sendbuf) != P or len(recvbuf) != P:
+        raise ValueError("per-rank arrays must have P entries")
+    _check(load().vccl_alltoall(_ptrs(sendbuf), _ptrs(recvbuf), int(bytes_per_peer), P, mode,
+                                _stream(stream)))
+
+
+def vccl_alltoallv(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P: int, mode: int,
+                   stream=None) -> None:
+    if len(sendbuf) != P or len(recvbuf) != P:
+        raise ValueError("per-rank arrays must have P entries")
+    sc, sd, rc, rd = (_u64(m, (P, P)) for m in (sendcounts, sdispls, recvcounts, rdispls))
+    _check(load().vccl_alltoallv(_ptrs(sendbuf), _p64(sc), _p64(sd), _ptrs(recvbuf), _p64(rc),
+                                 _p64(rd), P, mode, _stream(stream)))
+
+
+def vccl_moe_pack(x, expert_ids, P: int, tokens: int, topk: int, row_bytes: int, num_experts: int,
+                  packed, counts_dev, counts_host=None, bad_ids_dev=None, stream=None) -> None:
+    """counts_dev / bad_ids_dev: device tensors (uint64 [P, E] as int64 storage, uint32 [1]);
+    counts_host: pinned host tensor of the same shape, or None."""
+    if len(x) != P or len(expert_ids) != P or len(packed) != P:
+        raise ValueError("per-rank arrays must have P entries")
+    _check(load().vccl_moe_pack(_ptrs(x), _ptrs(expert_ids), P, tokens, topk, int(row_bytes),
+                                num_experts, _ptrs(packed), ctypes.c_void_p(_addr(counts_dev)),
+                                ctypes.c_void_p(_addr(counts_host)),
+                                ctypes.c_void_p(_addr(bad_ids_dev)), _stream(stream)))
+
+
+def vccl_moe_exchange_layout(counts, P: int, num_experts: int, experts_per_rank: int, row_bytes: int):
+    cnt = _u64(counts, (P, num_experts))
+    out = [np.zeros((P, P), dtype=np.uint64) for _ in range(4)]
+    _check(load().vccl_moe_exchange_layout(_p64(cnt), P, num_experts, experts_per_rank,
+                                           int(row_bytes), *[_p64(o) for o in out]))
+    return {"sendcounts": out[0], "sdispls": out[1], "recvcounts": out[2], "rdispls": out[3]}
+
+
+def vccl_fma_probe(out_dev, workgroups: int, threads: int, iters: int, stream=None) -> None:
+    _check(load().vccl_fma_probe(ctypes.c_void_p(_addr(out_dev)), workgroups, threads, int(iters),
+                                 _stream(stream)))
+
+
+def vccl_proxy_stats():
+    v = [ctypes.c_uint64() for _ in range(4)]
+    _check(load().vccl_proxy_stats(*[ctypes.byref(x) for x in v]))
+    return {"ops": v[0].value, "copies": v[1].value, "bytes": v[2].value, "issue_ns": v[3].value}

@@ -1,0 +1,533 @@
+// The C boundary: argument validation, the host planner that turns count /
+// displacement tables into segment descriptors, and dispatch to the compute-unit
+// or copy-engine path.  Primitive semantics: SendRecv and AlltoAll(v) as the
+// reduction-free P2P primitives of the paper (Section 1, Challenge 1; Section 2.1).
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <memory>
+
+#include "common.h"
+
+namespace vccl {
+
+// ------------------------------------------------------------------ errors ---
+static thread_local std::string tls_error = "";
+
+int fail(int status, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    tls_error = buf;
+    return status;
+}
+const char *last_error_cstr() { return tls_error.c_str(); }
+
+// --------------------------------------------------------- descriptor ring ---
+int DescRing::init(size_t cap) {
+    capacity = cap;
+    for (int i = 0; i < kSlots; ++i) {
+        VCCL_HIP(hipHostMalloc((void **)&slot[i].host, cap * sizeof(Seg), hipHostMallocDefault));
+        VCCL_HIP(hipMalloc((void **)&slot[i].dev, cap * sizeof(Seg)));
+        VCCL_HIP(hipEventCreateWithFlags(&slot[i].done, hipEventDisableTiming));
+        slot[i].used = false;
+    }
+    next = 0;
+    return VCCL_OK;
+}
+
+void DescRing::destroy() {
+    for (int i = 0; i < kSlots; ++i) {
+        if (slot[i].done) {
+            (void)hipEventSynchronize(slot[i].done);
+            (void)hipEventDestroy(slot[i].done);
+        }
+        if (slot[i].host) (void)hipHostFree(slot[i].host);
+        if (slot[i].dev) (void)hipFree(slot[i].dev);
+        slot[i] = DescSlot{};
+    }
+    capacity = 0;
+}
+
+int DescRing::acquire(DescSlot **out) {
+    DescSlot *s;
+    {
+        std::lock_guard<std::mutex> lk(mu);
+        s = &slot[next];
+        next = (next + 1) % kSlots;
+    }
+    // A slot is recycled only after the launch that last read it has finished.
+    if (s->used) VCCL_HIP(hipEventSynchronize(s->done));
+    s->used = true;
+    *out = s;
+    return VCCL_OK;
+}
+
+// ------------------------------------------------------------------ context ---
+struct Context {
+    int device = 0;
+    int max_ranks = 0;
+    int cu_count = 0;
+    Options opt;
+    std::mutex opt_mu;
+    DescRing ring;
+    FifoState fifo;
+    MoeScratch moe;
+    Proxy *proxy = nullptr;
+};
+
+static std::mutex g_mu;
+static std::shared_ptr<Context> g_ctx;
+
+static std::shared_ptr<Context> ctx_get() {
+    std::lock_guard<std::mutex> lk(g_mu);
+    return g_ctx;
+}
+
+static Options options_of(Context &c) {
+    std::lock_guard<std::mutex> lk(c.opt_mu);
+    return c.opt;
+}
+
+// ------------------------------------------------------------------ planner ---
+struct Piece {
+    const uint8_t *src;
+    uint8_t *dst;
+    uint64_t bytes;
+    int receiver;
+};
+
+static bool ranges_overlap(const uint8_t *a, uint64_t an, const uint8_t *b, uint64_t bn) {
+    return an && bn && a < b + bn && b < a + an;
+}
+
+// O(n log n) check that no receive piece overlaps another receive piece or any
+// send piece (undefined behaviour for an exchange; rejected when "check" is on).
+static int check_overlap(const std::vector<Piece> &pieces) {
+    struct R {
+        const uint8_t *p;
+        uint64_t n;
+        bool is_dst;
+    };
+    std::vector<R> rs;
+    rs.reserve(pieces.size() * 2);
+    for (const Piece &pc : pieces) {
+        if (!pc.bytes) continue;
+        rs.push_back(R{pc.src, pc.bytes, false});
+        rs.push_back(R{pc.dst, pc.bytes, true});
+    }
+    std::sort(rs.begin(), rs.end(), [](const R &a, const R &b) { return a.p < b.p; });
+    // sweep: remember the furthest-reaching range so far of each kind
+    const uint8_t *dst_end = nullptr, *src_end = nullptr;
+    for (const R &r : rs) {
+        if (r.is_dst) {
+            if ((dst_end && r.p < dst_end) || (src_end && r.p < src_end))
+                return fail(VCCL_ERR_OVERLAP, "a receive segment at %p (+%llu) overlaps another segment",
+                            (const void *)r.p, (unsigned long long)r.n);
+            if (!dst_end || r.p + r.n > dst_end) dst_end = r.p + r.n;
+        } else {
+            if (dst_end && r.p < dst_end)
+                return fail(VCCL_ERR_OVERLAP, "a send segment at %p (+%llu) overlaps a receive segment",
+                            (const void *)r.p, (unsigned long long)r.n);
+            if (!src_end || r.p + r.n > src_end) src_end = r.p + r.n;
+        }
+    }
+    (void)ranges_overlap;
+    return VCCL_OK;
+}
+
+static int run_pieces(Context &c, std::vector<Piece> &pieces, vccl_mode mode, hipStream_t stream,
+                      const std::vector<std::pair<int, void *>> *receivers) {
+    const Options opt = options_of(c);
+    if (opt.check) {
+        int rv = check_overlap(pieces);
+        if (rv) return rv;
+    }
+    if (mode == VCCL_MODE_CU) {
+        CopyPlan plan;
+        plan.segs.reserve(pieces.size());
+        for (const Piece &pc : pieces)
+            if (pc.bytes) plan.segs.push_back(Seg{pc.src, pc.dst, pc.bytes, 0, 0});
+        int rv = plan_tiles(plan, opt.cu_unroll);
+        if (rv) return rv;
+        return launch_copy(plan, opt, c.cu_count, c.ring, stream);
+    }
+    if (mode == VCCL_MODE_CE) {
+        std::vector<CeCopy> copies;
+        copies.reserve(pieces.size());
+        for (const Piece &pc : pieces)
+            if (pc.bytes) copies.push_back(CeCopy{pc.src, pc.dst, pc.bytes, pc.receiver});
+        if (copies.empty()) return VCCL_OK;
+        return proxy_submit(c.proxy, std::move(copies), opt, stream, receivers);
+    }
+    return fail(VCCL_ERR_ARG, "unknown mode %d", (int)mode);
+}
+
+static int check_common(const std::shared_ptr<Context> &c, int P, const void *a, const void *b) {
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    if (P < 1 || P > c->max_ranks)
+        return fail(VCCL_ERR_ARG, "P = %d is outside 1..max_ranks (%d)", P, c->max_ranks);
+    if (!a || !b) return fail(VCCL_ERR_ARG, "buffer pointer array is NULL");
+    return VCCL_OK;
+}
+
+static int alltoallv_impl(Context &c, void *const *sendbuf, const uint64_t *sendcounts,
+                          const uint64_t *sdispls, void *const *recvbuf, const uint64_t *recvcounts,
+                          const uint64_t *rdispls, int P, vccl_mode mode, hipStream_t stream) {
+    if (mode != VCCL_MODE_CU && mode != VCCL_MODE_CE)
+        return fail(mode == VCCL_MODE_CU_STAGED ? VCCL_ERR_UNSUPPORTED : VCCL_ERR_ARG,
+                    "mode %d is not available for AlltoAll(v)", (int)mode);
+    for (int s = 0; s < P; ++s)
+        for (int r = 0; r < P; ++r)
+            if (sendcounts[(size_t)s * P + r] != recvcounts[(size_t)r * P + s])
+                return fail(VCCL_ERR_COUNT_MISMATCH,
+                            "sendcounts[%d][%d] = %llu but recvcounts[%d][%d] = %llu", s, r,
+                            (unsigned long long)sendcounts[(size_t)s * P + r], r, s,
+                            (unsigned long long)recvcounts[(size_t)r * P + s]);
+    std::vector<Piece> pieces;
+    pieces.reserve((size_t)P * P);
+    // Destination-major with the source rotated by the destination index: at any
+    // moment the segments in flight fan out over all sources and destinations
+    // instead of converging on one receiver (the incast concern of Section 6).
+    for (int k = 0; k < P; ++k) {
+        for (int r = 0; r < P; ++r) {
+            const int s = (r + k) % P;
+            const uint64_t n = recvcounts[(size_t)r * P + s];
+            if (!n) continue;
+            if (!sendbuf[s] || !recvbuf[r])
+                return fail(VCCL_ERR_ARG, "NULL buffer for a non-empty segment %d -> %d", s, r);
+            pieces.push_back(Piece{(const uint8_t *)sendbuf[s] + sdispls[(size_t)s * P + r],
+                                   (uint8_t *)recvbuf[r] + rdispls[(size_t)r * P + s], n, -1});
+        }
+    }
+    return run_pieces(c, pieces, mode, stream, nullptr);
+}
+
+}  // namespace vccl
+
+using namespace vccl;
+
+// ================================================================= C boundary ==
+extern "C" {
+
+const char *vccl_last_error(void) { return last_error_cstr(); }
+
+int vccl_init(int device, int max_ranks) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (g_ctx) return fail(VCCL_ERR_ARG, "vccl_init called twice without vccl_finalize");
+    if (max_ranks < 1 || max_ranks > VCCL_MAX_RANKS)
+        return fail(VCCL_ERR_ARG, "max_ranks = %d is outside 1..%d", max_ranks, VCCL_MAX_RANKS);
+    int ndev = 0;
+    VCCL_HIP(hipGetDeviceCount(&ndev));
+    if (device < 0 || device >= ndev) return fail(VCCL_ERR_ARG, "device %d of %d", device, ndev);
+    VCCL_HIP(hipSetDevice(device));
+    auto c = std::make_shared<Context>();
+    c->device = device;
+    c->max_ranks = max_ranks;
+    VCCL_HIP(hipDeviceGetAttribute(&c->cu_count, hipDeviceAttributeMultiprocessorCount, device));
+    int rv = c->ring.init((size_t)max_ranks * (size_t)max_ranks);
+    if (rv) {
+        c->ring.destroy();
+        return rv;
+    }
+    c->proxy = proxy_create(device, 8);
+    if (!c->proxy) {
+        c->ring.destroy();
+        return fail(VCCL_ERR_HIP, "could not create the copy-engine proxy (streams)");
+    }
+    g_ctx = c;
+    return VCCL_OK;
+}
+
+int vccl_finalize(void) {
+    std::shared_ptr<Context> c;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        c.swap(g_ctx);
+    }
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_finalize without vccl_init");
+    (void)hipSetDevice(c->device);
+    proxy_destroy(c->proxy);
+    c->proxy = nullptr;
+    (void)hipDeviceSynchronize();
+    c->ring.destroy();
+    c->fifo.destroy();
+    c->moe.destroy();
+    return VCCL_OK;
+}
+
+int vccl_device_cu_count(void) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    return c->cu_count;
+}
+
+static bool parse_u64(const char *v, uint64_t *out) {
+    if (!v || !*v) return false;
+    char *end = nullptr;
+    unsigned long long x = strtoull(v, &end, 10);
+    if (*end != '\0' || v[0] == '-') return false;
+    *out = x;
+    return true;
+}
+
+int vccl_set_option(const char *key, const char *value) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    if (!key || !value) return fail(VCCL_ERR_ARG, "NULL option key or value");
+    std::lock_guard<std::mutex> lk(c->opt_mu);
+    Options &o = c->opt;
+    const std::string k(key);
+    if (k == "ce_kind") {
+        if (!strcmp(value, "nocu")) o.ce_kind_nocu = 1;
+        else if (!strcmp(value, "default")) o.ce_kind_nocu = 0;
+        else return fail(VCCL_ERR_ARG, "ce_kind must be 'nocu' or 'default', got '%s'", value);
+        return VCCL_OK;
+    }
+    uint64_t x = 0;
+    if (!parse_u64(value, &x)) return fail(VCCL_ERR_ARG, "option %s: '%s' is not a number", key, value);
+    auto in = [&](uint64_t lo, uint64_t hi) { return x >= lo && x <= hi; };
+    if (k == "cu_unroll") {
+        if (!(x == 1 || x == 2 || x == 4 || x == 8 || x == 16))
+            return fail(VCCL_ERR_ARG, "cu_unroll must be 1, 2, 4, 8 or 16");
+        o.cu_unroll = (int)x;
+    } else if (k == "cu_wg_per_cu") {
+        if (!in(1, 16)) return fail(VCCL_ERR_ARG, "cu_wg_per_cu must be 1..16");
+        o.cu_wg_per_cu = (int)x;
+    } else if (k == "cu_max_wg") {
+        if (!in(0, 1u << 20)) return fail(VCCL_ERR_ARG, "cu_max_wg must be 0..1048576");
+        o.cu_max_wg = (int)x;
+    } else if (k == "cu_nontemporal") {
+        if (!in(0, 1)) return fail(VCCL_ERR_ARG, "cu_nontemporal must be 0 or 1");
+        o.cu_nontemporal = (int)x;
+    } else if (k == "cu_xcd_map") {
+        if (!in(0, 1)) return fail(VCCL_ERR_ARG, "cu_xcd_map must be 0 or 1");
+        o.cu_xcd_map = (int)x;
+    } else if (k == "ce_streams") {
+        if (!in(1, 8)) return fail(VCCL_ERR_ARG, "ce_streams must be 1..8");
+        o.ce_streams = (int)x;
+    } else if (k == "check") {
+        if (!in(0, 1)) return fail(VCCL_ERR_ARG, "check must be 0 or 1");
+        o.check = (int)x;
+    } else if (k == "fifo_chunk_bytes") {
+        if (!in(4096, 64u << 20) || (x & 4095))
+            return fail(VCCL_ERR_ARG, "fifo_chunk_bytes must be a multiple of 4096 in 4 KiB..64 MiB");
+        o.fifo_chunk_bytes = x;
+    } else if (k == "fifo_slots") {
+        if (!in(1, 64)) return fail(VCCL_ERR_ARG, "fifo_slots must be 1..64");
+        o.fifo_slots = (int)x;
+    } else if (k == "fifo_wg_per_conn") {
+        if (!in(1, 64)) return fail(VCCL_ERR_ARG, "fifo_wg_per_conn must be 1..64");
+        o.fifo_wg_per_conn = (int)x;
+    } else if (k == "fifo_spin_limit") {
+        if (!in(1, 1ull << 40)) return fail(VCCL_ERR_ARG, "fifo_spin_limit must be 1..2^40");
+        o.fifo_spin_limit = x;
+    } else {
+        return fail(VCCL_ERR_ARG, "unknown option '%s'", key);
+    }
+    return VCCL_OK;
+}
+
+int vccl_get_option(const char *key, char *out, int cap) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    if (!key || !out || cap < 2) return fail(VCCL_ERR_ARG, "bad arguments to vccl_get_option");
+    const Options o = options_of(*c);
+    const std::string k(key);
+    unsigned long long v;
+    if (k == "ce_kind") {
+        snprintf(out, (size_t)cap, "%s", o.ce_kind_nocu ? "nocu" : "default");
+        return VCCL_OK;
+    } else if (k == "cu_unroll") v = o.cu_unroll;
+    else if (k == "cu_wg_per_cu") v = o.cu_wg_per_cu;
+    else if (k == "cu_max_wg") v = o.cu_max_wg;
+    else if (k == "cu_nontemporal") v = o.cu_nontemporal;
+    else if (k == "cu_xcd_map") v = o.cu_xcd_map;
+    else if (k == "ce_streams") v = o.ce_streams;
+    else if (k == "check") v = o.check;
+    else if (k == "fifo_chunk_bytes") v = o.fifo_chunk_bytes;
+    else if (k == "fifo_slots") v = o.fifo_slots;
+    else if (k == "fifo_wg_per_conn") v = o.fifo_wg_per_conn;
+    else if (k == "fifo_spin_limit") v = o.fifo_spin_limit;
+    else return fail(VCCL_ERR_ARG, "unknown option '%s'", key);
+    snprintf(out, (size_t)cap, "%llu", v);
+    return VCCL_OK;
+}
+
+int vccl_alltoallv(void *const *sendbuf, const uint64_t *sendcounts, const uint64_t *sdispls,
+                   void *const *recvbuf, const uint64_t *recvcounts, const uint64_t *rdispls, int P,
+                   vccl_mode mode, void *stream) {
+    auto c = ctx_get();
+    int rv = check_common(c, P, sendbuf, recvbuf);
+    if (rv) return rv;
+    if (!sendcounts || !sdispls || !recvcounts || !rdispls)
+        return fail(VCCL_ERR_ARG, "count or displacement table is NULL");
+    return alltoallv_impl(*c, sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, mode,
+                          (hipStream_t)stream);
+}
+
+int vccl_alltoall(void *const *sendbuf, void *const *recvbuf, uint64_t bytes_per_peer, int P,
+                  vccl_mode mode, void *stream) {
+    auto c = ctx_get();
+    int rv = check_common(c, P, sendbuf, recvbuf);
+    if (rv) return rv;
+    std::vector<uint64_t> cnt((size_t)P * P, bytes_per_peer), dsp((size_t)P * P);
+    for (int a = 0; a < P; ++a)
+        for (int b = 0; b < P; ++b) dsp[(size_t)a * P + b] = (uint64_t)b * bytes_per_peer;
+    return alltoallv_impl(*c, sendbuf, cnt.data(), dsp.data(), recvbuf, cnt.data(), dsp.data(), P,
+                          mode, (hipStream_t)stream);
+}
+
+int vccl_sendrecv(void *const *sendbuf, const uint64_t *sendbytes, const int *send_to,
+                  void *const *recvbuf, const uint64_t *recvbytes, const int *recv_from, int P,
+                  vccl_mode mode, void *stream) {
+    auto c = ctx_get();
+    int rv = check_common(c, P, sendbuf, recvbuf);
+    if (rv) return rv;
+    if (!sendbytes || !send_to || !recvbytes || !recv_from)
+        return fail(VCCL_ERR_ARG, "size or peer table is NULL");
+    if (mode != VCCL_MODE_CU && mode != VCCL_MODE_CE && mode != VCCL_MODE_CU_STAGED)
+        return fail(VCCL_ERR_ARG, "unknown mode %d", (int)mode);
+    for (int s = 0; s < P; ++s) {
+        const int r = send_to[s];
+        if (r < 0 || r >= P) return fail(VCCL_ERR_ARG, "send_to[%d] = %d is not a rank", s, r);
+        if (recv_from[r] != s)
+            return fail(VCCL_ERR_ARG, "recv_from[%d] = %d does not invert send_to[%d] = %d", r,
+                        recv_from[r], s, r);
+        if (sendbytes[s] != recvbytes[r])
+            return fail(VCCL_ERR_COUNT_MISMATCH, "rank %d sends %llu bytes but rank %d expects %llu",
+                        s, (unsigned long long)sendbytes[s], r, (unsigned long long)recvbytes[r]);
+        if (sendbytes[s] && (!sendbuf[s] || !recvbuf[r]))
+            return fail(VCCL_ERR_ARG, "NULL buffer on connection %d -> %d", s, r);
+    }
+    if (mode == VCCL_MODE_CU_STAGED) {
+        const Options opt = options_of(*c);
+        std::vector<FifoConn> conns;
+        std::vector<Piece> pieces;
+        for (int s = 0; s < P; ++s) {
+            if (!sendbytes[s]) continue;
+            conns.push_back(FifoConn{(const uint8_t *)sendbuf[s], (uint8_t *)recvbuf[send_to[s]],
+                                     sendbytes[s]});
+            pieces.push_back(Piece{conns.back().src, conns.back().dst, sendbytes[s], -1});
+        }
+        if (opt.check) {
+            rv = check_overlap(pieces);
+            if (rv) return rv;
+        }
+        if (conns.empty()) return VCCL_OK;
+        return launch_fifo(c->fifo, conns, opt, c->cu_count, (hipStream_t)stream);
+    }
+    std::vector<Piece> pieces;
+    std::vector<std::pair<int, void *>> receivers;
+    for (int s = 0; s < P; ++s) {
+        if (!sendbytes[s]) continue;
+        const int r = send_to[s];
+        pieces.push_back(Piece{(const uint8_t *)sendbuf[s], (uint8_t *)recvbuf[r], sendbytes[s],
+                               mode == VCCL_MODE_CE ? r : -1});
+        if (mode == VCCL_MODE_CE) receivers.emplace_back(r, recvbuf[r]);
+    }
+    return run_pieces(*c, pieces, mode, (hipStream_t)stream,
+                      mode == VCCL_MODE_CE ? &receivers : nullptr);
+}
+
+int vccl_moe_pack(const void *const *x, const int32_t *const *expert_ids, int P, int tokens, int topk,
+                  uint64_t row_bytes, int num_experts, void *const *packed, uint64_t *counts_dev,
+                  uint64_t *counts_host, uint32_t *bad_ids_dev, void *stream) {
+    auto c = ctx_get();
+    int rv = check_common(c, P, x, packed);
+    if (rv) return rv;
+    if (!expert_ids || !counts_dev) return fail(VCCL_ERR_ARG, "expert_ids or counts_dev is NULL");
+    if (tokens < 0 || topk < 1 || topk > 64)
+        return fail(VCCL_ERR_ARG, "tokens = %d, topk = %d (topk must be 1..64)", tokens, topk);
+    if (num_experts < 1 || num_experts > 1024)
+        return fail(VCCL_ERR_ARG, "num_experts = %d is outside 1..1024", num_experts);
+    if (row_bytes == 0 || (row_bytes & 15u))
+        return fail(VCCL_ERR_ARG, "row_bytes = %llu must be a positive multiple of 16",
+                    (unsigned long long)row_bytes);
+    if ((uint64_t)tokens * (uint64_t)topk > 0x7fffffffull)
+        return fail(VCCL_ERR_UNSUPPORTED, "more than 2^31 (token, slot) pairs per rank");
+    for (int s = 0; s < P; ++s) {
+        if (tokens && (!x[s] || !expert_ids[s] || !packed[s]))
+            return fail(VCCL_ERR_ARG, "NULL buffer for rank %d", s);
+        if ((reinterpret_cast<uintptr_t>(x[s]) | reinterpret_cast<uintptr_t>(packed[s])) & 15u)
+            return fail(VCCL_ERR_ARG, "x / packed of rank %d are not 16-byte aligned", s);
+    }
+    return launch_moe_pack(c->moe, x, expert_ids, P, tokens, topk, row_bytes, num_experts, packed,
+                           counts_dev, counts_host, bad_ids_dev, (hipStream_t)stream);
+}
+
+int vccl_moe_exchange_layout(const uint64_t *counts, int P, int num_experts, int experts_per_rank,
+                             uint64_t row_bytes, uint64_t *sendcounts, uint64_t *sdispls,
+                             uint64_t *recvcounts, uint64_t *rdispls) {
+    if (!counts || !sendcounts || !sdispls || !recvcounts || !rdispls)
+        return fail(VCCL_ERR_ARG, "NULL table");
+    if (P < 1 || experts_per_rank < 1 || (int64_t)P * experts_per_rank != num_experts)
+        return fail(VCCL_ERR_ARG, "num_experts (%d) must equal P (%d) x experts_per_rank (%d)",
+                    num_experts, P, experts_per_rank);
+    // Rows of one source rank are already grouped by destination, so the send
+    // displacements are a running sum along the row of the rank-to-rank matrix.
+    std::vector<uint64_t> rows((size_t)P * P, 0);
+    for (int s = 0; s < P; ++s) {
+        const uint64_t *cs = counts + (size_t)s * num_experts;
+        uint64_t run = 0;
+        for (int r = 0; r < P; ++r) {
+            uint64_t n = 0;
+            for (int j = 0; j < experts_per_rank; ++j) n += cs[(size_t)r * experts_per_rank + j];
+            rows[(size_t)s * P + r] = n;
+            sendcounts[(size_t)s * P + r] = n * row_bytes;
+            sdispls[(size_t)s * P + r] = run;
+            run += n * row_bytes;
+        }
+    }
+    // A receiver lays incoming segments out in source-rank order.
+    for (int r = 0; r < P; ++r) {
+        uint64_t run = 0;
+        for (int s = 0; s < P; ++s) {
+            const uint64_t b = rows[(size_t)s * P + r] * row_bytes;
+            recvcounts[(size_t)r * P + s] = b;
+            rdispls[(size_t)r * P + s] = run;
+            run += b;
+        }
+    }
+    return VCCL_OK;
+}
+
+int vccl_fma_probe(float *out_dev, uint32_t workgroups, uint32_t threads, uint64_t iters, void *stream) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    if (!out_dev) return fail(VCCL_ERR_ARG, "out_dev is NULL");
+    if (threads == 0 || threads > 1024 || (threads & 63u))
+        return fail(VCCL_ERR_ARG, "threads = %u must be a multiple of 64 up to 1024", threads);
+    if (workgroups == 0) workgroups = (uint32_t)c->cu_count;
+    if (workgroups > (1u << 20)) return fail(VCCL_ERR_ARG, "workgroups = %u is too large", workgroups);
+    return launch_fma_probe(out_dev, workgroups, threads, iters, (hipStream_t)stream);
+}
+
+int vccl_sendrecv_staged_status(void) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    uint32_t st = 0;
+    int rv = fifo_last_status(c->fifo, &st);
+    if (rv) return rv;
+    if (st) return fail(VCCL_ERR_TIMEOUT, "a staged SendRecv wait exceeded fifo_spin_limit polls");
+    return VCCL_OK;
+}
+
+int vccl_proxy_stats(uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t *issue_ns) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    proxy_stats(c->proxy, ops, copies, bytes, issue_ns);
+    return VCCL_OK;
+}
+
+int vccl_p2p_reginfo(int receiver_rank, uint64_t *receiver_ready, uint64_t *copy_started,
+                     uint64_t *copy_done, void **receiver_reg_addr) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    return proxy_reginfo(c->proxy, receiver_rank, receiver_ready, copy_started, copy_done,
+                         receiver_reg_addr);
+}
+
+}  // extern "C"

@@ -1,0 +1,161 @@
+// Internal declarations shared by the translation units of libvccl.
+// Nothing here is part of the public boundary (that is include/vccl.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <mutex>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "vccl.h"
+
+namespace vccl {
+
+// One contiguous piece of an exchange: `bytes` bytes from src to dst.
+// tile_begin is the index of the segment's first tile in the launch-wide tile
+// numbering; head is the number of leading bytes copied bytewise so that the
+// vector body starts at a 16-byte aligned destination.
+struct Seg {
+    const uint8_t *src;
+    uint8_t *dst;
+    uint64_t bytes;
+    uint32_t tile_begin;
+    uint32_t head;
+};
+static_assert(sizeof(Seg) == 32, "descriptor layout");
+
+constexpr int kInlineSegs = 64;     // descriptors carried in the kernel arguments
+constexpr int kCopyThreads = 256;   // 4 wavefronts per workgroup
+
+struct Options {
+    int cu_unroll = 8;
+    int cu_wg_per_cu = 8;
+    int cu_max_wg = 0;
+    int cu_nontemporal = 1;
+    int cu_xcd_map = 0;
+    int ce_streams = 4;
+    int ce_kind_nocu = 1;
+    int check = 0;
+    uint64_t fifo_chunk_bytes = 512u << 10;
+    int fifo_slots = 8;
+    int fifo_wg_per_conn = 16;
+    uint64_t fifo_spin_limit = 1ull << 24;
+};
+
+// thread-local error message + status helper
+int fail(int status, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+const char *last_error_cstr();
+
+#define VCCL_HIP(expr)                                                                       \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return ::vccl::fail(VCCL_ERR_HIP, "%s failed: %s (%s:%d)", #expr,                \
+                                hipGetErrorString(e_), __FILE__, __LINE__);                  \
+    } while (0)
+
+// ---- descriptor staging ring (host pinned + device), one slot per in-flight launch
+struct DescSlot {
+    Seg *host = nullptr;
+    Seg *dev = nullptr;
+    hipEvent_t done = nullptr;
+    bool used = false;
+};
+
+struct DescRing {
+    static constexpr int kSlots = 8;
+    DescSlot slot[kSlots];
+    size_t capacity = 0;   // descriptors per slot
+    int next = 0;
+    std::mutex mu;
+    int init(size_t cap);
+    void destroy();
+    // Blocks until the slot's previous launch has finished on the device.
+    int acquire(DescSlot **out);
+};
+
+// ---- CU copy path
+struct CopyPlan {
+    std::vector<Seg> segs;       // non-empty segments only, tile_begin / head filled in
+    uint32_t total_tiles = 0;
+    uint32_t uniform_tiles = 0;  // > 0: every segment has exactly this many tiles
+    uint64_t bytes = 0;
+};
+// Fills tile_begin/head for plan.segs (src, dst, bytes already set).
+int plan_tiles(CopyPlan &plan, int unroll);
+int launch_copy(const CopyPlan &plan, const Options &opt, int cu_count, DescRing &ring,
+                hipStream_t stream);
+
+// ---- staged FIFO SendRecv (CU_STAGED)
+struct FifoState {
+    uint8_t *slots = nullptr;        // connections x fifo_slots x chunk bytes
+    uint64_t *counters = nullptr;    // per (connection, lane-group): head, tail
+    uint32_t *status = nullptr;      // device word: non-zero when a bounded wait gave up
+    uint32_t *status_host = nullptr; // pinned mirror read after the stream is synchronised
+    struct FifoConn *conns_dev = nullptr;
+    struct FifoConn *conns_host = nullptr;
+    hipEvent_t done = nullptr;       // recorded behind the last staged operation
+    size_t slots_bytes = 0;
+    size_t counters_n = 0;
+    size_t conns_n = 0;
+    std::mutex mu;
+    void destroy();
+};
+struct FifoConn {
+    const uint8_t *src;
+    uint8_t *dst;
+    uint64_t bytes;
+};
+// Waits for the last staged operation and reports whether a bounded wait gave up.
+int fifo_last_status(FifoState &st, uint32_t *out);
+int launch_fifo(FifoState &st, const std::vector<FifoConn> &conns, const Options &opt,
+                int cu_count, hipStream_t stream);
+
+// ---- MoE pack
+struct MoeScratch {
+    uint32_t *hist = nullptr;    // [P][blocks][E] per-block histograms, then offsets
+    size_t hist_n = 0;
+    void **ptrs = nullptr;       // device copies of the x / ids / packed pointer arrays
+    void **ptrs_host = nullptr;  // pinned staging for them
+    hipEvent_t done = nullptr;
+    size_t ptrs_n = 0;
+    std::mutex mu;
+    void destroy();
+};
+int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P,
+                    int tokens, int topk, uint64_t row_bytes, int num_experts,
+                    void *const *packed, uint64_t *counts_dev, uint64_t *counts_host,
+                    uint32_t *bad_ids_dev, hipStream_t stream);
+
+// ---- co-run probe
+int launch_fma_probe(float *out, uint32_t workgroups, uint32_t threads, uint64_t iters,
+                     hipStream_t stream);
+
+// ---- copy-engine proxy
+struct CeCopy {
+    const void *src;
+    void *dst;
+    uint64_t bytes;
+    int receiver;  // >= 0: SendRecv copy whose destination is read from that rank's handshake record
+};
+class Proxy;
+Proxy *proxy_create(int device, int max_streams);
+void proxy_destroy(Proxy *p);
+// Orders the copies after everything already on `stream`, has the proxy thread
+// issue them on the internal copy streams, and makes `stream` wait for them.
+// `receivers` (may be null) lists (receiving rank, application buffer) pairs that
+// go through the per-connection handshake record.
+int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hipStream_t stream,
+                 const std::vector<std::pair<int, void *>> *receivers);
+int proxy_reginfo(Proxy *p, int receiver, uint64_t *ready, uint64_t *started, uint64_t *done,
+                  void **addr);
+int proxy_drain(Proxy *p);
+void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t *issue_ns);
+
+}  // namespace vccl

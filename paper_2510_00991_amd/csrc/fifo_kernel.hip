@@ -1,0 +1,221 @@
+// Staged SendRecv on compute units: the two-step intra-node pattern of a
+// kernel-driven library (paper Section 2.2): sender workgroups copy the
+// application buffer chunk by chunk into a chunk FIFO, receiver workgroups copy
+// each chunk out into the destination as it arrives.  It exists as the baseline
+// the zero-copy and copy-engine paths are compared with; it moves every byte
+// twice and holds compute units for the whole transfer.
+//
+// Each connection is served by W independent sender/receiver workgroup pairs.
+// Pair j owns slice j of every chunk and its own head/tail counters, so every
+// counter has exactly one writer and one reader.  Chunk k lives in slot
+// k mod slots; the sender waits while head - tail == slots, the receiver while
+// tail == head.  Every wait is bounded: after spin_limit polls the workgroup
+// raises the status word and leaves, so the grid always drains.
+#include "common.h"
+
+namespace vccl {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kFifoThreads = 256;
+
+struct FifoArgs {
+    const FifoConn *conns;   // device array
+    uint8_t *slots;          // [conn][slot][chunk_bytes]
+    uint64_t *counters;      // [conn][W][2]: head, tail
+    uint32_t *status;
+    uint64_t chunk_bytes;
+    uint64_t spin_limit;
+    uint32_t nslots;
+    uint32_t W;
+};
+
+__global__ void fifo_reset_kernel(uint64_t *counters, uint32_t n, uint32_t *status) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) counters[i] = 0;
+    if (i == 0) *status = 0;
+}
+
+// Copy [a, b) of a chunk; `from`/`to` are the chunk bases.  Vector path when both
+// sides are 16-byte aligned at `a`, bytewise otherwise.
+__device__ __forceinline__ void copy_range(const uint8_t *from, uint8_t *to, uint64_t a, uint64_t b) {
+    const uint8_t *s = from + a;
+    uint8_t *d = to + a;
+    const uint64_t n = b - a;
+    if (((reinterpret_cast<uintptr_t>(s) | reinterpret_cast<uintptr_t>(d)) & 15u) == 0) {
+        const uint64_t nv = n >> 4;
+        const u32x4 *sv = reinterpret_cast<const u32x4 *>(s);
+        u32x4 *dv = reinterpret_cast<u32x4 *>(d);
+        uint64_t i = threadIdx.x;
+        for (; i + 3 * kFifoThreads < nv; i += 4 * kFifoThreads) {
+            const u32x4 r0 = sv[i], r1 = sv[i + kFifoThreads], r2 = sv[i + 2 * kFifoThreads],
+                        r3 = sv[i + 3 * kFifoThreads];
+            dv[i] = r0;
+            dv[i + kFifoThreads] = r1;
+            dv[i + 2 * kFifoThreads] = r2;
+            dv[i + 3 * kFifoThreads] = r3;
+        }
+        for (; i < nv; i += kFifoThreads) dv[i] = sv[i];
+        for (uint64_t t = (nv << 4) + threadIdx.x; t < n; t += kFifoThreads) d[t] = s[t];
+    } else {
+        for (uint64_t t = threadIdx.x; t < n; t += kFifoThreads) d[t] = s[t];
+    }
+}
+
+__global__ __launch_bounds__(kFifoThreads) void fifo_sendrecv_kernel(FifoArgs a) {
+    __shared__ int give_up;
+    // sender and receiver of a pair sit next to each other in the launch order
+    const uint32_t side = blockIdx.x & 1u;
+    const uint32_t pair = blockIdx.x >> 1;
+    const uint32_t conn = pair / a.W, j = pair - conn * a.W;
+    const FifoConn c = a.conns[conn];
+    uint64_t *head = a.counters + ((size_t)conn * a.W + j) * 2;
+    uint64_t *tail = head + 1;
+    uint8_t *fifo = a.slots + (size_t)conn * a.nslots * a.chunk_bytes;
+    const uint64_t nchunks = (c.bytes + a.chunk_bytes - 1) / a.chunk_bytes;
+    // slice j of a chunk, on 16-byte boundaries of the chunk
+    const uint64_t cv = a.chunk_bytes >> 4;
+    const uint64_t lo = (cv * j / a.W) << 4, hi = (cv * (j + 1) / a.W) << 4;
+    if (threadIdx.x == 0) give_up = 0;
+    __syncthreads();
+    for (uint64_t k = 0; k < nchunks; ++k) {
+        const uint64_t off = k * a.chunk_bytes;
+        const uint64_t len = min(a.chunk_bytes, c.bytes - off);
+        const uint64_t b0 = min(lo, len), b1 = min(hi, len);
+        uint8_t *slot = fifo + (k % a.nslots) * a.chunk_bytes;
+        if (threadIdx.x == 0) {
+            uint64_t polls = 0;
+            if (side == 0) {
+                while (k - __hip_atomic_load(tail, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= a.nslots) {
+                    if (++polls > a.spin_limit || __hip_atomic_load(a.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+                        give_up = 1;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(8);
+                }
+            } else {
+                while (__hip_atomic_load(head, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) <= k) {
+                    if (++polls > a.spin_limit || __hip_atomic_load(a.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+                        give_up = 1;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(8);
+                }
+            }
+        }
+        __syncthreads();
+        if (give_up) {
+            if (threadIdx.x == 0) __hip_atomic_store(a.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+        __threadfence();   // what the other side wrote before publishing is visible now
+        if (side == 0) copy_range(c.src + off, slot, b0, b1);
+        else copy_range(slot, c.dst + off, b0, b1);
+        __threadfence();   // this lane's stores are out before the counter moves
+        __syncthreads();
+        if (threadIdx.x == 0)
+            __hip_atomic_store(side == 0 ? head : tail, k + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+void FifoState::destroy() {
+    if (slots) (void)hipFree(slots);
+    if (counters) (void)hipFree(counters);
+    if (status) (void)hipFree(status);
+    if (status_host) (void)hipHostFree(status_host);
+    if (conns_dev) (void)hipFree(conns_dev);
+    if (conns_host) (void)hipHostFree(conns_host);
+    if (done) {
+        (void)hipEventDestroy(done);
+        done = nullptr;
+    }
+    slots = nullptr;
+    counters = nullptr;
+    status = nullptr;
+    status_host = nullptr;
+    conns_dev = nullptr;
+    conns_host = nullptr;
+    slots_bytes = counters_n = conns_n = 0;
+}
+
+int launch_fifo(FifoState &st, const std::vector<FifoConn> &conns, const Options &opt, int cu_count,
+                hipStream_t stream) {
+    const size_t nconn = conns.size();
+    // Both sides of every pair must be able to be resident together; keep the grid
+    // well inside what the device holds at once.
+    uint32_t W = (uint32_t)opt.fifo_wg_per_conn;
+    const uint64_t max_wg = (uint64_t)cu_count * 2;
+    while (W > 1 && 2ull * W * nconn > max_wg) W >>= 1;
+    if (2ull * W * nconn > (uint64_t)cu_count * 8)
+        return fail(VCCL_ERR_UNSUPPORTED, "%zu connections need more co-resident workgroups than the device holds",
+                    nconn);
+    const uint64_t cv = opt.fifo_chunk_bytes >> 4;
+    if (cv < W) W = (uint32_t)cv;
+    const size_t slots_bytes = nconn * (size_t)opt.fifo_slots * opt.fifo_chunk_bytes;
+    const size_t counters_n = nconn * W * 2;
+
+    std::lock_guard<std::mutex> lk(st.mu);
+    if (!st.done) VCCL_HIP(hipEventCreateWithFlags(&st.done, hipEventDisableTiming));
+    // One staged operation at a time owns the FIFO memory and the pinned staging.
+    VCCL_HIP(hipEventSynchronize(st.done));
+    if (st.status_host && *st.status_host) {
+        *st.status_host = 0;   // a previous operation gave up; it was reported then
+    }
+    if (!st.status) {
+        VCCL_HIP(hipMalloc((void **)&st.status, sizeof(uint32_t)));
+        VCCL_HIP(hipHostMalloc((void **)&st.status_host, sizeof(uint32_t), hipHostMallocDefault));
+        *st.status_host = 0;
+    }
+    if (slots_bytes > st.slots_bytes) {   // the FIFO is allocated on first use and grown on demand
+        if (st.slots) VCCL_HIP(hipFree(st.slots));
+        st.slots = nullptr;
+        st.slots_bytes = 0;
+        VCCL_HIP(hipMalloc((void **)&st.slots, slots_bytes));
+        st.slots_bytes = slots_bytes;
+    }
+    if (counters_n > st.counters_n) {
+        if (st.counters) VCCL_HIP(hipFree(st.counters));
+        st.counters = nullptr;
+        st.counters_n = 0;
+        VCCL_HIP(hipMalloc((void **)&st.counters, counters_n * sizeof(uint64_t)));
+        st.counters_n = counters_n;
+    }
+    if (nconn > st.conns_n) {
+        if (st.conns_dev) VCCL_HIP(hipFree(st.conns_dev));
+        if (st.conns_host) VCCL_HIP(hipHostFree(st.conns_host));
+        st.conns_dev = nullptr;
+        st.conns_host = nullptr;
+        st.conns_n = 0;
+        VCCL_HIP(hipMalloc((void **)&st.conns_dev, nconn * sizeof(FifoConn)));
+        VCCL_HIP(hipHostMalloc((void **)&st.conns_host, nconn * sizeof(FifoConn), hipHostMallocDefault));
+        st.conns_n = nconn;
+    }
+    for (size_t i = 0; i < nconn; ++i) st.conns_host[i] = conns[i];
+    VCCL_HIP(hipMemcpyAsync(st.conns_dev, st.conns_host, nconn * sizeof(FifoConn), hipMemcpyHostToDevice,
+                            stream));
+    fifo_reset_kernel<<<dim3((uint32_t)((counters_n + 255) / 256)), dim3(256), 0, stream>>>(
+        st.counters, (uint32_t)counters_n, st.status);
+    VCCL_HIP(hipGetLastError());
+    FifoArgs a;
+    a.conns = st.conns_dev;
+    a.slots = st.slots;
+    a.counters = st.counters;
+    a.status = st.status;
+    a.chunk_bytes = opt.fifo_chunk_bytes;
+    a.spin_limit = opt.fifo_spin_limit;
+    a.nslots = (uint32_t)opt.fifo_slots;
+    a.W = W;
+    fifo_sendrecv_kernel<<<dim3((uint32_t)(2 * W * nconn)), dim3(kFifoThreads), 0, stream>>>(a);
+    VCCL_HIP(hipGetLastError());
+    VCCL_HIP(hipMemcpyAsync(st.status_host, st.status, sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
+    VCCL_HIP(hipEventRecord(st.done, stream));
+    return VCCL_OK;
+}
+
+int fifo_last_status(FifoState &st, uint32_t *out) {
+    std::lock_guard<std::mutex> lk(st.mu);
+    if (st.done) VCCL_HIP(hipEventSynchronize(st.done));
+    *out = st.status_host ? *st.status_host : 0u;
+    return VCCL_OK;
+}
+
+}  // namespace vccl

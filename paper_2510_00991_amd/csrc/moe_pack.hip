@@ -1,0 +1,256 @@
+// MoE dispatch pack: make the rows bound for each destination rank contiguous
+// before the AlltoAllv (token routing by AlltoAll, paper Section 2.1; dispatch
+// phase, Section 6).  The (token, slot) pairs of a rank, in order p = t*K + k,
+// are stably sorted by expert id; row j of the packed buffer is the row of the
+// token of the j-th pair.  Stability makes the result unique, so it can be
+// compared bit for bit.
+//
+// Four launches, all ranks at once (blockIdx.y = rank):
+//   1 histogram   per-block expert counts (LDS atomics; counts do not depend on order)
+//   2 scan        per expert: exclusive sum over blocks; across experts: exclusive
+//                 sum with a wavefront shuffle scan  -> first row of (block, expert)
+//   3 rank        wavefront ballot matching gives each pair its stable position
+//   4 gather      one wavefront per token reads the row once into registers and
+//                 stores it to its K destinations (16 bytes per lane per access)
+#include "common.h"
+
+namespace vccl {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kPairsPerBlock = 2048;
+constexpr int kMoeThreads = 256;
+constexpr uint32_t kDropped = 0xffffffffu;
+constexpr int kMaxExperts = 1024;
+
+struct MoePtrs {       // device arrays of P pointers each, in one allocation
+    const uint8_t *const *x;
+    const int32_t *const *ids;
+    uint8_t *const *packed;
+};
+
+__global__ __launch_bounds__(kMoeThreads) void moe_hist_kernel(MoePtrs ptrs, uint32_t npairs, int E,
+                                                               uint32_t nblk, uint32_t *hist,
+                                                               uint32_t *bad_ids) {
+    __shared__ uint32_t h[kMaxExperts];
+    const uint32_t rank = blockIdx.y, b = blockIdx.x;
+    for (int e = threadIdx.x; e < E; e += kMoeThreads) h[e] = 0;
+    __syncthreads();
+    const int32_t *ids = ptrs.ids[rank];
+    const uint32_t p0 = b * kPairsPerBlock;
+    const uint32_t p1 = min(npairs, p0 + kPairsPerBlock);
+    uint32_t bad = 0;
+    for (uint32_t p = p0 + threadIdx.x; p < p1; p += kMoeThreads) {
+        const int32_t e = ids[p];
+        if (e >= 0 && e < E) atomicAdd(&h[e], 1u);
+        else ++bad;
+    }
+    if (bad && bad_ids) atomicAdd(bad_ids, bad);
+    __syncthreads();
+    uint32_t *out = hist + ((size_t)rank * nblk + b) * (size_t)E;
+    for (int e = threadIdx.x; e < E; e += kMoeThreads) out[e] = h[e];
+}
+
+// Inclusive scan across the 64 lanes of a wavefront.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, uint32_t lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(v, d, 64);
+        if (lane >= (uint32_t)d) v += o;
+    }
+    return v;
+}
+
+__global__ __launch_bounds__(kMoeThreads) void moe_scan_kernel(int E, uint32_t nblk, uint32_t *hist,
+                                                               uint64_t *counts) {
+    __shared__ uint32_t wave_tot[kMoeThreads / 64];
+    const uint32_t rank = blockIdx.x;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    uint32_t *hr = hist + (size_t)rank * nblk * (size_t)E;
+    const int per = (E + kMoeThreads - 1) / kMoeThreads;   // consecutive experts per thread
+    const int e0 = (int)tid * per;
+    uint32_t tot[kMaxExperts / kMoeThreads];
+    uint32_t mine = 0;
+    for (int j = 0; j < per; ++j) {
+        const int e = e0 + j;
+        uint32_t run = 0;
+        if (e < E) {
+            for (uint32_t b = 0; b < nblk; ++b) {   // exclusive sum over blocks, in place
+                const uint32_t c = hr[(size_t)b * E + e];
+                hr[(size_t)b * E + e] = run;
+                run += c;
+            }
+            counts[(size_t)rank * E + e] = run;
+        }
+        tot[j] = run;
+        mine += run;
+    }
+    const uint32_t incl = wave_inclusive_scan(mine, lane);
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t base = incl - mine;
+    for (uint32_t w = 0; w < wave; ++w) base += wave_tot[w];
+    for (int j = 0; j < per; ++j) {
+        const int e = e0 + j;
+        if (e < E)
+            for (uint32_t b = 0; b < nblk; ++b) hr[(size_t)b * E + e] += base;
+        base += tot[j];
+    }
+}
+
+__global__ __launch_bounds__(kMoeThreads) void moe_rank_kernel(MoePtrs ptrs, uint32_t npairs, int E,
+                                                               int ebits, uint32_t nblk,
+                                                               const uint32_t *hist, uint32_t *dest) {
+    __shared__ uint32_t next_row[kMaxExperts];
+    const uint32_t rank = blockIdx.y, b = blockIdx.x;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t *off = hist + ((size_t)rank * nblk + b) * (size_t)E;
+    for (int e = tid; e < E; e += kMoeThreads) next_row[e] = off[e];
+    __syncthreads();
+    const int32_t *ids = ptrs.ids[rank];
+    uint32_t *drow = dest + (size_t)rank * npairs;
+    const uint32_t p0 = b * kPairsPerBlock;
+    const uint32_t p1 = min(npairs, p0 + kPairsPerBlock);
+    const uint64_t lower_lanes = (1ull << lane) - 1ull;
+    for (uint32_t base = p0; base < p1; base += kMoeThreads) {   // uniform trip count
+        const uint32_t p = base + tid;
+        const bool live = p < p1;
+        const int32_t e = live ? ids[p] : -1;
+        const bool ok = live && e >= 0 && e < E;
+        // lanes of this wavefront that hold the same expert id
+        uint64_t peers = __ballot(ok);
+        for (int bit = 0; bit < ebits; ++bit) {
+            const bool one = ((uint32_t)e >> bit) & 1u;
+            const uint64_t m = __ballot(ok && one);
+            peers &= one ? m : ~m;
+        }
+        const uint32_t before = (uint32_t)__popcll(peers & lower_lanes);
+        const uint32_t group = (uint32_t)__popcll(peers);
+        // the four wavefronts take their turn in pair order, which keeps the sort stable
+        for (uint32_t w = 0; w < kMoeThreads / 64; ++w) {
+            if (wave == w && ok) {
+                const uint32_t start = next_row[e];
+                drow[p] = start + before;
+                if (before + 1 == group) next_row[e] = start + group;   // last peer advances
+            }
+            __syncthreads();
+        }
+        if (live && !ok) drow[p] = kDropped;
+    }
+}
+
+constexpr int kRowVecs = 8;   // 16-byte vectors a lane holds per pass over a row
+
+__global__ __launch_bounds__(kMoeThreads) void moe_gather_kernel(MoePtrs ptrs, uint32_t tokens, int K,
+                                                                 uint32_t row_vecs,
+                                                                 const uint32_t *dest, uint32_t npairs) {
+    const uint32_t rank = blockIdx.y;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t t = blockIdx.x * (kMoeThreads / 64) + (threadIdx.x >> 6);
+    if (t >= tokens) return;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(ptrs.x[rank]) + (size_t)t * row_vecs;
+    u32x4 *out = reinterpret_cast<u32x4 *>(ptrs.packed[rank]);
+    const uint32_t *d = dest + (size_t)rank * npairs + (size_t)t * K;
+    for (uint32_t v0 = 0; v0 < row_vecs; v0 += 64u * kRowVecs) {
+        u32x4 r[kRowVecs];
+#pragma unroll
+        for (int u = 0; u < kRowVecs; ++u) {
+            const uint32_t v = v0 + u * 64u + lane;
+            if (v < row_vecs) r[u] = __builtin_nontemporal_load(row + v);
+        }
+        for (int k = 0; k < K; ++k) {
+            const uint32_t j = d[k];
+            if (j == kDropped) continue;
+            u32x4 *o = out + (size_t)j * row_vecs;
+#pragma unroll
+            for (int u = 0; u < kRowVecs; ++u) {
+                const uint32_t v = v0 + u * 64u + lane;
+                if (v < row_vecs) __builtin_nontemporal_store(r[u], o + v);
+            }
+        }
+    }
+}
+
+void MoeScratch::destroy() {
+    if (done) {
+        (void)hipEventSynchronize(done);
+        (void)hipEventDestroy(done);
+        done = nullptr;
+    }
+    if (hist) (void)hipFree(hist);
+    if (ptrs) (void)hipFree(ptrs);
+    if (ptrs_host) (void)hipHostFree(ptrs_host);
+    hist = nullptr;
+    ptrs = nullptr;
+    ptrs_host = nullptr;
+    hist_n = ptrs_n = 0;
+}
+
+int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P, int tokens,
+                    int topk, uint64_t row_bytes, int num_experts, void *const *packed,
+                    uint64_t *counts_dev, uint64_t *counts_host, uint32_t *bad_ids_dev,
+                    hipStream_t stream) {
+    const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
+    const uint32_t nblk = npairs ? (npairs + kPairsPerBlock - 1) / kPairsPerBlock : 1;
+    const size_t hist_n = (size_t)P * nblk * (size_t)num_experts;
+    const size_t need = hist_n + (size_t)P * npairs;   // histograms, then destination rows
+    std::lock_guard<std::mutex> lk(sc.mu);
+    if (!sc.done) VCCL_HIP(hipEventCreateWithFlags(&sc.done, hipEventDisableTiming));
+    // The scratch is shared: a new call starts after the previous one has finished
+    // with it on the device, and the pinned pointer staging is free again.
+    VCCL_HIP(hipEventSynchronize(sc.done));
+    if (need > sc.hist_n) {
+        if (sc.hist) VCCL_HIP(hipFree(sc.hist));
+        sc.hist = nullptr;
+        sc.hist_n = 0;
+        VCCL_HIP(hipMalloc((void **)&sc.hist, need * sizeof(uint32_t)));
+        sc.hist_n = need;
+    }
+    if ((size_t)3 * P > sc.ptrs_n) {
+        if (sc.ptrs) VCCL_HIP(hipFree(sc.ptrs));
+        if (sc.ptrs_host) VCCL_HIP(hipHostFree(sc.ptrs_host));
+        sc.ptrs = nullptr;
+        sc.ptrs_host = nullptr;
+        sc.ptrs_n = 0;
+        VCCL_HIP(hipMalloc((void **)&sc.ptrs, (size_t)3 * P * sizeof(void *)));
+        VCCL_HIP(hipHostMalloc((void **)&sc.ptrs_host, (size_t)3 * P * sizeof(void *), hipHostMallocDefault));
+        sc.ptrs_n = (size_t)3 * P;
+    }
+    for (int s = 0; s < P; ++s) {
+        sc.ptrs_host[s] = const_cast<void *>(x[s]);
+        sc.ptrs_host[P + s] = const_cast<int32_t *>(ids[s]);
+        sc.ptrs_host[2 * P + s] = packed[s];
+    }
+    VCCL_HIP(hipMemcpyAsync(sc.ptrs, sc.ptrs_host, (size_t)3 * P * sizeof(void *),
+                            hipMemcpyHostToDevice, stream));
+    MoePtrs ptrs;
+    ptrs.x = reinterpret_cast<const uint8_t *const *>(sc.ptrs);
+    ptrs.ids = reinterpret_cast<const int32_t *const *>(sc.ptrs + P);
+    ptrs.packed = reinterpret_cast<uint8_t *const *>(sc.ptrs + 2 * P);
+    uint32_t *hist = sc.hist;
+    uint32_t *dest = sc.hist + hist_n;
+    int ebits = 0;
+    while ((1 << ebits) < num_experts) ++ebits;
+
+    moe_hist_kernel<<<dim3(nblk, P), dim3(kMoeThreads), 0, stream>>>(ptrs, npairs, num_experts, nblk,
+                                                                    hist, bad_ids_dev);
+    VCCL_HIP(hipGetLastError());
+    moe_scan_kernel<<<dim3(P), dim3(kMoeThreads), 0, stream>>>(num_experts, nblk, hist, counts_dev);
+    VCCL_HIP(hipGetLastError());
+    if (npairs) {
+        moe_rank_kernel<<<dim3(nblk, P), dim3(kMoeThreads), 0, stream>>>(ptrs, npairs, num_experts,
+                                                                        ebits, nblk, hist, dest);
+        VCCL_HIP(hipGetLastError());
+        const uint32_t tok_blocks = ((uint32_t)tokens + kMoeThreads / 64 - 1) / (kMoeThreads / 64);
+        moe_gather_kernel<<<dim3(tok_blocks, P), dim3(kMoeThreads), 0, stream>>>(
+            ptrs, (uint32_t)tokens, topk, (uint32_t)(row_bytes >> 4), dest, npairs);
+        VCCL_HIP(hipGetLastError());
+    }
+    if (counts_host)
+        VCCL_HIP(hipMemcpyAsync(counts_host, counts_dev, (size_t)P * num_experts * sizeof(uint64_t),
+                                hipMemcpyDeviceToHost, stream));
+    VCCL_HIP(hipEventRecord(sc.done, stream));
+    return VCCL_OK;
+}
+
+}  // namespace vccl

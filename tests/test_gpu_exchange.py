@@ -1,0 +1,226 @@
+"""GPU parity: AlltoAll / AlltoAllv through the C boundary against the CPU oracle,
+bit for bit, whole buffers (bytes no segment covers must keep the sentinel)."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from gpu_util import SENTINEL, assert_same, require_gpu, stream_handle, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+MODES = ["cu", "ce"]
+
+
+@pytest.fixture(scope="module")
+def vccl():
+    require_gpu()
+    import paper_2510_00991_amd as v
+    v.vccl_init(0, 64)
+    yield v
+    v.vccl_finalize()
+
+
+def _mode(v, name):
+    return {"cu": v.MODE_CU, "ce": v.MODE_CE}[name]
+
+
+def _run_v(torch, v, lay, send_np, mode, misalign_send=None, misalign_recv=None, stream=None):
+    P = len(send_np)
+    ms = misalign_send or [0] * P
+    mr = misalign_recv or [0] * P
+    send = [to_dev(torch, send_np[s], ms[s]) for s in range(P)]
+    recv_np = [np.full(int(lay["recv_sizes"][r]), SENTINEL, dtype=np.uint8) for r in range(P)]
+    recv = [to_dev(torch, recv_np[r], mr[r]) for r in range(P)]
+    v.vccl_alltoallv(send, lay["sendcounts"], lay["sdispls"], recv, lay["recvcounts"], lay["rdispls"],
+                     P, mode, stream_handle(torch, stream))
+    torch.cuda.synchronize()
+    oracle.alltoallv(send_np, lay["sendcounts"], lay["sdispls"], recv_np, lay["recvcounts"],
+                     lay["rdispls"])
+    for r in range(P):
+        assert_same(to_host(recv[r]), recv_np[r], f"recv[{r}]")
+    for s in range(P):
+        assert_same(to_host(send[s]), send_np[s], f"send[{s}] must be unchanged")
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_config1_alltoall_p4_64k(vccl, mode):
+    """P = 4, equal 64 KiB blocks, uint8 payload from the seeded generator."""
+    torch = require_gpu()
+    P, c = 4, 65536
+    seed = wl.config_seed(1)
+    send_np = [wl.payload_bytes(seed, s, P * c) for s in range(P)]
+    recv_np = [np.full(P * c, SENTINEL, dtype=np.uint8) for _ in range(P)]
+    send = [to_dev(torch, a) for a in send_np]
+    recv = [to_dev(torch, a) for a in recv_np]
+    vccl.vccl_alltoall(send, recv, c, P, _mode(vccl, mode), stream_handle(torch))
+    torch.cuda.synchronize()
+    oracle.alltoall(send_np, recv_np, c)
+    for r in range(P):
+        assert_same(to_host(recv[r]), recv_np[r], f"recv[{r}]")
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_config2_alltoall_p8_16m_full_size(vccl, mode):
+    """P = 8, 16 MiB per peer (1 GiB sent), random 16-bit patterns; the launch
+    configuration is the one the benchmark times."""
+    torch = require_gpu()
+    P, c = 8, 16 << 20
+    seed = wl.config_seed(2)
+    send_np = [wl.payload_bytes(seed, s, P * c) for s in range(P)]
+    send = [to_dev(torch, a) for a in send_np]
+    recv = [torch.full((P * c,), SENTINEL, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    vccl.vccl_alltoall(send, recv, c, P, _mode(vccl, mode), stream_handle(torch))
+    torch.cuda.synchronize()
+    recv_np = [np.empty(P * c, dtype=np.uint8) for _ in range(P)]
+    oracle.alltoall(send_np, recv_np, c, threads=8)
+    for r in range(P):
+        assert_same(to_host(recv[r]), recv_np[r], f"recv[{r}]")
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("seed", range(8))
+def test_alltoallv_random_layouts(vccl, mode, seed):
+    """Random P in 1..9, counts with zeros, shuffled unaligned segments with gaps,
+    buffers starting at odd device addresses."""
+    torch = require_gpu()
+    rng = np.random.Generator(np.random.PCG64(1000 + seed))
+    P = int(rng.integers(1, 10))
+    max_count = int(rng.choice([40, 3000, 70000, 300000]))
+    lay = wl.random_layout(2000 + seed, P, max_count, align=1)
+    send_np = [wl.payload_bytes(seed, s, int(lay["send_sizes"][s])) for s in range(P)]
+    _run_v(torch, vccl, lay, send_np, _mode(vccl, mode),
+           misalign_send=[int(x) for x in rng.integers(0, 16, P)],
+           misalign_recv=[int(x) for x in rng.integers(0, 16, P)])
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_alltoallv_aligned_layout_spans_tiles(vccl, mode):
+    """16-byte aligned fast path: segments of several tiles plus a ragged tail."""
+    torch = require_gpu()
+    lay = wl.random_layout(77, 5, 700000, align=16, zero_fraction=0.1)
+    send_np = [wl.payload_bytes(78, s, int(lay["send_sizes"][s])) for s in range(5)]
+    _run_v(torch, vccl, lay, send_np, _mode(vccl, mode))
+
+
+def test_every_relative_misalignment_cu(vccl):
+    """All 16 x 16 (source, destination) address residues modulo 16 in one call:
+    segment s -> r reads at residue r and writes at residue s, and its length
+    leaves a head, several LDS rounds of body and a tail."""
+    torch = require_gpu()
+    P = 16
+    n = 40000 + 13
+    stride = n + 64
+    counts = np.full((P, P), n, dtype=np.uint64)
+    sd = np.zeros((P, P), dtype=np.uint64)
+    rd = np.zeros((P, P), dtype=np.uint64)
+    for a in range(P):
+        for b in range(P):
+            sd[a, b] = b * stride + ((b - (b * stride)) % 16)        # residue b in rank a's buffer
+            rd[a, b] = b * stride + ((b - (b * stride)) % 16)        # residue b in rank a's buffer
+    lay = {"sendcounts": counts, "sdispls": sd, "recvcounts": counts.copy(), "rdispls": rd,
+           "send_sizes": np.full(P, P * stride + 32), "recv_sizes": np.full(P, P * stride + 32)}
+    send_np = [wl.payload_bytes(5, s, int(lay["send_sizes"][s])) for s in range(P)]
+    _run_v(torch, vccl, lay, send_np, vccl.MODE_CU)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("c", [4096, 65536])
+def test_config5_p64_sweep_points(vccl, mode, c):
+    """P = 64 (4096 segments, the device descriptor table path) at two sweep sizes."""
+    torch = require_gpu()
+    P = 64
+    seed = wl.config_seed(5)
+    send_np = [wl.payload_bytes(seed, s, P * c) for s in range(P)]
+    recv_np = [np.full(P * c, SENTINEL, dtype=np.uint8) for _ in range(P)]
+    send = [to_dev(torch, a) for a in send_np]
+    recv = [to_dev(torch, a) for a in recv_np]
+    vccl.vccl_alltoall(send, recv, c, P, _mode(vccl, mode), stream_handle(torch))
+    torch.cuda.synchronize()
+    oracle.alltoall(send_np, recv_np, c, threads=4)
+    for r in range(P):
+        assert_same(to_host(recv[r]), recv_np[r], f"recv[{r}]")
+
+
+def test_p64_alltoallv_non_uniform_table_search(vccl):
+    """More than 64 segments of different tile counts: the wavefront search of the
+    descriptor table is exercised (uniform layouts bypass it)."""
+    torch = require_gpu()
+    lay = wl.random_layout(4242, 40, 90000, align=16, zero_fraction=0.3)
+    send_np = [wl.payload_bytes(9, s, int(lay["send_sizes"][s])) for s in range(40)]
+    _run_v(torch, vccl, lay, send_np, vccl.MODE_CU)
+    vccl.vccl_set_option("cu_unroll", 1)
+    vccl.vccl_set_option("cu_xcd_map", 1)
+    try:
+        _run_v(torch, vccl, lay, send_np, vccl.MODE_CU)
+    finally:
+        vccl.vccl_set_option("cu_unroll", 8)
+        vccl.vccl_set_option("cu_xcd_map", 0)
+
+
+@pytest.mark.parametrize("unroll", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("nt", [0, 1])
+def test_copy_kernel_variants(vccl, unroll, nt):
+    torch = require_gpu()
+    lay = wl.random_layout(31, 4, 500000, align=1)
+    send_np = [wl.payload_bytes(32, s, int(lay["send_sizes"][s])) for s in range(4)]
+    vccl.vccl_set_option("cu_unroll", unroll)
+    vccl.vccl_set_option("cu_nontemporal", nt)
+    try:
+        _run_v(torch, vccl, lay, send_np, vccl.MODE_CU)
+    finally:
+        vccl.vccl_set_option("cu_unroll", 8)
+        vccl.vccl_set_option("cu_nontemporal", 1)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_edge_cases(vccl, mode):
+    torch = require_gpu()
+    m = _mode(vccl, mode)
+    # P = 1 is the identity
+    x_np = wl.payload_bytes(1, 0, 1000)
+    x = to_dev(torch, x_np, 3)
+    y = to_dev(torch, np.full(1000, SENTINEL, np.uint8), 5)
+    vccl.vccl_alltoall([x], [y], 1000, 1, m, stream_handle(torch))
+    torch.cuda.synchronize()
+    assert_same(to_host(y), x_np, "P=1 identity")
+    # all-zero counts: nothing happens, NULL buffers are fine
+    z = np.zeros((3, 3), dtype=np.uint64)
+    vccl.vccl_alltoallv([0, 0, 0], z, z, [0, 0, 0], z, z, 3, m, stream_handle(torch))
+    # zero bytes per peer
+    vccl.vccl_alltoall([x], [y], 0, 1, m, stream_handle(torch))
+    # single-byte segments
+    one = np.ones((2, 2), dtype=np.uint64)
+    d = np.array([[0, 1], [0, 1]], dtype=np.uint64)
+    s_np = [np.array([10, 11], np.uint8), np.array([20, 21], np.uint8)]
+    s_dev = [to_dev(torch, a, 1) for a in s_np]
+    r_dev = [to_dev(torch, np.full(3, SENTINEL, np.uint8), 7) for _ in range(2)]
+    vccl.vccl_alltoallv(s_dev, one, d, r_dev, one, d, 2, m, stream_handle(torch))
+    torch.cuda.synchronize()
+    assert to_host(r_dev[0]).tolist() == [10, 20, SENTINEL]
+    assert to_host(r_dev[1]).tolist() == [11, 21, SENTINEL]
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_stream_ordering(vccl, mode):
+    """The exchange starts after earlier work on the caller's stream and later work
+    on that stream sees the received data (a side stream, repeated)."""
+    torch = require_gpu()
+    P, c = 4, 1 << 20
+    side = torch.cuda.Stream()
+    send = [torch.zeros(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    recv = [torch.zeros(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    snap = [torch.zeros(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    torch.cuda.synchronize()
+    for it in range(1, 6):
+        with torch.cuda.stream(side):
+            for s in range(P):
+                send[s].fill_(it * 10 + s)                       # producer on the same stream
+            vccl.vccl_alltoall(send, recv, c, P, _mode(vccl, mode), stream_handle(torch, side))
+            for r in range(P):
+                snap[r].copy_(recv[r])                           # consumer on the same stream
+        side.synchronize()
+        for r in range(P):
+            got = to_host(snap[r]).reshape(P, c)
+            for s in range(P):
+                assert (got[s] == it * 10 + s).all(), (mode, it, r, s)

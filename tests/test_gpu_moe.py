@@ -1,0 +1,130 @@
+"""GPU parity: MoE dispatch pack (stable sort by expert + row gather) and the
+AlltoAllv that follows it, against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from gpu_util import SENTINEL, assert_same, require_gpu, stream_handle, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vccl():
+    require_gpu()
+    import paper_2510_00991_amd as v
+    v.vccl_init(0, 64)
+    yield v
+    v.vccl_finalize()
+
+
+def _dispatch(torch, v, P, T, K, E, row, seed, mode, x_np=None, ids_np=None):
+    epr = E // P
+    if x_np is None:
+        x_np = [wl.payload_bytes(seed, s, T * row) for s in range(P)]
+    if ids_np is None:
+        ids_np = [wl.zipf_topk_expert_ids(seed, s, T, K, E) for s in range(P)]
+    x = [to_dev(torch, a) for a in x_np]
+    ids = [torch.from_numpy(a.reshape(-1).copy()).cuda() for a in ids_np]
+    packed = [torch.full((max(1, T * K * row),), SENTINEL, dtype=torch.uint8, device="cuda")
+              for _ in range(P)]
+    counts_dev = torch.zeros((P, E), dtype=torch.int64, device="cuda")
+    counts_host = torch.zeros((P, E), dtype=torch.int64).pin_memory()
+    bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    st = stream_handle(torch)
+    v.vccl_moe_pack(x, ids, P, T, K, row, E, packed, counts_dev, counts_host, bad, st)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0
+    cnt_got = counts_host.numpy().astype(np.uint64)
+    assert np.array_equal(cnt_got, counts_dev.cpu().numpy().astype(np.uint64))
+    want_packed, cnts = [], []
+    for s in range(P):
+        pk, order, cnt = oracle.moe_pack(x_np[s], ids_np[s], row, E)
+        assert np.array_equal(cnt_got[s], cnt), f"counts of rank {s}"
+        assert_same(to_host(packed[s])[:T * K * row], pk, f"packed[{s}]")
+        want_packed.append(pk)
+        cnts.append(cnt)
+    lay = v.vccl_moe_exchange_layout(cnt_got, P, E, epr, row)
+    want_lay = oracle.moe_exchange_layout(np.stack(cnts), epr, row)
+    for k in want_lay:
+        assert np.array_equal(lay[k], want_lay[k]), k
+    rsz = [int(lay["recvcounts"][r].sum()) for r in range(P)]
+    recv = [torch.full((rsz[r] + 16,), SENTINEL, dtype=torch.uint8, device="cuda") for r in range(P)]
+    v.vccl_alltoallv(packed, lay["sendcounts"], lay["sdispls"], recv, lay["recvcounts"],
+                     lay["rdispls"], P, mode, st)
+    torch.cuda.synchronize()
+    recv_np = [np.full(rsz[r] + 16, SENTINEL, dtype=np.uint8) for r in range(P)]
+    oracle.alltoallv(want_packed, want_lay["sendcounts"], want_lay["sdispls"], recv_np,
+                     want_lay["recvcounts"], want_lay["rdispls"], threads=8)
+    for r in range(P):
+        assert_same(to_host(recv[r]), recv_np[r], f"recv[{r}]")
+    return rsz
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1, 16), (2, 5, 2, 4, 32), (2, 300, 8, 256, 48),
+                                   (4, 1000, 4, 64, 14336), (8, 2049, 8, 256, 272),
+                                   (3, 700, 3, 999, 16)])
+def test_pack_and_exchange_small(vccl, shape):
+    """Several histogram blocks, a ragged last block, row sizes below / above one
+    register pass, expert counts that are not powers of two."""
+    torch = require_gpu()
+    P, T, K, E, row = shape
+    if E % P:
+        E = (E // P) * P
+    _dispatch(torch, vccl, P, T, K, E, row, 300 + P + T, vccl.MODE_CU)
+
+
+def test_pack_then_copy_engine_exchange(vccl):
+    torch = require_gpu()
+    _dispatch(torch, vccl, 4, 512, 8, 64, 1024, 77, vccl.MODE_CE)
+
+
+def test_empty_and_degenerate(vccl):
+    torch = require_gpu()
+    # no tokens at all
+    _dispatch(torch, vccl, 2, 0, 2, 4, 16, 1, vccl.MODE_CU)
+    # every pair to one expert: one destination gets everything, stable order is the input order
+    P, T, K, E, row = 2, 600, 2, 8, 64
+    ids = [np.full((T, K), 5, dtype=np.int32) for _ in range(P)]
+    rsz = _dispatch(torch, vccl, P, T, K, E, row, 2, vccl.MODE_CU, ids_np=ids)
+    assert rsz == [0, P * T * K * row]
+
+
+def test_out_of_range_ids_are_counted_and_dropped(vccl):
+    torch = require_gpu()
+    T, K, E, row = 64, 2, 4, 32
+    ids_np = wl.zipf_topk_expert_ids(5, 0, T, K, E).copy()
+    ids_np[3, 1] = 9
+    ids_np[10, 0] = -2
+    x_np = wl.payload_bytes(6, 0, T * row)
+    x = to_dev(torch, x_np)
+    ids = torch.from_numpy(ids_np.reshape(-1).copy()).cuda()
+    packed = torch.full((T * K * row,), SENTINEL, dtype=torch.uint8, device="cuda")
+    counts = torch.zeros((1, E), dtype=torch.int64, device="cuda")
+    bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    vccl.vccl_moe_pack([x], [ids], 1, T, K, row, E, [packed], counts, None, bad, stream_handle(torch))
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 2
+    # the remaining pairs are packed as the oracle packs the list with the two pairs removed
+    keys = ids_np.reshape(-1)
+    keep = (keys >= 0) & (keys < E)
+    order = np.argsort(np.where(keep, keys, E), kind="stable")[:keep.sum()]
+    want = x_np.reshape(T, row)[order // K].reshape(-1)
+    assert_same(to_host(packed)[:want.size], want, "packed with dropped pairs")
+    assert (to_host(packed)[want.size:] == SENTINEL).all()
+    assert counts.cpu().numpy().sum() == keep.sum()
+
+
+def test_config3_moe_dispatch_full_size(vccl):
+    """P = 8, 8192 tokens x 7168 bf16 N(0,1) per rank, top-8 of 256 experts with
+    Zipf(1.2) ids: pack (65 536 rows of 14 336 B per rank) then AlltoAllv."""
+    torch = require_gpu()
+    P, T, K, E, H = 8, 8192, 8, 256, 7168
+    row = H * 2
+    seed = wl.config_seed(3)
+    x_np = [wl.normal_bf16_bits(seed, s, T * H).view(np.uint8) for s in range(P)]
+    ids_np = [wl.zipf_topk_expert_ids(seed, s, T, K, E) for s in range(P)]
+    rsz = _dispatch(torch, vccl, P, T, K, E, row, seed, vccl.MODE_CU, x_np=x_np, ids_np=ids_np)
+    assert sum(rsz) == P * T * K * row
+    assert rsz[0] == max(rsz), "rank 0 hosts the hot experts"
