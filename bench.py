@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the P2P data-movement path on one MI355X.
+
+A step is one AlltoAll of the headline workload (P = 8 virtual ranks, 16 MiB per
+peer, 1 GiB sent, random 16-bit patterns) through the C boundary on the
+compute-unit copy path: host planning, launch and the copy itself.  The metric is
+achieved GB/s counted as bytes read plus bytes written, set against the HBM peak.
+The same run also reports the copy-engine path on the same workload, the co-run
+slowdown each path causes to a compute-bound FMA kernel, the MoE pack, the
+SendRecv ring, and the CPU oracle timed on the host cores.
+
+Prints ONE JSON line.  `python bench.py --gpus 1 --steps K --warmup W`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def _events(torch, n):
+    return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            for _ in range(n)]
+
+
+def time_calls(torch, fn, steps, warmup):
+    """Wall time of `steps` back-to-back calls plus per-call device durations
+    from events recorded on the stream the library launches on."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = _events(torch, steps)
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per = [a.elapsed_time(b) * 1e-3 for a, b in ev]
+    return wall, per
+
+
+def corun_slowdown(torch, v, comm_fn, comm_stream, fma_out, iters, reps, n_comm):
+    """Median FMA-probe time with `comm_fn` looping on another stream, and alone."""
+    comp = torch.cuda.Stream()
+    st = int(comp.cuda_stream)
+
+    def probe_alone():
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(comp):
+            a.record()
+            v.vccl_fma_probe(fma_out, 0, 256, iters, st)
+            b.record()
+        comp.synchronize()
+        return a.elapsed_time(b) * 1e-3
+
+    for _ in range(3):
+        probe_alone()
+    alone = [probe_alone() for _ in range(reps)]
+    both, comm_bytes_time = [], []
+    for _ in range(reps):
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(comm_stream):
+            c0.record()
+            for _ in range(n_comm):
+                comm_fn()
+            c1.record()
+        with torch.cuda.stream(comp):
+            a.record()
+            v.vccl_fma_probe(fma_out, 0, 256, iters, st)
+            b.record()
+        torch.cuda.synchronize()
+        both.append(a.elapsed_time(b) * 1e-3)
+        comm_bytes_time.append(c0.elapsed_time(c1) * 1e-3)
+    t0 = statistics.median(alone)
+    t1 = statistics.median(both)
+    return {"alone_ms": t0 * 1e3, "corun_ms": t1 * 1e3, "slowdown_pct": 100.0 * (t1 - t0) / t0,
+            "comm_ms": statistics.median(comm_bytes_time) * 1e3}
+
+
+def cpu_baseline(P, c, budget_s=12.0):
+    """The oracle, as it stands, on the host cores: the destination-rank loop
+    spread over min(P, cores) threads; a bounded number of passes."""
+    import numpy as np
+
+    import oracle
+    import workloads as wl
+
+    cores = min(P, len(os.sched_getaffinity(0)))
+    send = [wl.payload_bytes(wl.config_seed(2), s, P * c) for s in range(P)]
+    recv = [np.empty(P * c, dtype=np.uint8) for _ in range(P)]
+    oracle.alltoall(send, recv, c, threads=cores)        # touch pages
+    t_end = time.perf_counter() + budget_s
+    times = []
+    while time.perf_counter() < t_end and len(times) < 20:
+        t0 = time.perf_counter()
+        oracle.alltoall(send, recv, c, threads=cores)
+        times.append(time.perf_counter() - t0)
+    t1 = time.perf_counter()
+    oracle.alltoall(send, recv, c, threads=1)
+    single = time.perf_counter() - t1
+    gb = 2.0 * P * P * c / 1e9
+    return {"value": gb / statistics.median(times), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{len(times)} passes of the full P={P}, {c >> 20} MiB-per-peer AlltoAll "
+                      f"({P * P * c >> 20} MiB sent per pass), bytes read + written",
+            "single_core_GBps": gb / single}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--skip-extras", action="store_true", help="only the headline AlltoAll timing")
+    ap.add_argument("--skip-cpu", action="store_true", help="leave out the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path is built and measured on ONE GPU (P virtual ranks in one HBM); "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2510_00991_amd as v
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    v.vccl_init(0, 64)
+    out = {}
+    try:
+        P, c = 8, 16 << 20
+        total = P * P * c
+        seed = wl.config_seed(2)
+        send = [torch.from_numpy(wl.payload_bytes(seed, s, P * c)).cuda() for s in range(P)]
+        recv = [torch.zeros(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
+        st = int(torch.cuda.current_stream().cuda_stream)
+        algo_bytes = 2.0 * total                          # every byte is read once and written once
+
+        def a2a_cu():
+            v.vccl_alltoall(send, recv, c, P, v.MODE_CU, st)
+
+        def a2a_ce():
+            v.vccl_alltoall(send, recv, c, P, v.MODE_CE, st)
+
+        wall, per = time_calls(torch, a2a_cu, args.steps, args.warmup)
+        ms_per_step = wall / args.steps * 1e3
+        value = algo_bytes / (wall / args.steps) / 1e9
+        kern = statistics.mean(per)
+        achieved = algo_bytes / kern / 1e9
+        out = {
+            "metric": "AlltoAll(v) achieved GB/s (R+W) vs HBM peak; co-run compute slowdown %",
+            "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+            "config": {"workload": "AlltoAll P=8 virtual ranks, 16 MiB per peer (1 GiB sent), "
+                                   "bf16 payload as random 16-bit patterns, compute-unit copy path",
+                       "P": P, "bytes_per_peer": c, "mode": "cu",
+                       "cu_unroll": int(v.vccl_get_option("cu_unroll")),
+                       "cu_wg_per_cu": int(v.vccl_get_option("cu_wg_per_cu"))},
+            "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                         "kernel": "copy_segments_kernel", "kernel_us": kern * 1e6,
+                         "algorithmic_bytes": algo_bytes},
+            "frac_of_hbm_peak": value / HBM_PEAK_GBS,
+        }
+        # correctness spot check of what was just timed: block s of recv[r] is block r of send[s]
+        for r, s in ((0, 7), (5, 2)):
+            assert torch.equal(recv[r][s * c:(s + 1) * c], send[s][r * c:(r + 1) * c])
+
+        if not args.skip_extras:
+            k_ce = max(3, min(args.steps, 10))
+            wall_ce, per_ce = time_calls(torch, a2a_ce, k_ce, 2)
+            out["copy_engine"] = {"GBps": algo_bytes / (wall_ce / k_ce) / 1e9,
+                                  "ms_per_step": wall_ce / k_ce * 1e3, "steps": k_ce,
+                                  "streams": int(v.vccl_get_option("ce_streams")),
+                                  "kind": v.vccl_get_option("ce_kind")}
+            # co-run: FMA probe alone vs beside each path
+            cu = v.vccl_device_cu_count()
+            fma_out = torch.zeros(cu * 256, dtype=torch.float32, device="cuda")
+            comm = torch.cuda.Stream()
+            cst = int(comm.cuda_stream)
+            iters = 60000
+            n_cu = max(2, int(0.004 / kern) + 2)
+            cor_cu = corun_slowdown(torch, v, lambda: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, cst),
+                                    comm, fma_out, iters, 15, n_cu)
+            cor_ce = corun_slowdown(torch, v, lambda: v.vccl_alltoall(send, recv, c, P, v.MODE_CE, cst),
+                                    comm, fma_out, iters, 15, 1)
+            out["corun"] = {"probe": f"FMA kernel, {cu} workgroups x 256 threads, {iters} rounds",
+                            "cu_path": cor_cu, "copy_engine_path": cor_ce}
+            # SendRecv ring, 8 stages x 64 MiB
+            n = 64 << 20
+            to, frm = wl.ring_peers(P)
+            sr = {}
+            for name, mode in (("cu_direct", v.MODE_CU), ("cu_staged", v.MODE_CU_STAGED),
+                               ("copy_engine", v.MODE_CE)):
+                fn = lambda m=mode: v.vccl_sendrecv(send, [n] * P, to, recv, [n] * P, frm, P, m, st)
+                w, _ = time_calls(torch, fn, 5, 2)
+                sr[name] = {"GBps": 2.0 * P * n / (w / 5) / 1e9, "ms": w / 5 * 1e3}
+            v.vccl_sendrecv_staged_status()
+            out["sendrecv_ring_8x64MiB"] = sr
+            del send, recv
+            torch.cuda.empty_cache()
+            # MoE pack, config 3 shapes
+            T, K, E, H = 8192, 8, 256, 7168
+            row = H * 2
+            x = [torch.from_numpy(wl.normal_bf16_bits(wl.config_seed(3), s, T * H).view(np.uint8)).cuda()
+                 for s in range(P)]
+            ids = [torch.from_numpy(wl.zipf_topk_expert_ids(wl.config_seed(3), s, T, K, E).reshape(-1).copy()).cuda()
+                   for s in range(P)]
+            packed = [torch.empty(T * K * row, dtype=torch.uint8, device="cuda") for _ in range(P)]
+            counts = torch.zeros((P, E), dtype=torch.int64, device="cuda")
+            counts_h = torch.zeros((P, E), dtype=torch.int64).pin_memory()
+            fn = lambda: v.vccl_moe_pack(x, ids, P, T, K, row, E, packed, counts, counts_h, None, st)
+            w, _ = time_calls(torch, fn, 5, 2)
+            pack_bytes = P * (T * row + T * K * 4 + T * K * row)
+            lay = v.vccl_moe_exchange_layout(counts_h.numpy().astype(np.uint64), P, E, E // P, row)
+            rcv = [torch.empty(int(lay["recvcounts"][r].sum()), dtype=torch.uint8, device="cuda")
+                   for r in range(P)]
+            fx = lambda: v.vccl_alltoallv(packed, lay["sendcounts"], lay["sdispls"], rcv,
+                                          lay["recvcounts"], lay["rdispls"], P, v.MODE_CU, st)
+            wx, _ = time_calls(torch, fx, 5, 2)
+            out["moe_dispatch"] = {
+                "pack_GBps": pack_bytes / (w / 5) / 1e9, "pack_ms": w / 5 * 1e3,
+                "exchange_GBps": 2.0 * float(lay["sendcounts"].sum()) / (wx / 5) / 1e9,
+                "exchange_ms": wx / 5 * 1e3,
+                "recv_bytes_per_rank": [int(lay["recvcounts"][r].sum()) for r in range(P)]}
+            del x, ids, packed, rcv
+            torch.cuda.empty_cache()
+    finally:
+        v.vccl_finalize()
+
+    if not args.skip_cpu:
+        out["cpu_baseline"] = cpu_baseline(8, 16 << 20)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
