@@ -123,9 +123,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--skip-extras", action="store_true", help="only the headline AlltoAll timing")
-    ap.add_argument("--skip-cpu", action="store_true", help="leave out the CPU oracle baseline")
+    ap.add_argument("--legs", default="cu,ce,corun,sendrecv,moe,cpu",
+                    help="comma list of legs to run: cu (always), ce, corun, sendrecv, moe, cpu, "
+                         "calib (a plain 1 GiB device copy, used to scale profiler counters)")
     args = ap.parse_args()
+    legs = set(x.strip() for x in args.legs.split(",") if x.strip())
+    unknown = legs - {"cu", "ce", "corun", "sendrecv", "moe", "cpu", "calib"}
+    if unknown:
+        print(f"bench.py: unknown legs {sorted(unknown)}", file=sys.stderr)
+        sys.exit(2)
     if args.gpus != 1:
         print("bench.py: this path is built and measured on ONE GPU (P virtual ranks in one HBM); "
               "--gpus above 1 is not supported", file=sys.stderr)
@@ -183,13 +189,20 @@ def main():
         for r, s in ((0, 7), (5, 2)):
             assert torch.equal(recv[r][s * c:(s + 1) * c], send[s][r * c:(r + 1) * c])
 
-        if not args.skip_extras:
+        if "calib" in legs:
+            a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+            b = torch.empty_like(a)
+            w, _ = time_calls(torch, lambda: b.copy_(a), 5, 2)
+            out["calib_copy_1GiB"] = {"GBps": 2.0 * (1 << 30) / (w / 5) / 1e9, "launches": 7}
+            del a, b
+        if "ce" in legs:
             k_ce = max(3, min(args.steps, 10))
             wall_ce, per_ce = time_calls(torch, a2a_ce, k_ce, 2)
             out["copy_engine"] = {"GBps": algo_bytes / (wall_ce / k_ce) / 1e9,
                                   "ms_per_step": wall_ce / k_ce * 1e3, "steps": k_ce,
                                   "streams": int(v.vccl_get_option("ce_streams")),
                                   "kind": v.vccl_get_option("ce_kind")}
+        if "corun" in legs:
             # co-run: FMA probe alone vs beside each path
             cu = v.vccl_device_cu_count()
             fma_out = torch.zeros(cu * 256, dtype=torch.float32, device="cuda")
@@ -203,6 +216,7 @@ def main():
                                     comm, fma_out, iters, 15, 1)
             out["corun"] = {"probe": f"FMA kernel, {cu} workgroups x 256 threads, {iters} rounds",
                             "cu_path": cor_cu, "copy_engine_path": cor_ce}
+        if "sendrecv" in legs:
             # SendRecv ring, 8 stages x 64 MiB
             n = 64 << 20
             to, frm = wl.ring_peers(P)
@@ -214,8 +228,9 @@ def main():
                 sr[name] = {"GBps": 2.0 * P * n / (w / 5) / 1e9, "ms": w / 5 * 1e3}
             v.vccl_sendrecv_staged_status()
             out["sendrecv_ring_8x64MiB"] = sr
-            del send, recv
-            torch.cuda.empty_cache()
+        del send, recv
+        torch.cuda.empty_cache()
+        if "moe" in legs:
             # MoE pack, config 3 shapes
             T, K, E, H = 8192, 8, 256, 7168
             row = H * 2
@@ -245,10 +260,7 @@ def main():
     finally:
         v.vccl_finalize()
 
-    if not args.skip_cpu:
-        out["cpu_baseline"] = cpu_baseline(8, 16 << 20)
-    else:
-        out["cpu_baseline"] = None
+    out["cpu_baseline"] = cpu_baseline(8, 16 << 20) if "cpu" in legs else None
     print(json.dumps(out))
 
 

@@ -81,10 +81,12 @@ const char *vccl_last_error(void);
 
 /* Tuning and test knobs; unknown keys or unparsable values give VCCL_ERR_ARG
  * (silently ignored settings are the configuration hazard of Section 5).
- * Keys: "cu_unroll" (16-byte vectors per lane per tile: 1,2,4,8),
- *       "cu_wg_per_cu" (persistent workgroups per compute unit, 1..16),
+ * Keys: "cu_unroll" (16-byte vectors per lane per tile: 1,2,4,8,16),
+ *       "cu_wg_per_cu" (0 = one workgroup per tile; 1..16 = that many grid-striding
+ *                        workgroups per compute unit),
  *       "cu_max_wg" (cap on the copy grid, 0 = none; the co-run study sweeps it),
- *       "cu_nontemporal" (0/1), "ce_streams" (1..8 internal copy streams),
+ *       "cu_nontemporal" (0/1), "cu_fast_path" (0/1: allow the all-aligned kernel),
+ *       "ce_streams" (1..8 internal copy streams),
  *       "ce_kind" ("nocu" | "default": hipMemcpyKind of copy-engine copies),
  *       "check" (0/1 overlap validation),
  *       "fifo_chunk_bytes", "fifo_slots", "fifo_wg_per_conn",

@@ -227,7 +227,7 @@ int vccl_init(int device, int max_ranks) {
     c->device = device;
     c->max_ranks = max_ranks;
     VCCL_HIP(hipDeviceGetAttribute(&c->cu_count, hipDeviceAttributeMultiprocessorCount, device));
-    int rv = c->ring.init((size_t)max_ranks * (size_t)max_ranks);
+    int rv = c->ring.init((size_t)max_ranks * (size_t)max_ranks + 8192);  // + pieces of cut segments
     if (rv) {
         c->ring.destroy();
         return rv;
@@ -294,7 +294,7 @@ int vccl_set_option(const char *key, const char *value) {
             return fail(VCCL_ERR_ARG, "cu_unroll must be 1, 2, 4, 8 or 16");
         o.cu_unroll = (int)x;
     } else if (k == "cu_wg_per_cu") {
-        if (!in(1, 16)) return fail(VCCL_ERR_ARG, "cu_wg_per_cu must be 1..16");
+        if (!in(0, 16)) return fail(VCCL_ERR_ARG, "cu_wg_per_cu must be 0..16");
         o.cu_wg_per_cu = (int)x;
     } else if (k == "cu_max_wg") {
         if (!in(0, 1u << 20)) return fail(VCCL_ERR_ARG, "cu_max_wg must be 0..1048576");
@@ -302,9 +302,9 @@ int vccl_set_option(const char *key, const char *value) {
     } else if (k == "cu_nontemporal") {
         if (!in(0, 1)) return fail(VCCL_ERR_ARG, "cu_nontemporal must be 0 or 1");
         o.cu_nontemporal = (int)x;
-    } else if (k == "cu_xcd_map") {
-        if (!in(0, 1)) return fail(VCCL_ERR_ARG, "cu_xcd_map must be 0 or 1");
-        o.cu_xcd_map = (int)x;
+    } else if (k == "cu_fast_path") {
+        if (!in(0, 1)) return fail(VCCL_ERR_ARG, "cu_fast_path must be 0 or 1");
+        o.cu_fast_path = (int)x;
     } else if (k == "ce_streams") {
         if (!in(1, 8)) return fail(VCCL_ERR_ARG, "ce_streams must be 1..8");
         o.ce_streams = (int)x;
@@ -344,7 +344,7 @@ int vccl_get_option(const char *key, char *out, int cap) {
     else if (k == "cu_wg_per_cu") v = o.cu_wg_per_cu;
     else if (k == "cu_max_wg") v = o.cu_max_wg;
     else if (k == "cu_nontemporal") v = o.cu_nontemporal;
-    else if (k == "cu_xcd_map") v = o.cu_xcd_map;
+    else if (k == "cu_fast_path") v = o.cu_fast_path;
     else if (k == "ce_streams") v = o.ce_streams;
     else if (k == "check") v = o.check;
     else if (k == "fifo_chunk_bytes") v = o.fifo_chunk_bytes;

@@ -17,16 +17,15 @@
 
 namespace vccl {
 
-// One contiguous piece of an exchange: `bytes` bytes from src to dst.
-// tile_begin is the index of the segment's first tile in the launch-wide tile
-// numbering; head is the number of leading bytes copied bytewise so that the
-// vector body starts at a 16-byte aligned destination.
+// One contiguous piece of an exchange: `bytes` bytes from src to dst.  head is the
+// number of leading bytes copied bytewise so that the vector body starts at a
+// 16-byte aligned destination.
 struct Seg {
     const uint8_t *src;
     uint8_t *dst;
     uint64_t bytes;
-    uint32_t tile_begin;
     uint32_t head;
+    uint32_t reserved;
 };
 static_assert(sizeof(Seg) == 32, "descriptor layout");
 
@@ -34,11 +33,11 @@ constexpr int kInlineSegs = 64;     // descriptors carried in the kernel argumen
 constexpr int kCopyThreads = 256;   // 4 wavefronts per workgroup
 
 struct Options {
-    int cu_unroll = 8;
-    int cu_wg_per_cu = 8;
+    int cu_unroll = 1;
+    int cu_wg_per_cu = 0;
     int cu_max_wg = 0;
     int cu_nontemporal = 1;
-    int cu_xcd_map = 0;
+    int cu_fast_path = 1;
     int ce_streams = 4;
     int ce_kind_nocu = 1;
     int check = 0;
@@ -82,9 +81,10 @@ struct DescRing {
 
 // ---- CU copy path
 struct CopyPlan {
-    std::vector<Seg> segs;       // non-empty segments only, tile_begin / head filled in
-    uint32_t total_tiles = 0;
-    uint32_t uniform_tiles = 0;  // > 0: every segment has exactly this many tiles
+    std::vector<Seg> segs;       // non-empty descriptors, tile_begin / head filled in
+    uint64_t total_tiles = 0;
+    uint32_t max_tiles = 0;      // tiles of the longest descriptor (grid x)
+    bool all_aligned = false;    // every descriptor: 16-byte aligned ends, whole vectors
     uint64_t bytes = 0;
 };
 // Fills tile_begin/head for plan.segs (src, dst, bytes already set).

@@ -142,20 +142,68 @@ def test_config5_p64_sweep_points(vccl, mode, c):
         assert_same(to_host(recv[r]), recv_np[r], f"recv[{r}]")
 
 
-def test_p64_alltoallv_non_uniform_table_search(vccl):
-    """More than 64 segments of different tile counts: the wavefront search of the
-    descriptor table is exercised (uniform layouts bypass it)."""
+def _with_options(v, opts, fn):
+    saved = {k: v.vccl_get_option(k) for k in opts}
+    for k, val in opts.items():
+        v.vccl_set_option(k, val)
+    try:
+        fn()
+    finally:
+        for k, val in saved.items():
+            v.vccl_set_option(k, val)
+
+
+def test_p40_alltoallv_table_path_non_uniform(vccl):
+    """More than 64 descriptors of different lengths: the device descriptor table
+    and the early exit of workgroups past a short descriptor."""
     torch = require_gpu()
     lay = wl.random_layout(4242, 40, 90000, align=16, zero_fraction=0.3)
     send_np = [wl.payload_bytes(9, s, int(lay["send_sizes"][s])) for s in range(40)]
     _run_v(torch, vccl, lay, send_np, vccl.MODE_CU)
-    vccl.vccl_set_option("cu_unroll", 1)
-    vccl.vccl_set_option("cu_xcd_map", 1)
-    try:
-        _run_v(torch, vccl, lay, send_np, vccl.MODE_CU)
-    finally:
-        vccl.vccl_set_option("cu_unroll", 8)
-        vccl.vccl_set_option("cu_xcd_map", 0)
+    _with_options(vccl, {"cu_unroll": 1}, lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CU))
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_skewed_layout_is_cut_into_pieces(vccl, mode):
+    """One 40 MB segment among tiny ones, all unaligned: the planner cuts the long
+    segment into pieces; heads, tails and cut points must all land exactly."""
+    torch = require_gpu()
+    P = 4
+    counts = np.full((P, P), 9001, dtype=np.uint64)
+    counts[2, 1] = 40_000_003
+    counts[0, 3] = 0
+    counts[3, 3] = 5
+    sd = np.zeros((P, P), dtype=np.uint64)
+    rd = np.zeros((P, P), dtype=np.uint64)
+    ssz, rsz = [], []
+    for a in range(P):
+        pos = 3
+        for b in range(P):
+            sd[a, b] = pos
+            pos += int(counts[a, b]) + 7
+        ssz.append(pos)
+        pos = 11
+        for b in range(P):
+            rd[a, b] = pos
+            pos += int(counts[b, a]) + 5
+        rsz.append(pos)
+    lay = {"sendcounts": counts, "sdispls": sd, "recvcounts": counts.T.copy(), "rdispls": rd,
+           "send_sizes": np.array(ssz), "recv_sizes": np.array(rsz)}
+    send_np = [wl.payload_bytes(12, s, ssz[s]) for s in range(P)]
+    _run_v(torch, vccl, lay, send_np, _mode(vccl, mode))
+
+
+@pytest.mark.parametrize("opts", [{"cu_max_wg": 1}, {"cu_max_wg": 8}, {"cu_max_wg": 100},
+                                  {"cu_wg_per_cu": 1}, {"cu_wg_per_cu": 8}])
+def test_capped_grid_strides_over_descriptors_and_tiles(vccl, opts):
+    """A grid smaller than the tile count (the co-run study caps it) still copies everything."""
+    torch = require_gpu()
+    lay = wl.random_layout(555, 6, 400000, align=1, zero_fraction=0.2)
+    send_np = [wl.payload_bytes(13, s, int(lay["send_sizes"][s])) for s in range(6)]
+    _with_options(vccl, opts, lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CU))
+    lay = wl.random_layout(556, 12, 30000, align=16, zero_fraction=0.0)    # 144 descriptors: table path
+    send_np = [wl.payload_bytes(14, s, int(lay["send_sizes"][s])) for s in range(12)]
+    _with_options(vccl, opts, lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CU))
 
 
 @pytest.mark.parametrize("unroll", [1, 2, 4, 8, 16])
@@ -164,13 +212,8 @@ def test_copy_kernel_variants(vccl, unroll, nt):
     torch = require_gpu()
     lay = wl.random_layout(31, 4, 500000, align=1)
     send_np = [wl.payload_bytes(32, s, int(lay["send_sizes"][s])) for s in range(4)]
-    vccl.vccl_set_option("cu_unroll", unroll)
-    vccl.vccl_set_option("cu_nontemporal", nt)
-    try:
-        _run_v(torch, vccl, lay, send_np, vccl.MODE_CU)
-    finally:
-        vccl.vccl_set_option("cu_unroll", 8)
-        vccl.vccl_set_option("cu_nontemporal", 1)
+    _with_options(vccl, {"cu_unroll": unroll, "cu_nontemporal": nt},
+                  lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CU))
 
 
 @pytest.mark.parametrize("mode", MODES)
