@@ -118,6 +118,56 @@ def cpu_baseline(P, c, budget_s=12.0):
             "single_core_GBps": gb / single}
 
 
+def headline(torch, v, a2a_cu, args, algo_bytes, P, c, send, recv):
+    """The timed region of the benchmark: K AlltoAll calls on the compute-unit path."""
+    wall, per = time_calls(torch, a2a_cu, args.steps, args.warmup)
+    ms_per_step = wall / args.steps * 1e3
+    value = algo_bytes / (wall / args.steps) / 1e9
+    kern = statistics.mean(per)
+    achieved = algo_bytes / kern / 1e9
+    out = {
+        "metric": "AlltoAll(v) achieved GB/s (R+W) vs HBM peak; co-run compute slowdown %",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "AlltoAll P=8 virtual ranks, 16 MiB per peer (1 GiB sent), "
+                               "bf16 payload as random 16-bit patterns, compute-unit copy path",
+                   "P": P, "bytes_per_peer": c, "mode": "cu",
+                   "cu_unroll": int(v.vccl_get_option("cu_unroll")),
+                   "cu_wg_per_cu": int(v.vccl_get_option("cu_wg_per_cu"))},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(),
+                     "kernel": "copy_aligned_kernel", "kernel_us": kern * 1e6,
+                     "algorithmic_bytes": algo_bytes},
+        "frac_of_hbm_peak": value / HBM_PEAK_GBS,
+    }
+    # correctness spot check of what was just timed: block s of recv[r] is block r of send[s]
+    for r, s in ((0, 7), (5, 2)):
+        assert torch.equal(recv[r][s * c:(s + 1) * c], send[s][r * c:(r + 1) * c])
+    return out, kern
+
+
+def measured_traffic():
+    """HBM bytes per launch of the headline kernel from the committed counter
+    summary (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size); None
+    when there is no summary or the kernel source has changed since it was taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "copy_aligned_kernel_alltoall_p8_16MiB_pmc.txt")
+    src = os.path.join(ROOT, "paper_2510_00991_amd", "csrc", "copy_kernel.hip")
+    try:
+        fields = {}
+        for line in open(path):
+            if ":" in line:
+                k, val = line.split(":", 1)
+                fields[k.strip()] = val.strip()
+        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
+        if fields.get("kernel_source_sha256") != digest:
+            return None
+        return float(fields["traffic_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -164,30 +214,11 @@ def main():
         def a2a_ce():
             v.vccl_alltoall(send, recv, c, P, v.MODE_CE, st)
 
-        wall, per = time_calls(torch, a2a_cu, args.steps, args.warmup)
-        ms_per_step = wall / args.steps * 1e3
-        value = algo_bytes / (wall / args.steps) / 1e9
-        kern = statistics.mean(per)
-        achieved = algo_bytes / kern / 1e9
-        out = {
-            "metric": "AlltoAll(v) achieved GB/s (R+W) vs HBM peak; co-run compute slowdown %",
-            "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-            "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-            "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-            "config": {"workload": "AlltoAll P=8 virtual ranks, 16 MiB per peer (1 GiB sent), "
-                                   "bf16 payload as random 16-bit patterns, compute-unit copy path",
-                       "P": P, "bytes_per_peer": c, "mode": "cu",
-                       "cu_unroll": int(v.vccl_get_option("cu_unroll")),
-                       "cu_wg_per_cu": int(v.vccl_get_option("cu_wg_per_cu"))},
-            "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                         "kernel": "copy_segments_kernel", "kernel_us": kern * 1e6,
-                         "algorithmic_bytes": algo_bytes},
-            "frac_of_hbm_peak": value / HBM_PEAK_GBS,
-        }
-        # correctness spot check of what was just timed: block s of recv[r] is block r of send[s]
-        for r, s in ((0, 7), (5, 2)):
-            assert torch.equal(recv[r][s * c:(s + 1) * c], send[s][r * c:(r + 1) * c])
+        if "cu" not in legs:      # profiling runs that isolate another leg
+            out = {"metric": None, "value": None, "note": "headline leg skipped (--legs)"}
+            kern = 350e-6
+        else:
+            out, kern = headline(torch, v, a2a_cu, args, algo_bytes, P, c, send, recv)
 
         if "calib" in legs:
             a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
