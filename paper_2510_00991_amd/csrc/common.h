@@ -43,7 +43,7 @@ struct Options {
     int check = 0;
     uint64_t fifo_chunk_bytes = 512u << 10;
     int fifo_slots = 8;
-    int fifo_wg_per_conn = 16;
+    int fifo_wg_per_conn = 8;
     uint64_t fifo_spin_limit = 1ull << 24;
 };
 

@@ -45,16 +45,17 @@ __device__ __forceinline__ void copy_range(const uint8_t *from, uint8_t *to, uin
         const uint64_t nv = n >> 4;
         const u32x4 *sv = reinterpret_cast<const u32x4 *>(s);
         u32x4 *dv = reinterpret_cast<u32x4 *>(d);
+        // Streaming stores: the data is not read again by this workgroup, and little
+        // dirty data in L2 keeps the write-back of the release cheap.
         uint64_t i = threadIdx.x;
-        for (; i + 3 * kFifoThreads < nv; i += 4 * kFifoThreads) {
-            const u32x4 r0 = sv[i], r1 = sv[i + kFifoThreads], r2 = sv[i + 2 * kFifoThreads],
-                        r3 = sv[i + 3 * kFifoThreads];
-            dv[i] = r0;
-            dv[i + kFifoThreads] = r1;
-            dv[i + 2 * kFifoThreads] = r2;
-            dv[i + 3 * kFifoThreads] = r3;
+        for (; i + 7 * kFifoThreads < nv; i += 8 * kFifoThreads) {
+            u32x4 r[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) r[u] = sv[i + u * kFifoThreads];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) __builtin_nontemporal_store(r[u], dv + i + u * kFifoThreads);
         }
-        for (; i < nv; i += kFifoThreads) dv[i] = sv[i];
+        for (; i < nv; i += kFifoThreads) __builtin_nontemporal_store(sv[i], dv + i);
         for (uint64_t t = (nv << 4) + threadIdx.x; t < n; t += kFifoThreads) d[t] = s[t];
     } else {
         for (uint64_t t = threadIdx.x; t < n; t += kFifoThreads) d[t] = s[t];
@@ -85,20 +86,22 @@ __global__ __launch_bounds__(kFifoThreads) void fifo_sendrecv_kernel(FifoArgs a)
         if (threadIdx.x == 0) {
             uint64_t polls = 0;
             if (side == 0) {
-                while (k - __hip_atomic_load(tail, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= a.nslots) {
+                // Slot reuse carries no data back to the sender: a relaxed read is enough.
+                while (k - __hip_atomic_load(tail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= a.nslots) {
                     if (++polls > a.spin_limit || __hip_atomic_load(a.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
                         give_up = 1;
                         break;
                     }
-                    __builtin_amdgcn_s_sleep(8);
+                    __builtin_amdgcn_s_sleep(4);
                 }
             } else {
+                // Acquire: invalidates this compute unit's view of the slot before it is read.
                 while (__hip_atomic_load(head, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) <= k) {
                     if (++polls > a.spin_limit || __hip_atomic_load(a.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
                         give_up = 1;
                         break;
                     }
-                    __builtin_amdgcn_s_sleep(8);
+                    __builtin_amdgcn_s_sleep(4);
                 }
             }
         }
@@ -107,13 +110,18 @@ __global__ __launch_bounds__(kFifoThreads) void fifo_sendrecv_kernel(FifoArgs a)
             if (threadIdx.x == 0) __hip_atomic_store(a.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return;
         }
-        __threadfence();   // what the other side wrote before publishing is visible now
         if (side == 0) copy_range(c.src + off, slot, b0, b1);
         else copy_range(slot, c.dst + off, b0, b1);
-        __threadfence();   // this lane's stores are out before the counter moves
+        // Every lane waits for its own loads and stores to finish, the workgroup meets,
+        // then one lane moves the counter.  The sender's release writes the slot data
+        // back so that a receiver on another XCD sees it; the receiver only has to have
+        // finished reading the slot, so its counter store is relaxed.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (threadIdx.x == 0)
-            __hip_atomic_store(side == 0 ? head : tail, k + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        if (threadIdx.x == 0) {
+            if (side == 0) __hip_atomic_store(head, k + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            else __hip_atomic_store(tail, k + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 

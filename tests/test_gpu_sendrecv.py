@@ -98,7 +98,7 @@ def test_staged_equals_oracle_fifo_model(vccl):
         finally:
             vccl.vccl_set_option("fifo_chunk_bytes", 524288)
             vccl.vccl_set_option("fifo_slots", 8)
-            vccl.vccl_set_option("fifo_wg_per_conn", 16)
+            vccl.vccl_set_option("fifo_wg_per_conn", 8)
 
 
 def test_ce_handshake_record_advances(vccl):
