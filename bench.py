@@ -24,70 +24,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+from paper_2510_00991_amd.harness import time_calls  # noqa: E402  (event timing helper)
+
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
-
-
-def _events(torch, n):
-    return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-            for _ in range(n)]
-
-
-def time_calls(torch, fn, steps, warmup):
-    """Wall time of `steps` back-to-back calls plus per-call device durations
-    from events recorded on the stream the library launches on."""
-    for _ in range(warmup):
-        fn()
-    torch.cuda.synchronize()
-    ev = _events(torch, steps)
-    t0 = time.perf_counter()
-    for a, b in ev:
-        a.record()
-        fn()
-        b.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    per = [a.elapsed_time(b) * 1e-3 for a, b in ev]
-    return wall, per
-
-
-def corun_slowdown(torch, v, comm_fn, comm_stream, fma_out, iters, reps, n_comm):
-    """Median FMA-probe time with `comm_fn` looping on another stream, and alone."""
-    comp = torch.cuda.Stream()
-    st = int(comp.cuda_stream)
-
-    def probe_alone():
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        with torch.cuda.stream(comp):
-            a.record()
-            v.vccl_fma_probe(fma_out, 0, 256, iters, st)
-            b.record()
-        comp.synchronize()
-        return a.elapsed_time(b) * 1e-3
-
-    for _ in range(3):
-        probe_alone()
-    alone = [probe_alone() for _ in range(reps)]
-    both, comm_bytes_time = [], []
-    for _ in range(reps):
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        with torch.cuda.stream(comm_stream):
-            c0.record()
-            for _ in range(n_comm):
-                comm_fn()
-            c1.record()
-        with torch.cuda.stream(comp):
-            a.record()
-            v.vccl_fma_probe(fma_out, 0, 256, iters, st)
-            b.record()
-        torch.cuda.synchronize()
-        both.append(a.elapsed_time(b) * 1e-3)
-        comm_bytes_time.append(c0.elapsed_time(c1) * 1e-3)
-    t0 = statistics.median(alone)
-    t1 = statistics.median(both)
-    return {"alone_ms": t0 * 1e3, "corun_ms": t1 * 1e3, "slowdown_pct": 100.0 * (t1 - t0) / t0,
-            "comm_ms": statistics.median(comm_bytes_time) * 1e3}
 
 
 def cpu_baseline(P, c, budget_s=12.0):
@@ -192,6 +131,7 @@ def main():
 
     import paper_2510_00991_amd as v
     import workloads as wl
+    from paper_2510_00991_amd.harness import CoRun
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -234,19 +174,23 @@ def main():
                                   "streams": int(v.vccl_get_option("ce_streams")),
                                   "kind": v.vccl_get_option("ce_kind")}
         if "corun" in legs:
-            # co-run: FMA probe alone vs beside each path
-            cu = v.vccl_device_cu_count()
-            fma_out = torch.zeros(cu * 256, dtype=torch.float32, device="cuda")
-            comm = torch.cuda.Stream()
-            cst = int(comm.cuda_stream)
-            iters = 60000
-            n_cu = max(2, int(0.004 / kern) + 2)
-            cor_cu = corun_slowdown(torch, v, lambda: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, cst),
-                                    comm, fma_out, iters, 15, n_cu)
-            cor_ce = corun_slowdown(torch, v, lambda: v.vccl_alltoall(send, recv, c, P, v.MODE_CE, cst),
-                                    comm, fma_out, iters, 15, 1)
-            out["corun"] = {"probe": f"FMA kernel, {cu} workgroups x 256 threads, {iters} rounds",
-                            "cu_path": cor_cu, "copy_engine_path": cor_ce}
+            # co-run: FMA probe alone vs beside each path (protocol in harness.CoRun)
+            co = CoRun(torch)
+            cor_cu = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes, kern)
+            # the same path with its grid capped to one workgroup per compute unit
+            v.vccl_set_option("cu_max_wg", co.cu)
+            v.vccl_set_option("cu_unroll", 8)
+            wcap, _ = time_calls(torch, a2a_cu, 5, 2)
+            cor_cap = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes, wcap / 5)
+            cor_cap["GBps_alone"] = algo_bytes / (wcap / 5) / 1e9
+            v.vccl_set_option("cu_max_wg", 0)
+            v.vccl_set_option("cu_unroll", 1)
+            wce, _ = time_calls(torch, a2a_ce, 3, 1)
+            cor_ce = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CE, sh), algo_bytes, wce / 3)
+            out["corun"] = {"probe": f"FMA kernel, {co.cu} workgroups x {co.threads} threads, "
+                                     f"{co.iters} rounds of 64 FMAs per lane",
+                            "cu_path": cor_cu, "cu_path_capped_1wg_per_cu": cor_cap,
+                            "copy_engine_path": cor_ce}
         if "sendrecv" in legs:
             # SendRecv ring, 8 stages x 64 MiB
             n = 64 << 20

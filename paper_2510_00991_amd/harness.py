@@ -1,0 +1,221 @@
+"""Measurement harness around the C boundary: event timing, the co-run slowdown
+protocol (a compute-bound FMA kernel timed alone and beside a transfer, the
+effect the paper describes in Appendix E), the pipeline SendRecv ring and the
+P = 64 message-size sweep.  PyTorch is used for device memory, streams and
+events only; every byte is moved by libvccl.
+
+CLI:  python -m paper_2510_00991_amd.harness ring|sweep|all  [--json FILE]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import statistics
+import sys
+import time
+
+from . import binding as v
+
+
+def _ev(torch):
+    return torch.cuda.Event(enable_timing=True)
+
+
+def time_calls(torch, fn, steps, warmup):
+    """(wall seconds for `steps` back-to-back calls, per-call device seconds from
+    events recorded on the current stream around each call)."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = [(_ev(torch), _ev(torch)) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, [a.elapsed_time(b) * 1e-3 for a, b in ev]
+
+
+class CoRun:
+    """FMA probe on its own stream, timed alone and while `comm_fn` keeps another
+    stream busy.  slowdown = (T_with - T_alone) / T_alone."""
+
+    def __init__(self, torch, iters=60000, threads=256, workgroups=0):
+        self.torch = torch
+        self.iters, self.threads, self.workgroups = iters, threads, workgroups
+        self.cu = v.vccl_device_cu_count()
+        n = (workgroups or self.cu) * threads
+        self.out = torch.zeros(n, dtype=torch.float32, device="cuda")
+        self.comp = torch.cuda.Stream()
+        self.comm = torch.cuda.Stream()
+        self._alone = None
+
+    def comm_stream_handle(self) -> int:
+        return int(self.comm.cuda_stream)
+
+    def _probe(self):
+        torch = self.torch
+        a, b = _ev(torch), _ev(torch)
+        with torch.cuda.stream(self.comp):
+            a.record()
+            v.vccl_fma_probe(self.out, self.workgroups, self.threads, self.iters,
+                             int(self.comp.cuda_stream))
+            b.record()
+        return a, b
+
+    def _time_alone(self):
+        a, b = self._probe()
+        self.comp.synchronize()
+        return a.elapsed_time(b) * 1e-3
+
+    def alone(self, reps=20):
+        if self._alone is None:
+            for _ in range(3):
+                self._time_alone()
+            self._alone = statistics.median(self._time_alone() for _ in range(reps))
+        return self._alone
+
+    def beside(self, comm_fn, comm_bytes_per_call, comm_seconds_per_call, reps=12):
+        """comm_fn(stream_handle) enqueues one transfer on the given stream.  Each
+        repetition times the probe alone and then beside the transfer, so slow drifts
+        of the clocks cancel; the medians of both series are reported."""
+        torch = self.torch
+        t_guess = self.alone()
+        n_comm = max(1, int(1.25 * t_guess / max(comm_seconds_per_call, 1e-6)) + 1)
+        sh = self.comm_stream_handle()
+        alone, both, comm_t = [], [], []
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            alone.append(self._time_alone())
+            c0, c1 = _ev(torch), _ev(torch)
+            with torch.cuda.stream(self.comm):
+                c0.record()
+                for _ in range(n_comm):
+                    comm_fn(sh)
+                c1.record()
+            a, b = self._probe()
+            torch.cuda.synchronize()
+            both.append(a.elapsed_time(b) * 1e-3)
+            comm_t.append(c0.elapsed_time(c1) * 1e-3)
+        t_alone = statistics.median(alone)
+        t_with = statistics.median(both)
+        tc = statistics.median(comm_t)
+        return {"alone_ms": t_alone * 1e3, "corun_ms": t_with * 1e3,
+                "slowdown_pct": 100.0 * (t_with - t_alone) / t_alone,
+                "comm_calls": n_comm, "comm_ms": tc * 1e3,
+                "comm_GBps_while_corunning": comm_bytes_per_call * n_comm / tc / 1e9}
+
+
+def _set(opts):
+    saved = {k: v.vccl_get_option(k) for k in opts}
+    for k, val in opts.items():
+        v.vccl_set_option(k, val)
+    return saved
+
+
+def ring_corun(torch, P=8, nbytes=64 << 20, cu_grids=(8, 16, 32, 64, 256), steps=5):
+    """Pipeline SendRecv ring (P stages, one activation per stage) in every mode:
+    copy GB/s alone, and the FMA probe's slowdown beside it; for the direct
+    compute-unit mode also over a capped copy grid."""
+    import workloads as wl   # seeded inputs
+
+    send = [torch.from_numpy(wl.normal_bf16_bits(wl.config_seed(4), s, nbytes // 2).view("uint8")).cuda()
+            for s in range(P)]
+    recv = [torch.zeros(nbytes, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    to, frm = wl.ring_peers(P)
+    st = int(torch.cuda.current_stream().cuda_stream)
+    co = CoRun(torch)
+    rows = []
+
+    def run(name, mode, algo_factor, opts=None):
+        saved = _set(opts or {})
+        try:
+            fn = lambda s=st: v.vccl_sendrecv(send, [nbytes] * P, to, recv, [nbytes] * P, frm, P, mode, s)
+            wall, _ = time_calls(torch, fn, steps, 2)
+            per = wall / steps
+            moved = 2.0 * P * nbytes
+            row = {"mode": name, "ms": per * 1e3, "GBps_effective": moved / per / 1e9,
+                   "GBps_algorithmic": algo_factor * moved / per / 1e9}
+            row.update(co.beside(lambda s: v.vccl_sendrecv(send, [nbytes] * P, to, recv, [nbytes] * P,
+                                                           frm, P, mode, s), moved, per))
+            if mode == v.MODE_CU_STAGED:
+                v.vccl_sendrecv_staged_status()
+            rows.append(row)
+        finally:
+            _set(saved)
+
+    run("cu_direct", v.MODE_CU, 1.0)
+    for g in cu_grids:
+        run(f"cu_direct_grid{g}", v.MODE_CU, 1.0, {"cu_max_wg": g, "cu_unroll": 8})
+    run("cu_staged_fifo", v.MODE_CU_STAGED, 2.0)
+    run("copy_engine", v.MODE_CE, 1.0)
+    return {"workload": f"SendRecv ring, {P} stages x {nbytes >> 20} MiB, FMA probe on all CUs",
+            "probe": {"workgroups": co.cu, "threads": co.threads, "iters": co.iters}, "rows": rows}
+
+
+def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 << 30):
+    """AlltoAll over P virtual ranks for per-peer sizes 4 KiB .. 4 MiB: both paths'
+    bandwidth and the probe's slowdown beside each."""
+    import workloads as wl
+
+    sizes = sizes or [4096 << k for k in range(11)]
+    co = CoRun(torch) if with_corun else None
+    st = int(torch.cuda.current_stream().cuda_stream)
+    rows = []
+    for c in sizes:
+        if P * P * c > max_bytes_per_side:
+            continue
+        send = [torch.empty(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
+        recv = [torch.empty(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
+        for s in range(P):     # seeded payload, first 1 MiB of each buffer (timing does not depend on values)
+            n = min(P * c, 1 << 20)
+            send[s][:n].copy_(torch.from_numpy(wl.payload_bytes(wl.config_seed(5), s, n)))
+        moved = 2.0 * P * P * c
+        row = {"bytes_per_peer": c, "total_sent_MiB": P * P * c / (1 << 20)}
+        for name, mode in (("cu", v.MODE_CU), ("ce", v.MODE_CE)):
+            fn = lambda s=st, m=mode: v.vccl_alltoall(send, recv, c, P, m, s)
+            k = 10 if name == "cu" else 3
+            wall, per = time_calls(torch, fn, k, 2)
+            t = wall / k
+            row[name] = {"us": t * 1e6, "GBps": moved / t / 1e9}
+            if co is not None:
+                row[name].update(co.beside(lambda s, m=mode: v.vccl_alltoall(send, recv, c, P, m, s),
+                                           moved, t, reps=6))
+        rows.append(row)
+        del send, recv
+        torch.cuda.empty_cache()
+    return {"workload": f"AlltoAll sweep, P={P}, per-peer 4 KiB..4 MiB", "rows": rows}
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("what", choices=["ring", "sweep", "all"])
+    ap.add_argument("--json", default=None)
+    ap.add_argument("--no-corun", action="store_true")
+    args = ap.parse_args(argv)
+    import torch
+    if not torch.cuda.is_available():
+        print("harness: no GPU visible", file=sys.stderr)
+        return 1
+    torch.cuda.set_device(0)
+    v.vccl_init(0, 64)
+    out = {}
+    try:
+        if args.what in ("ring", "all"):
+            out["ring"] = ring_corun(torch)
+            print(json.dumps(out["ring"]), flush=True)
+        if args.what in ("sweep", "all"):
+            out["sweep"] = sweep_p64(torch, with_corun=not args.no_corun)
+            print(json.dumps(out["sweep"]), flush=True)
+    finally:
+        v.vccl_finalize()
+    if args.json:
+        with open(args.json, "w") as f:
+            json.dump(out, f, indent=1)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
