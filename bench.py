@@ -171,8 +171,8 @@ def main():
             wall_ce, per_ce = time_calls(torch, a2a_ce, k_ce, 2)
             out["copy_engine"] = {"GBps": algo_bytes / (wall_ce / k_ce) / 1e9,
                                   "ms_per_step": wall_ce / k_ce * 1e3, "steps": k_ce,
-                                  "streams": int(v.vccl_get_option("ce_streams")),
-                                  "kind": v.vccl_get_option("ce_kind")}
+                                  "kind": v.vccl_get_option("ce_kind"),
+                                  "engines": int(v.vccl_get_option("ce_engines"))}
         if "corun" in legs:
             # co-run: FMA probe alone vs beside each path (protocol in harness.CoRun)
             co = CoRun(torch)

@@ -10,9 +10,10 @@
  * Two data paths exist for every primitive:
  *   VCCL_MODE_CU  a compute-unit copy kernel on the caller's stream (the kind of
  *                 SM-consuming P2P kernel the paper sets out to remove, Section 2.2);
- *   VCCL_MODE_CE  copy engines driven by a host proxy thread, with no kernel
- *                 launched and stream order kept by events (the paper's SM-free
- *                 P2P, Section 3.2 items 1-3).
+ *   VCCL_MODE_CE  SDMA copy engines driven by a host proxy thread: no kernel is
+ *                 launched, no compute unit is used, and stream order is kept by
+ *                 stream write/wait-value operations (the paper's SM-free P2P,
+ *                 Section 3.2 items 1-3).
  *
  * Conventions
  *   - Every pointer named *_dev / every element of a buffer-pointer array is a
@@ -86,8 +87,12 @@ const char *vccl_last_error(void);
  *                        workgroups per compute unit),
  *       "cu_max_wg" (cap on the copy grid, 0 = none; the co-run study sweeps it),
  *       "cu_nontemporal" (0/1), "cu_fast_path" (0/1: allow the all-aligned kernel),
- *       "ce_streams" (1..8 internal copy streams),
- *       "ce_kind" ("nocu" | "default": hipMemcpyKind of copy-engine copies),
+ *       "ce_kind" (copy-engine back end: "sdma" = SDMA engines driven
+ *       through the HSA runtime with stream write/wait-value ordering, the default when the
+ *       device supports it; "hip_nocu" / "hip_default" = hipMemcpyAsync on internal streams
+ *       with event ordering, kind hipMemcpyDeviceToDeviceNoCU / hipMemcpyDeviceToDevice),
+ *       "ce_streams" (1..8 internal streams of the hip_* back ends),
+ *       "ce_engines" (read-only: SDMA engines in use),
  *       "check" (0/1 overlap validation),
  *       "fifo_chunk_bytes", "fifo_slots", "fifo_wg_per_conn",
  *       "fifo_spin_limit" (polls before a staged wait gives up).

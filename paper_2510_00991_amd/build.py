@@ -44,7 +44,7 @@ def build(verbose: bool = True) -> str:
     if failed:
         raise RuntimeError("libvccl build failed")
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
-                          + ["-lpthread"])
+                          + ["-lpthread", "-L/opt/rocm/lib", "-lhsa-runtime64"])
     return LIB
 
 

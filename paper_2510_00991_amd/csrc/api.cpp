@@ -237,6 +237,9 @@ int vccl_init(int device, int max_ranks) {
         c->ring.destroy();
         return fail(VCCL_ERR_HIP, "could not create the copy-engine proxy (streams)");
     }
+    // Default copy-engine back end: SDMA engines through the HSA runtime when the
+    // device supports stream wait-value operations, else hipMemcpyAsync(NoCU).
+    c->opt.ce_kind = proxy_sdma_available(c->proxy, nullptr) ? VCCL_CE_SDMA : VCCL_CE_HIP_NOCU;
     g_ctx = c;
     return VCCL_OK;
 }
@@ -281,11 +284,17 @@ int vccl_set_option(const char *key, const char *value) {
     Options &o = c->opt;
     const std::string k(key);
     if (k == "ce_kind") {
-        if (!strcmp(value, "nocu")) o.ce_kind_nocu = 1;
-        else if (!strcmp(value, "default")) o.ce_kind_nocu = 0;
-        else return fail(VCCL_ERR_ARG, "ce_kind must be 'nocu' or 'default', got '%s'", value);
+        if (!strcmp(value, "sdma")) {
+            const char *why = "";
+            if (!proxy_sdma_available(c->proxy, &why))
+                return fail(VCCL_ERR_UNSUPPORTED, "ce_kind 'sdma' is not available: %s", why);
+            o.ce_kind = VCCL_CE_SDMA;
+        } else if (!strcmp(value, "hip_nocu")) o.ce_kind = VCCL_CE_HIP_NOCU;
+        else if (!strcmp(value, "hip_default")) o.ce_kind = VCCL_CE_HIP_DEFAULT;
+        else return fail(VCCL_ERR_ARG, "ce_kind must be 'sdma', 'hip_nocu' or 'hip_default', got '%s'", value);
         return VCCL_OK;
     }
+    if (k == "ce_engines") return fail(VCCL_ERR_ARG, "ce_engines is read-only");
     uint64_t x = 0;
     if (!parse_u64(value, &x)) return fail(VCCL_ERR_ARG, "option %s: '%s' is not a number", key, value);
     auto in = [&](uint64_t lo, uint64_t hi) { return x >= lo && x <= hi; };
@@ -338,9 +347,11 @@ int vccl_get_option(const char *key, char *out, int cap) {
     const std::string k(key);
     unsigned long long v;
     if (k == "ce_kind") {
-        snprintf(out, (size_t)cap, "%s", o.ce_kind_nocu ? "nocu" : "default");
+        snprintf(out, (size_t)cap, "%s", o.ce_kind == VCCL_CE_SDMA ? "sdma"
+                                         : o.ce_kind == VCCL_CE_HIP_NOCU ? "hip_nocu" : "hip_default");
         return VCCL_OK;
-    } else if (k == "cu_unroll") v = o.cu_unroll;
+    } else if (k == "ce_engines") v = (unsigned long long)proxy_engine_count(c->proxy);
+    else if (k == "cu_unroll") v = o.cu_unroll;
     else if (k == "cu_wg_per_cu") v = o.cu_wg_per_cu;
     else if (k == "cu_max_wg") v = o.cu_max_wg;
     else if (k == "cu_nontemporal") v = o.cu_nontemporal;

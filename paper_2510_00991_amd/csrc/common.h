@@ -29,6 +29,9 @@ struct Seg {
 };
 static_assert(sizeof(Seg) == 32, "descriptor layout");
 
+// copy-engine back ends
+enum { VCCL_CE_SDMA = 0, VCCL_CE_HIP_NOCU = 1, VCCL_CE_HIP_DEFAULT = 2 };
+
 constexpr int kInlineSegs = 64;     // descriptors carried in the kernel arguments
 constexpr int kCopyThreads = 256;   // 4 wavefronts per workgroup
 
@@ -39,7 +42,7 @@ struct Options {
     int cu_nontemporal = 1;
     int cu_fast_path = 1;
     int ce_streams = 4;
-    int ce_kind_nocu = 1;
+    int ce_kind = 0;   // VCCL_CE_*
     int check = 0;
     uint64_t fifo_chunk_bytes = 512u << 10;
     int fifo_slots = 8;
@@ -156,6 +159,10 @@ int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hip
 int proxy_reginfo(Proxy *p, int receiver, uint64_t *ready, uint64_t *started, uint64_t *done,
                   void **addr);
 int proxy_drain(Proxy *p);
+// Whether the HSA/SDMA back end came up on this device (and, if not, why).
+bool proxy_sdma_available(Proxy *p, const char **why);
+int proxy_engine_count(Proxy *p);
+uint64_t proxy_sdma_errors(Proxy *p);
 void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t *issue_ns);
 
 }  // namespace vccl

@@ -1,23 +1,39 @@
-// Copy-engine path: a host proxy thread issues device-to-device copies on
-// internal streams so that no kernel is launched for the transfer (the paper's
-// SM-free P2P: data movement by copy engines, Section 3.2 item 1; control on the
-// CPU with completion polled by event query, Section 3.2 items 1-2).
+// Copy-engine path: a host proxy thread moves the data with the GPU's SDMA copy
+// engines so that no kernel is launched for the transfer and no compute unit is
+// touched (the paper's SM-free P2P: data movement by copy engines, control on a
+// CPU proxy thread with completion found by polling, Section 3.2 items 1-2).
 //
-// Stream order (Section 3.2 item 3) is kept with events only - no spin kernel and
-// no host callback (the host-function variant can deadlock because callbacks of
-// independent streams may be serialised):
-//   caller:  record `ready` on its stream -> hand the op to the proxy
-//   proxy:   every internal stream waits on `ready`, copies are issued, `done[i]`
-//            is recorded behind them
-//   caller:  its stream waits on every `done[i]`, then the call returns.
-// The host blocks only for the microseconds the proxy needs to enqueue the batch.
+// Two back ends:
+//
+//  "sdma" (default)  The proxy submits every copy straight to an SDMA engine
+//      through the HSA runtime, rotating over the engines, and stream order is
+//      kept with stream memory operations exactly as the paper ends up doing
+//      (Section 3.2 item 3): the caller's stream WRITES a sequence number into a
+//      host-visible ready word when the preceding work is done (the paper's
+//      proxyReadyEvent), the proxy polls that word, issues the copies, polls their
+//      completion signal, and then stores the sequence number into a signal word
+//      the caller's stream WAITS on (the role of proxyOpCount returning to zero).
+//      No kernel, no host callback, and the calling thread never blocks.
+//
+//  "hip_nocu" / "hip_default"  hipMemcpyAsync on internal streams, ordered with
+//      events (record `ready`, internal streams wait, record `done[i]`, caller's
+//      stream waits).  Whether hipMemcpyDeviceToDeviceNoCU really avoids compute
+//      units depends on the HIP runtime that is loaded, so this is not the default.
+//
+// hipLaunchHostFunc is never used: host callbacks of independent streams may be
+// serialised, which is the deadlock the paper describes.
 //
 // For SendRecv each connection also walks the receiver-owned handshake record of
 // Section 3.2 (receiverRegAddr / receiverReady -> copyStarted -> copyDone).  The
 // paper's 1-bit flags are kept here as monotonically increasing sequence numbers,
 // which need no reset between operations.
+#include <hsa/hsa.h>
+#include <hsa/hsa_ext_amd.h>
+
 #include <chrono>
 #include <condition_variable>
+#include <cstdlib>
+#include <cstring>
 #include <deque>
 #include <thread>
 
@@ -27,6 +43,8 @@ namespace vccl {
 
 namespace {
 constexpr int kMaxStreams = 8;
+constexpr int kMaxEngines = 16;
+constexpr uint64_t kMinPiece = 1u << 20;   // large copies are cut no finer than this
 
 struct RegInfo {  // one per receiving rank
     std::atomic<void *> receiverRegAddr{nullptr};
@@ -38,14 +56,21 @@ struct RegInfo {  // one per receiving rank
 struct Op {
     std::vector<CeCopy> copies;
     std::vector<std::pair<int, uint64_t>> conns;  // (receiver rank, sequence number)
+    int kind = VCCL_CE_SDMA;
+    // event back end
     hipEvent_t ready = nullptr;
     hipEvent_t done[kMaxStreams] = {};
-    int nstreams = 0;          // streams this op used
+    int nstreams = 0;
     int want_streams = 1;
-    bool nocu = true;
     int state = 0;             // 0 queued, 1 issued, 2 failed   (guarded by Proxy::mu)
     hipError_t err = hipSuccess;
     int refs = 0;              // caller + proxy                 (guarded by Proxy::mu)
+    // sdma back end
+    volatile uint64_t *ready_word = nullptr;   // pinned host memory, written by the caller's stream
+    uint64_t *done_word = nullptr;             // signal memory, waited on by the caller's stream
+    hsa_signal_t left = {0};                   // outstanding copies
+    uint64_t seq = 0;
+    bool sdma_failed = false;
 };
 }  // namespace
 
@@ -58,19 +83,118 @@ public:
     std::mutex mu, handshake_mu;
     std::condition_variable cv_work, cv_issued, cv_idle;
     std::deque<Op *> queue;
-    std::vector<Op *> pending;   // issued, completion not yet observed (proxy thread only)
+    std::vector<Op *> waiting;   // sdma ops whose ready word has not arrived (proxy thread only)
+    std::vector<Op *> pending;   // issued, completion not yet observed   (proxy thread only)
     std::vector<Op *> free_ops;
     bool stop = false;
-    size_t in_flight = 0;        // queued + pending
+    size_t in_flight = 0;        // queued + waiting + pending
     RegInfo reg[VCCL_MAX_RANKS];
-    std::atomic<uint64_t> n_ops{0}, n_copies{0}, n_bytes{0}, issue_ns{0};
+    std::atomic<uint64_t> n_ops{0}, n_copies{0}, n_bytes{0}, issue_ns{0}, sdma_errors{0};
+    // sdma back end
+    bool sdma_ok = false;
+    std::string sdma_why;
+    hsa_agent_t agent = {0};
+    bool hsa_up = false;
+    uint32_t engine_bit[kMaxEngines] = {};
+    int nengines = 0;
+    unsigned next_engine = 0;
+    void *warm = nullptr;
 
     void run();
-    void issue(Op *op);
+    void issue_events(Op *op);
+    bool issue_sdma(Op *op);
     void poll();
+    void finish(Op *op);
     Op *get_op();
     void put_ref(Op *op);
+    void setup_sdma();
+    std::vector<CeCopy> expand(const Op *op, size_t lanes);
 };
+
+// ------------------------------------------------------------------ set-up ---
+namespace {
+struct AgentSearch {
+    uint32_t want_bdf;
+    uint32_t want_domain;
+    hsa_agent_t match, first_gpu;
+    bool have_match = false;
+    int ngpu = 0;
+};
+
+hsa_status_t agent_cb(hsa_agent_t a, void *data) {
+    AgentSearch *s = static_cast<AgentSearch *>(data);
+    hsa_device_type_t t;
+    if (hsa_agent_get_info(a, HSA_AGENT_INFO_DEVICE, &t) != HSA_STATUS_SUCCESS) return HSA_STATUS_SUCCESS;
+    if (t != HSA_DEVICE_TYPE_GPU) return HSA_STATUS_SUCCESS;
+    if (s->ngpu++ == 0) s->first_gpu = a;
+    uint32_t bdf = 0, domain = 0;
+    if (hsa_agent_get_info(a, (hsa_agent_info_t)HSA_AMD_AGENT_INFO_BDFID, &bdf) == HSA_STATUS_SUCCESS &&
+        hsa_agent_get_info(a, (hsa_agent_info_t)HSA_AMD_AGENT_INFO_DOMAIN, &domain) == HSA_STATUS_SUCCESS &&
+        bdf == s->want_bdf && domain == s->want_domain) {
+        s->match = a;
+        s->have_match = true;
+    }
+    return HSA_STATUS_SUCCESS;
+}
+}  // namespace
+
+void Proxy::setup_sdma() {
+    int can = 0;
+    if (hipDeviceGetAttribute(&can, hipDeviceAttributeCanUseStreamWaitValue, device) != hipSuccess || !can) {
+        sdma_why = "the device does not support stream wait-value operations";
+        return;
+    }
+    if (hsa_init() != HSA_STATUS_SUCCESS) {
+        sdma_why = "hsa_init failed";
+        return;
+    }
+    hsa_up = true;
+    char bus[64] = {0};
+    AgentSearch s{};
+    unsigned dom = 0, b = 0, d = 0, f = 0;
+    if (hipDeviceGetPCIBusId(bus, sizeof(bus), device) == hipSuccess &&
+        sscanf(bus, "%x:%x:%x.%x", &dom, &b, &d, &f) == 4) {
+        s.want_domain = dom;
+        s.want_bdf = (b << 8) | (d << 3) | f;
+    } else {
+        s.want_bdf = 0xffffffffu;
+    }
+    hsa_iterate_agents(agent_cb, &s);
+    if (s.have_match) agent = s.match;
+    else if (s.ngpu == 1) agent = s.first_gpu;
+    else {
+        sdma_why = "could not identify the HSA agent of the device";
+        return;
+    }
+    if (hipMalloc(&warm, 8192) != hipSuccess) {
+        sdma_why = "could not allocate the engine warm-up buffer";
+        return;
+    }
+    // Try every engine id once with a tiny copy: ids the runtime rejects are left
+    // out, and the first use of an engine (queue creation, milliseconds) is paid here.
+    hsa_signal_t sig;
+    if (hsa_signal_create(1, 0, nullptr, &sig) != HSA_STATUS_SUCCESS) {
+        sdma_why = "hsa_signal_create failed";
+        return;
+    }
+    for (int i = 0; i < kMaxEngines; ++i) {
+        hsa_signal_store_relaxed(sig, 1);
+        hsa_status_t st = hsa_amd_memory_async_copy_on_engine(
+            (char *)warm + 4096, agent, warm, agent, 256, 0, nullptr, sig,
+            (hsa_amd_sdma_engine_id_t)(1u << i), true);
+        if (st != HSA_STATUS_SUCCESS) continue;
+        if (hsa_signal_wait_scacquire(sig, HSA_SIGNAL_CONDITION_LT, 1, 4000000000ull,
+                                      HSA_WAIT_STATE_BLOCKED) >= 1)
+            continue;   // never completed within 4 s: do not use this engine
+        engine_bit[nengines++] = 1u << i;
+    }
+    hsa_signal_destroy(sig);
+    if (nengines == 0) {
+        sdma_why = "no SDMA engine accepted a copy";
+        return;
+    }
+    sdma_ok = true;
+}
 
 Op *Proxy::get_op() {  // mu held
     if (!free_ops.empty()) {
@@ -79,15 +203,19 @@ Op *Proxy::get_op() {  // mu held
         return op;
     }
     Op *op = new Op;
-    if (hipEventCreateWithFlags(&op->ready, hipEventDisableTiming) != hipSuccess) {
+    bool ok = hipEventCreateWithFlags(&op->ready, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; ok && i < kMaxStreams; ++i)
+        ok = hipEventCreateWithFlags(&op->done[i], hipEventDisableTiming) == hipSuccess;
+    if (ok && sdma_ok) {
+        ok = hipHostMalloc((void **)&op->ready_word, 64, hipHostMallocDefault) == hipSuccess;
+        if (ok) *op->ready_word = 0;
+        ok = ok && hipExtMallocWithFlags((void **)&op->done_word, 8, hipMallocSignalMemory) == hipSuccess;
+        if (ok) __atomic_store_n(op->done_word, (uint64_t)0, __ATOMIC_RELEASE);
+        ok = ok && hsa_signal_create(0, 0, nullptr, &op->left) == HSA_STATUS_SUCCESS;
+    }
+    if (!ok) {   // events and words of a half-built op are few and leak only on this error path
         delete op;
         return nullptr;
-    }
-    for (int i = 0; i < kMaxStreams; ++i) {
-        if (hipEventCreateWithFlags(&op->done[i], hipEventDisableTiming) != hipSuccess) {
-            delete op;
-            return nullptr;
-        }
     }
     return op;
 }
@@ -97,18 +225,19 @@ void Proxy::put_ref(Op *op) {  // mu held
         op->copies.clear();
         op->conns.clear();
         op->state = 0;
+        op->sdma_failed = false;
         free_ops.push_back(op);
     }
 }
 
-void Proxy::issue(Op *op) {
-    const auto t0 = std::chrono::steady_clock::now();
+// Few large copies are cut so that every lane (stream or engine) gets a share.
+std::vector<CeCopy> Proxy::expand(const Op *op, size_t lanes) {
     std::vector<CeCopy> work;
-    int ns = op->want_streams < 1 ? 1 : (op->want_streams > max_streams ? max_streams : op->want_streams);
-    // Few large copies: cut them so that every internal stream (engine) gets a share.
+    size_t live = 0;
+    for (const CeCopy &c : op->copies)
+        if (c.bytes) ++live;
     size_t pieces = 1;
-    if (!op->copies.empty() && op->copies.size() < (size_t)ns)
-        pieces = ((size_t)ns + op->copies.size() - 1) / op->copies.size();
+    if (live && live < 2 * lanes) pieces = (2 * lanes + live - 1) / live;
     for (const CeCopy &c : op->copies) {
         if (c.bytes == 0) continue;
         // A SendRecv copy writes to the address the receiver published in its record.
@@ -116,19 +245,29 @@ void Proxy::issue(Op *op) {
             ? (uint8_t *)reg[c.receiver].receiverRegAddr.load(std::memory_order_acquire)
             : (uint8_t *)c.dst;
         size_t k = pieces;
-        if (c.bytes < (uint64_t)(1u << 20) * k) k = 1;
-        uint64_t per = ((c.bytes + k - 1) / k + 255u) & ~(uint64_t)255u;
+        if (c.bytes < kMinPiece * k) k = (size_t)(c.bytes / kMinPiece);
+        if (k < 1) k = 1;
+        const uint64_t per = ((c.bytes + k - 1) / k + 255u) & ~(uint64_t)255u;
         for (uint64_t off = 0; off < c.bytes; off += per) {
             const uint64_t n = c.bytes - off < per ? c.bytes - off : per;
             work.push_back(CeCopy{(const uint8_t *)c.src + off, dst_base + off, n, -1});
         }
     }
+    return work;
+}
+
+// ------------------------------------------------------- event back end ------
+void Proxy::issue_events(Op *op) {
+    const auto t0 = std::chrono::steady_clock::now();
+    int ns = op->want_streams < 1 ? 1 : (op->want_streams > max_streams ? max_streams : op->want_streams);
+    std::vector<CeCopy> work = expand(op, (size_t)ns);
     if ((size_t)ns > work.size()) ns = work.empty() ? 1 : (int)work.size();
     hipError_t err = hipSuccess;
     for (int i = 0; i < ns && err == hipSuccess; ++i) err = hipStreamWaitEvent(streams[i], op->ready, 0);
     for (auto &c : op->conns) reg[c.first].copyStarted.store(c.second, std::memory_order_release);
     uint64_t load[kMaxStreams] = {};
-    const hipMemcpyKind kind = op->nocu ? hipMemcpyDeviceToDeviceNoCU : hipMemcpyDeviceToDevice;
+    const hipMemcpyKind kind =
+        op->kind == VCCL_CE_HIP_NOCU ? hipMemcpyDeviceToDeviceNoCU : hipMemcpyDeviceToDevice;
     uint64_t bytes = 0;
     for (size_t j = 0; j < work.size() && err == hipSuccess; ++j) {
         int best = 0;
@@ -162,28 +301,78 @@ void Proxy::issue(Op *op) {
     }
 }
 
-// Completion polling by event query, as the paper's proxy does; sets copyDone.
+// -------------------------------------------------------- sdma back end ------
+// Returns false while the caller's stream has not yet reached the operation.
+bool Proxy::issue_sdma(Op *op) {
+    if (__atomic_load_n(op->ready_word, __ATOMIC_ACQUIRE) < op->seq) return false;
+    const auto t0 = std::chrono::steady_clock::now();
+    std::vector<CeCopy> work = expand(op, (size_t)nengines);
+    for (auto &c : op->conns) reg[c.first].copyStarted.store(c.second, std::memory_order_release);
+    hsa_signal_store_relaxed(op->left, (hsa_signal_value_t)work.size());
+    uint64_t bytes = 0;
+    for (const CeCopy &w : work) {
+        const uint32_t bit = engine_bit[next_engine++ % (unsigned)nengines];
+        hsa_status_t st = hsa_amd_memory_async_copy_on_engine(
+            w.dst, agent, w.src, agent, w.bytes, 0, nullptr, op->left, (hsa_amd_sdma_engine_id_t)bit, true);
+        if (st != HSA_STATUS_SUCCESS) {   // keep the count right so that the op still completes
+            hsa_signal_subtract_relaxed(op->left, 1);
+            op->sdma_failed = true;
+        }
+        bytes += w.bytes;
+    }
+    const auto t1 = std::chrono::steady_clock::now();
+    n_ops.fetch_add(1, std::memory_order_relaxed);
+    n_copies.fetch_add(work.size(), std::memory_order_relaxed);
+    n_bytes.fetch_add(bytes, std::memory_order_relaxed);
+    issue_ns.fetch_add((uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(t1 - t0).count(),
+                       std::memory_order_relaxed);
+    pending.push_back(op);
+    return true;
+}
+
+void Proxy::finish(Op *op) {
+    for (auto &c : op->conns) reg[c.first].copyDone.store(c.second, std::memory_order_release);
+    if (op->kind == VCCL_CE_SDMA) {
+        if (op->sdma_failed) sdma_errors.fetch_add(1, std::memory_order_relaxed);
+        // Release the caller's stream: it waits for this word to reach the sequence number.
+        __atomic_store_n(op->done_word, op->seq, __ATOMIC_RELEASE);
+    }
+    std::lock_guard<std::mutex> lk(mu);
+    --in_flight;
+    put_ref(op);
+    cv_idle.notify_all();
+}
+
+// Completion polling, as the paper's proxy does; sets copyDone.
 void Proxy::poll() {
+    for (size_t k = 0; k < waiting.size();) {
+        if (issue_sdma(waiting[k])) {
+            waiting[k] = waiting.back();
+            waiting.pop_back();
+        } else {
+            ++k;
+        }
+    }
     for (size_t k = 0; k < pending.size();) {
         Op *op = pending[k];
         bool complete = true;
-        for (int i = 0; i < op->nstreams; ++i) {
-            if (hipEventQuery(op->done[i]) == hipErrorNotReady) {
-                complete = false;
-                break;
+        if (op->kind == VCCL_CE_SDMA) {
+            complete = hsa_signal_load_scacquire(op->left) <= 0;
+        } else {
+            for (int i = 0; i < op->nstreams; ++i) {
+                if (hipEventQuery(op->done[i]) == hipErrorNotReady) {
+                    complete = false;
+                    break;
+                }
             }
         }
         if (!complete) {
             ++k;
             continue;
         }
-        for (auto &c : op->conns) reg[c.first].copyDone.store(c.second, std::memory_order_release);
         pending[k] = pending.back();
         pending.pop_back();
-        std::lock_guard<std::mutex> lk(mu);
-        --in_flight;
-        put_ref(op);
-        cv_idle.notify_all();
+        finish(op);
     }
 }
 
@@ -193,19 +382,25 @@ void Proxy::run() {
         Op *op = nullptr;
         {
             std::unique_lock<std::mutex> lk(mu);
-            if (pending.empty()) {
+            const bool busy = !pending.empty() || !waiting.empty();
+            if (!busy) {
                 cv_work.wait(lk, [&] { return stop || !queue.empty(); });
             } else if (queue.empty()) {
-                cv_work.wait_for(lk, std::chrono::microseconds(20));
+                lk.unlock();
+                std::this_thread::yield();   // poll, like the paper's proxy thread
+                lk.lock();
             }
             if (!queue.empty()) {
                 op = queue.front();
                 queue.pop_front();
-            } else if (stop && pending.empty()) {
+            } else if (stop && !busy) {
                 return;
             }
         }
-        if (op) issue(op);
+        if (op) {
+            if (op->kind == VCCL_CE_SDMA) waiting.push_back(op);
+            else issue_events(op);
+        }
         poll();
     }
 }
@@ -222,9 +417,17 @@ Proxy *proxy_create(int device, int max_streams) {
             return nullptr;
         }
     }
+    p->setup_sdma();
     p->th = std::thread([p] { p->run(); });
     return p;
 }
+
+bool proxy_sdma_available(Proxy *p, const char **why) {
+    if (why) *why = p->sdma_why.c_str();
+    return p->sdma_ok;
+}
+
+int proxy_engine_count(Proxy *p) { return p->nengines; }
 
 int proxy_drain(Proxy *p) {
     std::unique_lock<std::mutex> lk(p->mu);
@@ -245,27 +448,41 @@ void proxy_destroy(Proxy *p) {
         (void)hipStreamSynchronize(p->streams[i]);
         (void)hipStreamDestroy(p->streams[i]);
     }
+    (void)hipDeviceSynchronize();   // no stream still waits on a word that is about to go
     for (Op *op : p->free_ops) {
         (void)hipEventDestroy(op->ready);
         for (int i = 0; i < kMaxStreams; ++i) (void)hipEventDestroy(op->done[i]);
+        if (op->ready_word) (void)hipHostFree((void *)op->ready_word);
+        if (op->done_word) (void)hipFree(op->done_word);
+        if (op->left.handle) hsa_signal_destroy(op->left);
         delete op;
     }
+    if (p->warm) (void)hipFree(p->warm);
+    if (p->hsa_up) hsa_shut_down();
     delete p;
 }
 
+static int submit_sdma(Proxy *p, Op *op, hipStream_t stream,
+                       const std::vector<std::pair<int, void *>> *receivers);
+
 int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hipStream_t stream,
                  const std::vector<std::pair<int, void *>> *receivers) {
+    if (opt.ce_kind == VCCL_CE_SDMA && !p->sdma_ok)
+        return fail(VCCL_ERR_UNSUPPORTED, "copy-engine back end 'sdma' is not available: %s",
+                    p->sdma_why.c_str());
     Op *op;
     {
         std::lock_guard<std::mutex> lk(p->mu);
         op = p->get_op();
-        if (!op) return fail(VCCL_ERR_HIP, "could not create events for a copy-engine operation");
-        op->refs = 2;
+        if (!op) return fail(VCCL_ERR_HIP, "could not create the resources of a copy-engine operation");
+        op->refs = opt.ce_kind == VCCL_CE_SDMA ? 1 : 2;
         op->state = 0;
     }
     op->copies = std::move(copies);
     op->want_streams = opt.ce_streams;
-    op->nocu = opt.ce_kind_nocu != 0;
+    op->kind = opt.ce_kind;
+    if (op->kind == VCCL_CE_SDMA) return submit_sdma(p, op, stream, receivers);
+
     hipError_t e = hipEventRecord(op->ready, stream);
     if (e != hipSuccess) {
         std::lock_guard<std::mutex> lk(p->mu);
@@ -319,6 +536,50 @@ int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hip
     return rv;
 }
 
+static int submit_sdma(Proxy *p, Op *op, hipStream_t stream,
+                       const std::vector<std::pair<int, void *>> *receivers) {
+    const uint64_t seq = ++op->seq;
+    // proxyReadyEvent: the stream writes the sequence number once everything before
+    // this call has finished.
+    hipError_t e = hipStreamWriteValue64(stream, (void *)op->ready_word, seq, 0);
+    if (e != hipSuccess) {
+        --op->seq;
+        std::lock_guard<std::mutex> lk(p->mu);
+        p->put_ref(op);
+        return fail(VCCL_ERR_HIP, "hipStreamWriteValue64(ready) failed: %s", hipGetErrorString(e));
+    }
+    {
+        std::unique_lock<std::mutex> hs(p->handshake_mu, std::defer_lock);
+        if (receivers) {
+            hs.lock();
+            for (auto &rc : *receivers) {
+                RegInfo &ri = p->reg[rc.first];
+                while (ri.copyStarted.load(std::memory_order_acquire) !=
+                       ri.receiverReady.load(std::memory_order_relaxed))
+                    std::this_thread::yield();
+                ri.receiverRegAddr.store(rc.second, std::memory_order_relaxed);
+                const uint64_t s = ri.receiverReady.load(std::memory_order_relaxed) + 1;
+                ri.receiverReady.store(s, std::memory_order_release);
+                op->conns.emplace_back(rc.first, s);
+            }
+        }
+        uint64_t *done_word = op->done_word;
+        {
+            std::lock_guard<std::mutex> lk(p->mu);
+            p->queue.push_back(op);
+            ++p->in_flight;
+            p->cv_work.notify_one();
+        }
+        // From here on the proxy owns `op`.  The stream resumes when the proxy stores
+        // the sequence number into the done word (proxyOpCount back at zero).
+        e = hipStreamWaitValue64(stream, done_word, seq, hipStreamWaitValueGte, ~0ull);
+    }
+    if (e != hipSuccess)
+        return fail(VCCL_ERR_HIP, "hipStreamWaitValue64(done) failed: %s (the copies still run)",
+                    hipGetErrorString(e));
+    return VCCL_OK;
+}
+
 void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t *issue_ns) {
     if (ops) *ops = p->n_ops.load();
     if (copies) *copies = p->n_copies.load();
@@ -326,9 +587,12 @@ void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uin
     if (issue_ns) *issue_ns = p->issue_ns.load();
 }
 
+uint64_t proxy_sdma_errors(Proxy *p) { return p->sdma_errors.load(); }
+
 int proxy_reginfo(Proxy *p, int receiver, uint64_t *ready, uint64_t *started, uint64_t *done,
                   void **addr) {
-    if (receiver < 0 || receiver >= VCCL_MAX_RANKS) return fail(VCCL_ERR_ARG, "receiver rank %d out of range", receiver);
+    if (receiver < 0 || receiver >= VCCL_MAX_RANKS)
+        return fail(VCCL_ERR_ARG, "receiver rank %d out of range", receiver);
     RegInfo &ri = p->reg[receiver];
     if (ready) *ready = ri.receiverReady.load(std::memory_order_acquire);
     if (started) *started = ri.copyStarted.load(std::memory_order_acquire);

@@ -1,0 +1,90 @@
+"""Co-run behaviour: the FMA probe runs, and the copy-engine path makes progress
+while a compute kernel holds every wavefront slot of every compute unit (a copy
+kernel could not start then; copy engines can)."""
+import time
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from gpu_util import require_gpu, stream_handle
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vccl():
+    require_gpu()
+    import paper_2510_00991_amd as v
+    v.vccl_init(0, 16)
+    yield v
+    v.vccl_finalize()
+
+
+def test_fma_probe_runs_and_scales_with_iterations(vccl):
+    torch = require_gpu()
+    cu = vccl.vccl_device_cu_count()
+    out = torch.zeros(cu * 256, dtype=torch.float32, device="cuda")
+    st = stream_handle(torch)
+    ts = []
+    for iters in (2000, 8000):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        vccl.vccl_fma_probe(out, 0, 256, iters, st)
+        torch.cuda.synchronize()
+        a.record()
+        vccl.vccl_fma_probe(out, 0, 256, iters, st)
+        b.record()
+        torch.cuda.synchronize()
+        ts.append(a.elapsed_time(b))
+    assert torch.isfinite(out).all() and float(out.abs().sum()) > 0
+    assert 3.0 < ts[1] / ts[0] < 5.0, ts          # compute-bound: time follows the iteration count
+    with pytest.raises(vccl.VcclError):
+        vccl.vccl_fma_probe(out, 0, 100, 10, st)  # threads must be a multiple of 64
+
+
+@pytest.mark.parametrize("kind", ["sdma", "hip_nocu"])
+def test_copy_engine_progresses_while_all_wave_slots_are_busy(vccl, kind):
+    """The acceptance test for "zero compute units": with every wavefront slot of
+    the device held by a long compute kernel, the SDMA back end still completes an
+    AlltoAll long before that kernel ends.  The hipMemcpyAsync(NoCU) back end is
+    measured and reported only: whether it needs compute units depends on the HIP
+    runtime in the process."""
+    torch = require_gpu()
+    vccl.vccl_set_option("ce_kind", kind)
+    cu = vccl.vccl_device_cu_count()
+    P, c = 8, 4 << 20
+    send = [torch.from_numpy(wl.payload_bytes(9, s, P * c)).cuda() for s in range(P)]
+    recv = [torch.zeros(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    wgs = cu * 8                                   # 8 x 256 lanes = all 32 wavefront slots of a CU
+    out = torch.zeros(wgs * 256, dtype=torch.float32, device="cuda")
+    comp, comm = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    # size the compute kernel to roughly 40 ms
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(comp):
+        a.record()
+        vccl.vccl_fma_probe(out, wgs, 256, 2000, stream_handle(torch, comp))
+        b.record()
+    torch.cuda.synchronize()
+    iters = int(2000 * 40.0 / max(a.elapsed_time(b), 0.05))
+    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c1 = torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(comp):
+        a0.record()
+        vccl.vccl_fma_probe(out, wgs, 256, iters, stream_handle(torch, comp))
+        a1.record()
+    time.sleep(0.005)                              # the compute kernel now owns the device
+    assert not a1.query(), "compute kernel finished too early for the test to mean anything"
+    with torch.cuda.stream(comm):
+        vccl.vccl_alltoall(send, recv, c, P, vccl.MODE_CE, stream_handle(torch, comm))
+        c1.record()
+    torch.cuda.synchronize()
+    t_compute = a0.elapsed_time(a1)
+    t_copy_done = a0.elapsed_time(c1)
+    vccl.vccl_set_option("ce_kind", "sdma")
+    print(f"[{kind}] compute kernel {t_compute:.1f} ms; copy-engine AlltoAll finished "
+          f"{t_copy_done:.1f} ms after the kernel started")
+    if kind == "sdma":
+        assert t_copy_done < 0.7 * t_compute, (t_copy_done, t_compute)
+    for r, s in ((0, 5), (7, 7), (3, 0)):
+        assert torch.equal(recv[r][s * c:(s + 1) * c], send[s][r * c:(r + 1) * c])

@@ -57,14 +57,17 @@ def test_argument_errors(vccl):
 
 def test_unknown_or_bad_options_fail_loudly(vccl):
     for k, val in (("no_such_knob", "1"), ("cu_unroll", "3"), ("cu_unroll", "x"), ("ce_streams", "0"),
-                   ("ce_kind", "sdma"), ("fifo_chunk_bytes", "1000"), ("check", "-1")):
+                   ("ce_kind", "dma"), ("fifo_chunk_bytes", "1000"), ("check", "-1")):
         with pytest.raises(vccl.VcclError) as e:
             vccl.vccl_set_option(k, val)
         assert e.value.code == -1, (k, val)
     vccl.vccl_set_option("ce_streams", 2)
     assert vccl.vccl_get_option("ce_streams") == "2"
     vccl.vccl_set_option("ce_streams", 4)
-    assert vccl.vccl_get_option("ce_kind") == "nocu"
+    assert vccl.vccl_get_option("ce_kind") == "sdma"
+    assert int(vccl.vccl_get_option("ce_engines")) >= 1
+    with pytest.raises(vccl.VcclError):
+        vccl.vccl_set_option("ce_engines", 4)
 
 
 def test_overlap_check(vccl):

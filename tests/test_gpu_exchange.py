@@ -216,6 +216,37 @@ def test_copy_kernel_variants(vccl, unroll, nt):
                   lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CU))
 
 
+@pytest.mark.parametrize("kind", ["hip_nocu", "hip_default"])
+def test_event_ordered_copy_backends_are_bit_exact_too(vccl, kind):
+    """The hipMemcpyAsync back ends of the copy-engine mode (event ordering)."""
+    torch = require_gpu()
+    lay = wl.random_layout(91, 5, 200000, align=1)
+    send_np = [wl.payload_bytes(92, s, int(lay["send_sizes"][s])) for s in range(5)]
+    _with_options(vccl, {"ce_kind": kind}, lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CE))
+    _with_options(vccl, {"ce_kind": kind, "ce_streams": 1},
+                  lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CE))
+
+
+def test_many_copy_engine_operations_in_flight(vccl):
+    """Several copy-engine calls queued back to back on two streams before any
+    synchronisation: operation slots are recycled and every result is right."""
+    torch = require_gpu()
+    P, c = 4, 256 << 10
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    send = [[torch.from_numpy(wl.payload_bytes(100 + k, s, P * c)).cuda() for s in range(P)] for k in range(2)]
+    recv = [[torch.zeros(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)] for _ in range(2)]
+    torch.cuda.synchronize()
+    for it in range(40):
+        k = it % 2
+        vccl.vccl_alltoall(send[k], recv[k], c, P, vccl.MODE_CE, stream_handle(torch, streams[k]))
+    torch.cuda.synchronize()
+    for k in range(2):
+        want = [np.zeros(P * c, np.uint8) for _ in range(P)]
+        oracle.alltoall([wl.payload_bytes(100 + k, s, P * c) for s in range(P)], want, c)
+        for r in range(P):
+            assert_same(to_host(recv[k][r]), want[r], f"stream {k} recv[{r}]")
+
+
 @pytest.mark.parametrize("mode", MODES)
 def test_edge_cases(vccl, mode):
     torch = require_gpu()
