@@ -115,6 +115,9 @@ def main():
     ap.add_argument("--legs", default="cu,ce,corun,sendrecv,moe,cpu",
                     help="comma list of legs to run: cu (always), ce, corun, sendrecv, moe, cpu, "
                          "calib (a plain 1 GiB device copy, used to scale profiler counters)")
+    ap.add_argument("--ce-sync", default="memops", choices=["memops", "host"],
+                    help="ordering of the copy-engine path: stream write/wait-value operations, "
+                         "or none (the call blocks)")
     args = ap.parse_args()
     legs = set(x.strip() for x in args.legs.split(",") if x.strip())
     unknown = legs - {"cu", "ce", "corun", "sendrecv", "moe", "cpu", "calib"}
@@ -138,6 +141,7 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     v.vccl_init(0, 64)
+    v.vccl_set_option("ce_sync", args.ce_sync)
     out = {}
     try:
         P, c = 8, 16 << 20
@@ -171,7 +175,7 @@ def main():
             wall_ce, per_ce = time_calls(torch, a2a_ce, k_ce, 2)
             out["copy_engine"] = {"GBps": algo_bytes / (wall_ce / k_ce) / 1e9,
                                   "ms_per_step": wall_ce / k_ce * 1e3, "steps": k_ce,
-                                  "kind": v.vccl_get_option("ce_kind"),
+                                  "kind": v.vccl_get_option("ce_kind"), "sync": v.vccl_get_option("ce_sync"),
                                   "engines": int(v.vccl_get_option("ce_engines"))}
         if "corun" in legs:
             # co-run: FMA probe alone vs beside each path (protocol in harness.CoRun)

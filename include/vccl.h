@@ -92,7 +92,12 @@ const char *vccl_last_error(void);
  *       device supports it; "hip_nocu" / "hip_default" = hipMemcpyAsync on internal streams
  *       with event ordering, kind hipMemcpyDeviceToDeviceNoCU / hipMemcpyDeviceToDevice),
  *       "ce_streams" (1..8 internal streams of the hip_* back ends),
- *       "ce_engines" (read-only: SDMA engines in use),
+ *       "ce_sync" (sdma back end only: "memops" = the stream writes a ready word and
+ *       waits on a done word, the call returns at once - the HIP runtime may carry out each
+ *       of the two stream operations with a one-lane helper kernel; "host" = no stream
+ *       operation at all, the calling thread blocks until the copies are done),
+ *       "ce_engines" (read-only: SDMA engines found),
+ *       "ce_max_engines" (0 = all; else use only that many engines),
  *       "check" (0/1 overlap validation),
  *       "fifo_chunk_bytes", "fifo_slots", "fifo_wg_per_conn",
  *       "fifo_spin_limit" (polls before a staged wait gives up).

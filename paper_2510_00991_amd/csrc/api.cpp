@@ -295,6 +295,12 @@ int vccl_set_option(const char *key, const char *value) {
         return VCCL_OK;
     }
     if (k == "ce_engines") return fail(VCCL_ERR_ARG, "ce_engines is read-only");
+    if (k == "ce_sync") {
+        if (!strcmp(value, "memops")) o.ce_sync_host = 0;
+        else if (!strcmp(value, "host")) o.ce_sync_host = 1;
+        else return fail(VCCL_ERR_ARG, "ce_sync must be 'memops' or 'host', got '%s'", value);
+        return VCCL_OK;
+    }
     uint64_t x = 0;
     if (!parse_u64(value, &x)) return fail(VCCL_ERR_ARG, "option %s: '%s' is not a number", key, value);
     auto in = [&](uint64_t lo, uint64_t hi) { return x >= lo && x <= hi; };
@@ -317,6 +323,9 @@ int vccl_set_option(const char *key, const char *value) {
     } else if (k == "ce_streams") {
         if (!in(1, 8)) return fail(VCCL_ERR_ARG, "ce_streams must be 1..8");
         o.ce_streams = (int)x;
+    } else if (k == "ce_max_engines") {
+        if (!in(0, 16)) return fail(VCCL_ERR_ARG, "ce_max_engines must be 0..16");
+        o.ce_max_engines = (int)x;
     } else if (k == "check") {
         if (!in(0, 1)) return fail(VCCL_ERR_ARG, "check must be 0 or 1");
         o.check = (int)x;
@@ -350,6 +359,9 @@ int vccl_get_option(const char *key, char *out, int cap) {
         snprintf(out, (size_t)cap, "%s", o.ce_kind == VCCL_CE_SDMA ? "sdma"
                                          : o.ce_kind == VCCL_CE_HIP_NOCU ? "hip_nocu" : "hip_default");
         return VCCL_OK;
+    } else if (k == "ce_sync") {
+        snprintf(out, (size_t)cap, "%s", o.ce_sync_host ? "host" : "memops");
+        return VCCL_OK;
     } else if (k == "ce_engines") v = (unsigned long long)proxy_engine_count(c->proxy);
     else if (k == "cu_unroll") v = o.cu_unroll;
     else if (k == "cu_wg_per_cu") v = o.cu_wg_per_cu;
@@ -357,6 +369,7 @@ int vccl_get_option(const char *key, char *out, int cap) {
     else if (k == "cu_nontemporal") v = o.cu_nontemporal;
     else if (k == "cu_fast_path") v = o.cu_fast_path;
     else if (k == "ce_streams") v = o.ce_streams;
+    else if (k == "ce_max_engines") v = o.ce_max_engines;
     else if (k == "check") v = o.check;
     else if (k == "fifo_chunk_bytes") v = o.fifo_chunk_bytes;
     else if (k == "fifo_slots") v = o.fifo_slots;

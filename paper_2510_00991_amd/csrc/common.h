@@ -43,6 +43,8 @@ struct Options {
     int cu_fast_path = 1;
     int ce_streams = 4;
     int ce_kind = 0;   // VCCL_CE_*
+    int ce_max_engines = 0;
+    int ce_sync_host = 0;
     int check = 0;
     uint64_t fifo_chunk_bytes = 512u << 10;
     int fifo_slots = 8;

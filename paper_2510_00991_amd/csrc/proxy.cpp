@@ -70,6 +70,8 @@ struct Op {
     uint64_t *done_word = nullptr;             // signal memory, waited on by the caller's stream
     hsa_signal_t left = {0};                   // outstanding copies
     uint64_t seq = 0;
+    bool host_sync = false;                    // no stream memory operations: the caller blocks
+    int max_engines = 0;
     bool sdma_failed = false;
 };
 }  // namespace
@@ -304,14 +306,19 @@ void Proxy::issue_events(Op *op) {
 // -------------------------------------------------------- sdma back end ------
 // Returns false while the caller's stream has not yet reached the operation.
 bool Proxy::issue_sdma(Op *op) {
-    if (__atomic_load_n(op->ready_word, __ATOMIC_ACQUIRE) < op->seq) return false;
+    if (op->host_sync) {
+        if (hipEventQuery(op->ready) == hipErrorNotReady) return false;
+    } else if (__atomic_load_n(op->ready_word, __ATOMIC_ACQUIRE) < op->seq) {
+        return false;
+    }
     const auto t0 = std::chrono::steady_clock::now();
-    std::vector<CeCopy> work = expand(op, (size_t)nengines);
+    const int ne = op->max_engines > 0 && op->max_engines < nengines ? op->max_engines : nengines;
+    std::vector<CeCopy> work = expand(op, (size_t)ne);
     for (auto &c : op->conns) reg[c.first].copyStarted.store(c.second, std::memory_order_release);
     hsa_signal_store_relaxed(op->left, (hsa_signal_value_t)work.size());
     uint64_t bytes = 0;
     for (const CeCopy &w : work) {
-        const uint32_t bit = engine_bit[next_engine++ % (unsigned)nengines];
+        const uint32_t bit = engine_bit[next_engine++ % (unsigned)ne];
         hsa_status_t st = hsa_amd_memory_async_copy_on_engine(
             w.dst, agent, w.src, agent, w.bytes, 0, nullptr, op->left, (hsa_amd_sdma_engine_id_t)bit, true);
         if (st != HSA_STATUS_SUCCESS) {   // keep the count right so that the op still completes
@@ -335,9 +342,13 @@ void Proxy::finish(Op *op) {
     if (op->kind == VCCL_CE_SDMA) {
         if (op->sdma_failed) sdma_errors.fetch_add(1, std::memory_order_relaxed);
         // Release the caller's stream: it waits for this word to reach the sequence number.
-        __atomic_store_n(op->done_word, op->seq, __ATOMIC_RELEASE);
+        if (!op->host_sync) __atomic_store_n(op->done_word, op->seq, __ATOMIC_RELEASE);
     }
     std::lock_guard<std::mutex> lk(mu);
+    if (op->kind == VCCL_CE_SDMA && op->host_sync) {
+        op->state = op->sdma_failed ? 2 : 3;   // wakes the blocked caller
+        cv_issued.notify_all();
+    }
     --in_flight;
     put_ref(op);
     cv_idle.notify_all();
@@ -464,6 +475,7 @@ void proxy_destroy(Proxy *p) {
 
 static int submit_sdma(Proxy *p, Op *op, hipStream_t stream,
                        const std::vector<std::pair<int, void *>> *receivers);
+static void publish_receivers(Proxy *p, Op *op, const std::vector<std::pair<int, void *>> &receivers);
 
 int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hipStream_t stream,
                  const std::vector<std::pair<int, void *>> *receivers) {
@@ -475,12 +487,14 @@ int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hip
         std::lock_guard<std::mutex> lk(p->mu);
         op = p->get_op();
         if (!op) return fail(VCCL_ERR_HIP, "could not create the resources of a copy-engine operation");
-        op->refs = opt.ce_kind == VCCL_CE_SDMA ? 1 : 2;
+        op->host_sync = opt.ce_kind == VCCL_CE_SDMA && opt.ce_sync_host;
+        op->refs = (opt.ce_kind == VCCL_CE_SDMA && !op->host_sync) ? 1 : 2;
         op->state = 0;
     }
     op->copies = std::move(copies);
     op->want_streams = opt.ce_streams;
     op->kind = opt.ce_kind;
+    op->max_engines = opt.ce_max_engines;
     if (op->kind == VCCL_CE_SDMA) return submit_sdma(p, op, stream, receivers);
 
     hipError_t e = hipEventRecord(op->ready, stream);
@@ -494,20 +508,8 @@ int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hip
     hipError_t err = hipSuccess;
     std::unique_lock<std::mutex> hs(p->handshake_mu, std::defer_lock);
     if (receivers) {
-        // Receiver side of the handshake: once the previous transfer on the
-        // connection has started, publish the application buffer and raise ready.
-        // The lock is held until the op is queued so that records and queue agree.
         hs.lock();
-        for (auto &rc : *receivers) {
-            RegInfo &ri = p->reg[rc.first];
-            while (ri.copyStarted.load(std::memory_order_acquire) !=
-                   ri.receiverReady.load(std::memory_order_relaxed))
-                std::this_thread::yield();
-            ri.receiverRegAddr.store(rc.second, std::memory_order_relaxed);
-            const uint64_t seq = ri.receiverReady.load(std::memory_order_relaxed) + 1;
-            ri.receiverReady.store(seq, std::memory_order_release);
-            op->conns.emplace_back(rc.first, seq);
-        }
+        publish_receivers(p, op, *receivers);
     }
     {
         std::unique_lock<std::mutex> lk(p->mu);
@@ -536,8 +538,58 @@ int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hip
     return rv;
 }
 
+// Receiver side of the handshake: once the previous transfer on the connection has
+// started, publish the application buffer and raise ready.  Called with
+// handshake_mu held, which stays held until the op is queued so that records and
+// queue agree.
+static void publish_receivers(Proxy *p, Op *op, const std::vector<std::pair<int, void *>> &receivers) {
+    for (auto &rc : receivers) {
+        RegInfo &ri = p->reg[rc.first];
+        while (ri.copyStarted.load(std::memory_order_acquire) !=
+               ri.receiverReady.load(std::memory_order_relaxed))
+            std::this_thread::yield();
+        ri.receiverRegAddr.store(rc.second, std::memory_order_relaxed);
+        const uint64_t s = ri.receiverReady.load(std::memory_order_relaxed) + 1;
+        ri.receiverReady.store(s, std::memory_order_release);
+        op->conns.emplace_back(rc.first, s);
+    }
+}
+
+// SDMA back end without stream memory operations: the calling thread itself waits
+// until the copies are done, so nothing at all is enqueued on the device except
+// the `ready` event.  Zero kernels, at the price of a blocking call.
+static int submit_sdma_host_sync(Proxy *p, Op *op, hipStream_t stream,
+                                 const std::vector<std::pair<int, void *>> *receivers) {
+    hipError_t e = hipEventRecord(op->ready, stream);
+    if (e != hipSuccess) {
+        std::lock_guard<std::mutex> lk(p->mu);
+        op->refs = 1;
+        p->put_ref(op);
+        return fail(VCCL_ERR_HIP, "hipEventRecord(ready) failed: %s", hipGetErrorString(e));
+    }
+    std::unique_lock<std::mutex> hs(p->handshake_mu, std::defer_lock);
+    if (receivers) {
+        hs.lock();
+        publish_receivers(p, op, *receivers);
+    }
+    int state;
+    {
+        std::unique_lock<std::mutex> lk(p->mu);
+        p->queue.push_back(op);
+        ++p->in_flight;
+        p->cv_work.notify_one();
+        if (hs.owns_lock()) hs.unlock();
+        p->cv_issued.wait(lk, [&] { return op->state >= 2; });
+        state = op->state;
+        p->put_ref(op);
+    }
+    if (state == 2) return fail(VCCL_ERR_HIP, "an SDMA copy could not be submitted");
+    return VCCL_OK;
+}
+
 static int submit_sdma(Proxy *p, Op *op, hipStream_t stream,
                        const std::vector<std::pair<int, void *>> *receivers) {
+    if (op->host_sync) return submit_sdma_host_sync(p, op, stream, receivers);
     const uint64_t seq = ++op->seq;
     // proxyReadyEvent: the stream writes the sequence number once everything before
     // this call has finished.
@@ -552,16 +604,7 @@ static int submit_sdma(Proxy *p, Op *op, hipStream_t stream,
         std::unique_lock<std::mutex> hs(p->handshake_mu, std::defer_lock);
         if (receivers) {
             hs.lock();
-            for (auto &rc : *receivers) {
-                RegInfo &ri = p->reg[rc.first];
-                while (ri.copyStarted.load(std::memory_order_acquire) !=
-                       ri.receiverReady.load(std::memory_order_relaxed))
-                    std::this_thread::yield();
-                ri.receiverRegAddr.store(rc.second, std::memory_order_relaxed);
-                const uint64_t s = ri.receiverReady.load(std::memory_order_relaxed) + 1;
-                ri.receiverReady.store(s, std::memory_order_release);
-                op->conns.emplace_back(rc.first, s);
-            }
+            publish_receivers(p, op, *receivers);
         }
         uint64_t *done_word = op->done_word;
         {

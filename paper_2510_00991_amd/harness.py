@@ -66,21 +66,25 @@ class CoRun:
         return a, b
 
     def _time_alone(self):
+        """Probe preceded by an untimed probe, so that the timed one always starts
+        with the compute units already busy and the clocks settled."""
+        self._probe()
         a, b = self._probe()
         self.comp.synchronize()
         return a.elapsed_time(b) * 1e-3
 
-    def alone(self, reps=20):
+    def alone(self, reps=10):
         if self._alone is None:
-            for _ in range(3):
-                self._time_alone()
+            self._time_alone()
             self._alone = statistics.median(self._time_alone() for _ in range(reps))
         return self._alone
 
     def beside(self, comm_fn, comm_bytes_per_call, comm_seconds_per_call, reps=12):
         """comm_fn(stream_handle) enqueues one transfer on the given stream.  Each
-        repetition times the probe alone and then beside the transfer, so slow drifts
-        of the clocks cancel; the medians of both series are reported."""
+        repetition times the probe alone and then beside the transfer; in both cases
+        the timed probe directly follows an untimed one, and the transfers are held
+        back until that untimed probe has finished, so both timed probes start from
+        the same state.  The medians of both series are reported."""
         torch = self.torch
         t_guess = self.alone()
         n_comm = max(1, int(1.25 * t_guess / max(comm_seconds_per_call, 1e-6)) + 1)
@@ -89,6 +93,10 @@ class CoRun:
         for _ in range(reps):
             torch.cuda.synchronize()
             alone.append(self._time_alone())
+            self._probe()                                   # untimed lead-in
+            gate = torch.cuda.Event()
+            gate.record(self.comp)
+            self.comm.wait_event(gate)
             c0, c1 = _ev(torch), _ev(torch)
             with torch.cuda.stream(self.comm):
                 c0.record()
@@ -177,7 +185,13 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
         for name, mode in (("cu", v.MODE_CU), ("ce", v.MODE_CE)):
             fn = lambda s=st, m=mode: v.vccl_alltoall(send, recv, c, P, m, s)
             k = 10 if name == "cu" else 3
-            wall, per = time_calls(torch, fn, k, 2)
+            # keep the device busy for ~50 ms first: the memory clocks of an idle
+            # device ramp up slowly under copy-engine traffic alone
+            t_warm = time.perf_counter()
+            while time.perf_counter() - t_warm < 0.05:
+                fn()
+                torch.cuda.synchronize()
+            wall, per = time_calls(torch, fn, k, 1)
             t = wall / k
             row[name] = {"us": t * 1e6, "GBps": moved / t / 1e9}
             if co is not None:

@@ -227,6 +227,19 @@ def test_event_ordered_copy_backends_are_bit_exact_too(vccl, kind):
                   lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CE))
 
 
+@pytest.mark.parametrize("seed", [3, 5])
+def test_sdma_host_sync_mode(vccl, seed):
+    """SDMA back end without stream memory operations (the call blocks until done)."""
+    torch = require_gpu()
+    rng = np.random.Generator(np.random.PCG64(seed))
+    P = int(rng.integers(2, 8))
+    lay = wl.random_layout(700 + seed, P, 150000, align=1)
+    send_np = [wl.payload_bytes(seed, s, int(lay["send_sizes"][s])) for s in range(P)]
+    _with_options(vccl, {"ce_sync": "host"}, lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CE))
+    _with_options(vccl, {"ce_sync": "host", "ce_max_engines": 1},
+                  lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CE))
+
+
 def test_many_copy_engine_operations_in_flight(vccl):
     """Several copy-engine calls queued back to back on two streams before any
     synchronisation: operation slots are recycled and every result is right."""
@@ -275,11 +288,23 @@ def test_edge_cases(vccl, mode):
     assert to_host(r_dev[1]).tolist() == [11, 21, SENTINEL]
 
 
-@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("mode", MODES + ["ce_host", "ce_hip"])
 def test_stream_ordering(vccl, mode):
     """The exchange starts after earlier work on the caller's stream and later work
     on that stream sees the received data (a side stream, repeated)."""
     torch = require_gpu()
+    opts = {"ce_host": {"ce_sync": "host"}, "ce_hip": {"ce_kind": "hip_nocu"}}.get(mode, {})
+    saved = {k: vccl.vccl_get_option(k) for k in opts}
+    for k, val in opts.items():
+        vccl.vccl_set_option(k, val)
+    try:
+        _stream_ordering_body(torch, vccl, vccl.MODE_CU if mode == "cu" else vccl.MODE_CE)
+    finally:
+        for k, val in saved.items():
+            vccl.vccl_set_option(k, val)
+
+
+def _stream_ordering_body(torch, vccl, m):
     P, c = 4, 1 << 20
     side = torch.cuda.Stream()
     send = [torch.zeros(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
@@ -290,11 +315,11 @@ def test_stream_ordering(vccl, mode):
         with torch.cuda.stream(side):
             for s in range(P):
                 send[s].fill_(it * 10 + s)                       # producer on the same stream
-            vccl.vccl_alltoall(send, recv, c, P, _mode(vccl, mode), stream_handle(torch, side))
+            vccl.vccl_alltoall(send, recv, c, P, m, stream_handle(torch, side))
             for r in range(P):
                 snap[r].copy_(recv[r])                           # consumer on the same stream
         side.synchronize()
         for r in range(P):
             got = to_host(snap[r]).reshape(P, c)
             for s in range(P):
-                assert (got[s] == it * 10 + s).all(), (mode, it, r, s)
+                assert (got[s] == it * 10 + s).all(), (m, it, r, s)

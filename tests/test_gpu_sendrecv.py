@@ -77,6 +77,15 @@ def test_config4_ring_p8_64m_full_size(vccl, mode):
         assert_same(to_host(recv[r]), recv_np[r], f"recv[{r}]")
 
 
+def test_ring_sdma_host_sync(vccl):
+    torch = require_gpu()
+    vccl.vccl_set_option("ce_sync", "host")
+    try:
+        _ring(torch, vccl, vccl.MODE_CE, [700001, 33, 524288 + 1, 0, 99999], misalign=3)
+    finally:
+        vccl.vccl_set_option("ce_sync", "memops")
+
+
 def test_staged_equals_oracle_fifo_model(vccl):
     """Different chunk / slot settings give the same bytes as the oracle's FIFO model."""
     torch = require_gpu()
