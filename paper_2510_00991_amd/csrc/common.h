@@ -41,6 +41,7 @@ struct Options {
     int cu_max_wg = 0;
     int cu_nontemporal = 1;
     int cu_fast_path = 1;
+    int moe_gather_variant = 116;
     int ce_streams = 4;
     int ce_kind = 0;   // VCCL_CE_*
     int ce_max_engines = 0;
@@ -136,7 +137,7 @@ struct MoeScratch {
 int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P,
                     int tokens, int topk, uint64_t row_bytes, int num_experts,
                     void *const *packed, uint64_t *counts_dev, uint64_t *counts_host,
-                    uint32_t *bad_ids_dev, hipStream_t stream);
+                    uint32_t *bad_ids_dev, int gather_variant, hipStream_t stream);
 
 // ---- co-run probe
 int launch_fma_probe(float *out, uint32_t workgroups, uint32_t threads, uint64_t iters,

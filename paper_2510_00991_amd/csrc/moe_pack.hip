@@ -139,8 +139,8 @@ __global__ __launch_bounds__(kMoeThreads) void moe_rank_kernel(MoePtrs ptrs, uin
     }
 }
 
-constexpr int kRowVecs = 8;   // 16-byte vectors a lane holds per pass over a row
-
+// kRowVecs = 16-byte vectors a lane holds per pass over a row
+template <int kRowVecs, bool NT>
 __global__ __launch_bounds__(kMoeThreads) void moe_gather_kernel(MoePtrs ptrs, uint32_t tokens, int K,
                                                                  uint32_t row_vecs,
                                                                  const uint32_t *dest, uint32_t npairs) {
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(kMoeThreads) void moe_gather_kernel(MoePtrs ptrs, u
 #pragma unroll
         for (int u = 0; u < kRowVecs; ++u) {
             const uint32_t v = v0 + u * 64u + lane;
-            if (v < row_vecs) r[u] = __builtin_nontemporal_load(row + v);
+            if (v < row_vecs) r[u] = __builtin_nontemporal_load(row + v);   // read once
         }
         for (int k = 0; k < K; ++k) {
             const uint32_t j = d[k];
@@ -165,7 +165,10 @@ __global__ __launch_bounds__(kMoeThreads) void moe_gather_kernel(MoePtrs ptrs, u
 #pragma unroll
             for (int u = 0; u < kRowVecs; ++u) {
                 const uint32_t v = v0 + u * 64u + lane;
-                if (v < row_vecs) __builtin_nontemporal_store(r[u], o + v);
+                if (v < row_vecs) {
+                    if (NT) __builtin_nontemporal_store(r[u], o + v);
+                    else o[v] = r[u];
+                }
             }
         }
     }
@@ -189,7 +192,7 @@ void MoeScratch::destroy() {
 int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P, int tokens,
                     int topk, uint64_t row_bytes, int num_experts, void *const *packed,
                     uint64_t *counts_dev, uint64_t *counts_host, uint32_t *bad_ids_dev,
-                    hipStream_t stream) {
+                    int gather_variant, hipStream_t stream) {
     const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
     const uint32_t nblk = npairs ? (npairs + kPairsPerBlock - 1) / kPairsPerBlock : 1;
     const size_t hist_n = (size_t)P * nblk * (size_t)num_experts;
@@ -242,8 +245,15 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
                                                                         ebits, nblk, hist, dest);
         VCCL_HIP(hipGetLastError());
         const uint32_t tok_blocks = ((uint32_t)tokens + kMoeThreads / 64 - 1) / (kMoeThreads / 64);
-        moe_gather_kernel<<<dim3(tok_blocks, P), dim3(kMoeThreads), 0, stream>>>(
-            ptrs, (uint32_t)tokens, topk, (uint32_t)(row_bytes >> 4), dest, npairs);
+        const dim3 g(tok_blocks, P), b(kMoeThreads);
+        const uint32_t rv = (uint32_t)(row_bytes >> 4);
+        switch (gather_variant) {
+            case 4: moe_gather_kernel<4, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
+            case 16: moe_gather_kernel<16, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
+            case 108: moe_gather_kernel<8, false><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
+            case 116: moe_gather_kernel<16, false><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
+            default: moe_gather_kernel<8, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
+        }
         VCCL_HIP(hipGetLastError());
     }
     if (counts_host)

@@ -84,7 +84,7 @@ class CoRun:
         repetition times the probe alone and then beside the transfer; in both cases
         the timed probe directly follows an untimed one, and the transfers are held
         back until that untimed probe has finished, so both timed probes start from
-        the same state.  The medians of both series are reported."""
+        the same state.  The slowdown is the median of the per-repetition ratios."""
         torch = self.torch
         t_guess = self.alone()
         n_comm = max(1, int(1.25 * t_guess / max(comm_seconds_per_call, 1e-6)) + 1)
@@ -110,8 +110,10 @@ class CoRun:
         t_alone = statistics.median(alone)
         t_with = statistics.median(both)
         tc = statistics.median(comm_t)
+        # paired: each repetition's two probes are adjacent in time, so clock drift cancels
+        ratio = statistics.median(b / a for a, b in zip(alone, both))
         return {"alone_ms": t_alone * 1e3, "corun_ms": t_with * 1e3,
-                "slowdown_pct": 100.0 * (t_with - t_alone) / t_alone,
+                "slowdown_pct": 100.0 * (ratio - 1.0),
                 "comm_calls": n_comm, "comm_ms": tc * 1e3,
                 "comm_GBps_while_corunning": comm_bytes_per_call * n_comm / tc / 1e9}
 
