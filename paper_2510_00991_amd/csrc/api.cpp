@@ -402,6 +402,11 @@ int vccl_alltoall(void *const *sendbuf, void *const *recvbuf, uint64_t bytes_per
     auto c = ctx_get();
     int rv = check_common(c, P, sendbuf, recvbuf);
     if (rv) return rv;
+    if (mode == VCCL_MODE_CU && P > 8) {   // up to 64 descriptors already ride in the kernel arguments
+        const Options opt = options_of(*c);
+        if (uniform_alltoall_applies(sendbuf, recvbuf, bytes_per_peer, P, opt))
+            return launch_uniform_alltoall(sendbuf, recvbuf, bytes_per_peer, P, opt, (hipStream_t)stream);
+    }
     std::vector<uint64_t> cnt((size_t)P * P, bytes_per_peer), dsp((size_t)P * P);
     for (int a = 0; a < P; ++a)
         for (int b = 0; b < P; ++b) dsp[(size_t)a * P + b] = (uint64_t)b * bytes_per_peer;

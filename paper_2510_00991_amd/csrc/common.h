@@ -98,6 +98,13 @@ int plan_tiles(CopyPlan &plan, int unroll);
 int launch_copy(const CopyPlan &plan, const Options &opt, int cu_count, DescRing &ring,
                 hipStream_t stream);
 
+// Equal-block AlltoAll whose descriptors are derived in the kernel from the rank
+// pointers (no table, no upload); applies when everything is 16-byte aligned.
+bool uniform_alltoall_applies(void *const *sendbuf, void *const *recvbuf, uint64_t bytes_per_peer, int P,
+                              const Options &opt);
+int launch_uniform_alltoall(void *const *sendbuf, void *const *recvbuf, uint64_t bytes_per_peer, int P,
+                            const Options &opt, hipStream_t stream);
+
 // ---- staged FIFO SendRecv (CU_STAGED)
 struct FifoState {
     uint8_t *slots = nullptr;        // connections x fifo_slots x chunk bytes

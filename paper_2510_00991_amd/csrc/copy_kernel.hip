@@ -155,6 +155,92 @@ __global__ __launch_bounds__(kCopyThreads) void copy_aligned_kernel(CopyArgs by_
     }
 }
 
+// Equal-block AlltoAll without a descriptor table: the P send and P receive
+// pointers ride in the kernel arguments and a workgroup derives its segment from
+// blockIdx.y - segment q = k*P + r moves block r of send[(r+k) mod P] to block
+// (r+k) mod P of recv[r], the same rotated order the planner uses.  Nothing is
+// uploaded, so a P = 64 exchange of small blocks costs one launch.
+constexpr int kUniformRanks = 128;
+struct UniformArgs {
+    const uint8_t *send[kUniformRanks];
+    uint8_t *recv[kUniformRanks];
+    uint64_t vecs_per_block;   // bytes_per_peer / 16
+    uint32_t P;
+    uint32_t pad;
+};
+
+template <int U, bool NT>
+__global__ __launch_bounds__(kCopyThreads) void copy_uniform_kernel(UniformArgs by_value) {
+    (void)by_value;
+    const UniformArgs *a =
+        reinterpret_cast<const UniformArgs *>((const void *)__builtin_amdgcn_kernarg_segment_ptr());
+    constexpr uint32_t kTileVecs = (uint32_t)U * kCopyThreads;
+    const uint64_t nv = a->vecs_per_block;
+    const uint64_t v0 = (uint64_t)blockIdx.x * kTileVecs;
+    if (v0 >= nv) return;
+    const uint32_t P = a->P;
+    const uint32_t k = blockIdx.y / P, r = blockIdx.y - k * P;
+    uint32_t s_rank = r + k;
+    if (s_rank >= P) s_rank -= P;
+    const u32x4 *s = reinterpret_cast<const u32x4 *>(a->send[s_rank]) + (uint64_t)r * nv + v0;
+    u32x4 *d = reinterpret_cast<u32x4 *>(a->recv[r]) + (uint64_t)s_rank * nv + v0;
+    const uint32_t tid = threadIdx.x;
+    if (nv - v0 >= kTileVecs) {
+        u32x4 reg[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) reg[u] = ld16<NT>(s + u * kCopyThreads + tid);
+#pragma unroll
+        for (int u = 0; u < U; ++u) st16<NT>(d + u * kCopyThreads + tid, reg[u]);
+    } else {
+        const uint32_t cnt = (uint32_t)(nv - v0);
+        for (uint32_t i = tid; i < cnt; i += kCopyThreads) st16<NT>(d + i, ld16<NT>(s + i));
+    }
+}
+
+bool uniform_alltoall_applies(void *const *sendbuf, void *const *recvbuf, uint64_t bytes_per_peer, int P,
+                              const Options &opt) {
+    if (!opt.cu_fast_path || opt.check || opt.cu_max_wg || opt.cu_wg_per_cu) return false;
+    if (P > kUniformRanks || (uint64_t)P * P > 65535 || bytes_per_peer == 0 || (bytes_per_peer & 15u)) return false;
+    const uint64_t tiles = ((bytes_per_peer >> 4) + (uint64_t)opt.cu_unroll * kCopyThreads - 1) /
+                           ((uint64_t)opt.cu_unroll * kCopyThreads);
+    if (tiles > 0x7fffffffull) return false;
+    for (int i = 0; i < P; ++i)
+        if (!sendbuf[i] || !recvbuf[i] ||
+            ((reinterpret_cast<uintptr_t>(sendbuf[i]) | reinterpret_cast<uintptr_t>(recvbuf[i])) & 15u))
+            return false;
+    return true;
+}
+
+int launch_uniform_alltoall(void *const *sendbuf, void *const *recvbuf, uint64_t bytes_per_peer, int P,
+                            const Options &opt, hipStream_t stream) {
+    UniformArgs a;
+    for (int i = 0; i < P; ++i) {
+        a.send[i] = static_cast<const uint8_t *>(sendbuf[i]);
+        a.recv[i] = static_cast<uint8_t *>(recvbuf[i]);
+    }
+    a.vecs_per_block = bytes_per_peer >> 4;
+    a.P = (uint32_t)P;
+    a.pad = 0;
+    const uint64_t tile_vecs = (uint64_t)opt.cu_unroll * kCopyThreads;
+    const dim3 grid((uint32_t)((a.vecs_per_block + tile_vecs - 1) / tile_vecs), (uint32_t)(P * P));
+    const dim3 block(kCopyThreads);
+    const bool nt = opt.cu_nontemporal != 0;
+#define VCCL_UNI(U)                                                                          \
+    if (nt) copy_uniform_kernel<U, true><<<grid, block, 0, stream>>>(a);                     \
+    else copy_uniform_kernel<U, false><<<grid, block, 0, stream>>>(a)
+    switch (opt.cu_unroll) {
+        case 1: VCCL_UNI(1); break;
+        case 2: VCCL_UNI(2); break;
+        case 4: VCCL_UNI(4); break;
+        case 8: VCCL_UNI(8); break;
+        case 16: VCCL_UNI(16); break;
+        default: return fail(VCCL_ERR_ARG, "cu_unroll %d is not one of 1,2,4,8,16", opt.cu_unroll);
+    }
+#undef VCCL_UNI
+    VCCL_HIP(hipGetLastError());
+    return VCCL_OK;
+}
+
 // Head bytes of a segment: what precedes the first 16-byte aligned destination address.
 static inline uint32_t head_of(const uint8_t *dst, uint64_t bytes) {
     const uint64_t to_align = (16u - (reinterpret_cast<uintptr_t>(dst) & 15u)) & 15u;

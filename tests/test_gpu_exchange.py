@@ -153,6 +153,25 @@ def _with_options(v, opts, fn):
             v.vccl_set_option(k, val)
 
 
+@pytest.mark.parametrize("P,c", [(9, 16), (16, 4096 + 16), (37, 50000 - 50000 % 16), (64, 1 << 20)])
+def test_alltoall_pointer_table_kernel(vccl, P, c):
+    """Equal-block AlltoAll above 8 ranks derives its segments in the kernel from
+    the rank pointers (no descriptor upload); odd P, ragged last tile, and the same
+    call with the fast path switched off must all agree with the oracle."""
+    torch = require_gpu()
+    send_np = [wl.payload_bytes(600 + P, s, P * c) for s in range(P)]
+    want = [np.full(P * c + 32, SENTINEL, dtype=np.uint8) for _ in range(P)]
+    oracle.alltoall(send_np, want, c, threads=4)
+    send = [to_dev(torch, a) for a in send_np]
+    for fast in (1, 0):
+        recv = [to_dev(torch, np.full(P * c + 32, SENTINEL, dtype=np.uint8)) for _ in range(P)]
+        _with_options(vccl, {"cu_fast_path": fast},
+                      lambda: vccl.vccl_alltoall(send, recv, c, P, vccl.MODE_CU, stream_handle(torch)))
+        torch.cuda.synchronize()
+        for r in range(P):
+            assert_same(to_host(recv[r]), want[r], f"fast={fast} recv[{r}]")
+
+
 def test_p40_alltoallv_table_path_non_uniform(vccl):
     """More than 64 descriptors of different lengths: the device descriptor table
     and the early exit of workgroups past a short descriptor."""
