@@ -148,6 +148,24 @@ int vccl_alltoallv(void *const *sendbuf, const uint64_t *sendcounts, const uint6
                    void *const *recvbuf, const uint64_t *recvcounts, const uint64_t *rdispls,
                    int P, vccl_mode mode, void *stream);
 
+/* Host-only view of the planner of the compute-unit path (needs no device and no
+ * vccl_init; buffer addresses are never dereferenced).  For an AlltoAllv
+ * description it reports the copy descriptors in launch order - non-empty segments,
+ * destination-major with the source rotated by the destination index (the incast
+ * counter-measure, Section 6), long segments cut into pieces of equal tile count -
+ * and the launch grid: grid_x tiles of cu_unroll*4096 bytes per descriptor,
+ * grid_y descriptors.  head is the number of leading bytes copied bytewise before
+ * the destination is 16-byte aligned; all_aligned tells whether the fast kernel
+ * applies.  out may be NULL to query the count. */
+typedef struct {
+    uint64_t src, dst, bytes;
+    uint32_t head, reserved;
+} vccl_plan_desc;
+int vccl_plan_alltoallv(void *const *sendbuf, const uint64_t *sendcounts, const uint64_t *sdispls,
+                        void *const *recvbuf, const uint64_t *recvcounts, const uint64_t *rdispls,
+                        int P, int cu_unroll, vccl_plan_desc *out, int out_cap, int *n_out,
+                        uint32_t *grid_x, uint32_t *grid_y, int *all_aligned);
+
 /* MoE dispatch pack (Section 2.1 token routing; Section 6 dispatch phase) for all
  * P source ranks in one call.  For rank s, x[s] holds `tokens` rows of row_bytes
  * bytes (row_bytes a multiple of 16, rows 16-byte aligned) and expert_ids[s] holds

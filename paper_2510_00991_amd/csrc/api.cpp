@@ -173,12 +173,10 @@ static int check_common(const std::shared_ptr<Context> &c, int P, const void *a,
     return VCCL_OK;
 }
 
-static int alltoallv_impl(Context &c, void *const *sendbuf, const uint64_t *sendcounts,
-                          const uint64_t *sdispls, void *const *recvbuf, const uint64_t *recvcounts,
-                          const uint64_t *rdispls, int P, vccl_mode mode, hipStream_t stream) {
-    if (mode != VCCL_MODE_CU && mode != VCCL_MODE_CE)
-        return fail(mode == VCCL_MODE_CU_STAGED ? VCCL_ERR_UNSUPPORTED : VCCL_ERR_ARG,
-                    "mode %d is not available for AlltoAll(v)", (int)mode);
+// Validation and descriptor order of an AlltoAllv description (host only).
+static int alltoallv_pieces(void *const *sendbuf, const uint64_t *sendcounts, const uint64_t *sdispls,
+                            void *const *recvbuf, const uint64_t *recvcounts, const uint64_t *rdispls,
+                            int P, std::vector<Piece> &pieces) {
     for (int s = 0; s < P; ++s)
         for (int r = 0; r < P; ++r)
             if (sendcounts[(size_t)s * P + r] != recvcounts[(size_t)r * P + s])
@@ -186,7 +184,7 @@ static int alltoallv_impl(Context &c, void *const *sendbuf, const uint64_t *send
                             "sendcounts[%d][%d] = %llu but recvcounts[%d][%d] = %llu", s, r,
                             (unsigned long long)sendcounts[(size_t)s * P + r], r, s,
                             (unsigned long long)recvcounts[(size_t)r * P + s]);
-    std::vector<Piece> pieces;
+    pieces.clear();
     pieces.reserve((size_t)P * P);
     // Destination-major with the source rotated by the destination index: at any
     // moment the segments in flight fan out over all sources and destinations
@@ -202,6 +200,18 @@ static int alltoallv_impl(Context &c, void *const *sendbuf, const uint64_t *send
                                    (uint8_t *)recvbuf[r] + rdispls[(size_t)r * P + s], n, -1});
         }
     }
+    return VCCL_OK;
+}
+
+static int alltoallv_impl(Context &c, void *const *sendbuf, const uint64_t *sendcounts,
+                          const uint64_t *sdispls, void *const *recvbuf, const uint64_t *recvcounts,
+                          const uint64_t *rdispls, int P, vccl_mode mode, hipStream_t stream) {
+    if (mode != VCCL_MODE_CU && mode != VCCL_MODE_CE)
+        return fail(mode == VCCL_MODE_CU_STAGED ? VCCL_ERR_UNSUPPORTED : VCCL_ERR_ARG,
+                    "mode %d is not available for AlltoAll(v)", (int)mode);
+    std::vector<Piece> pieces;
+    int rv = alltoallv_pieces(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, pieces);
+    if (rv) return rv;
     return run_pieces(c, pieces, mode, stream, nullptr);
 }
 
@@ -524,6 +534,40 @@ int vccl_moe_exchange_layout(const uint64_t *counts, int P, int num_experts, int
             recvcounts[(size_t)r * P + s] = b;
             rdispls[(size_t)r * P + s] = run;
             run += b;
+        }
+    }
+    return VCCL_OK;
+}
+
+int vccl_plan_alltoallv(void *const *sendbuf, const uint64_t *sendcounts, const uint64_t *sdispls,
+                        void *const *recvbuf, const uint64_t *recvcounts, const uint64_t *rdispls, int P,
+                        int cu_unroll, vccl_plan_desc *out, int out_cap, int *n_out, uint32_t *grid_x,
+                        uint32_t *grid_y, int *all_aligned) {
+    if (P < 1 || P > VCCL_MAX_RANKS) return fail(VCCL_ERR_ARG, "P = %d is outside 1..%d", P, VCCL_MAX_RANKS);
+    if (!sendbuf || !recvbuf || !sendcounts || !sdispls || !recvcounts || !rdispls || !n_out)
+        return fail(VCCL_ERR_ARG, "NULL argument");
+    if (!(cu_unroll == 1 || cu_unroll == 2 || cu_unroll == 4 || cu_unroll == 8 || cu_unroll == 16))
+        return fail(VCCL_ERR_ARG, "cu_unroll must be 1, 2, 4, 8 or 16");
+    std::vector<Piece> pieces;
+    int rv = alltoallv_pieces(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, pieces);
+    if (rv) return rv;
+    CopyPlan plan;
+    for (const Piece &pc : pieces) plan.segs.push_back(Seg{pc.src, pc.dst, pc.bytes, 0, 0});
+    rv = plan_tiles(plan, cu_unroll);
+    if (rv) return rv;
+    *n_out = (int)plan.segs.size();
+    if (grid_x) *grid_x = plan.max_tiles;
+    if (grid_y) *grid_y = (uint32_t)(plan.segs.size() > 65535 ? 65535 : plan.segs.size());
+    if (all_aligned) *all_aligned = plan.all_aligned ? 1 : 0;
+    if (out) {
+        if ((size_t)out_cap < plan.segs.size())
+            return fail(VCCL_ERR_ARG, "the plan has %zu descriptors, room for %d", plan.segs.size(), out_cap);
+        for (size_t i = 0; i < plan.segs.size(); ++i) {
+            out[i].src = reinterpret_cast<uintptr_t>(plan.segs[i].src);
+            out[i].dst = reinterpret_cast<uintptr_t>(plan.segs[i].dst);
+            out[i].bytes = plan.segs[i].bytes;
+            out[i].head = plan.segs[i].head;
+            out[i].reserved = 0;
         }
     }
     return VCCL_OK;
