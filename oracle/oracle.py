@@ -148,6 +148,20 @@ def moe_pack(x: np.ndarray, ids: np.ndarray, row_bytes: int, num_experts: int):
     return packed, order, cnt
 
 
+def moe_unpack(packed: np.ndarray, ids: np.ndarray, row_bytes: int, num_experts: int) -> np.ndarray:
+    """Inverse row movement of moe_pack: returns uint8 [T*K*row_bytes] in (token, slot) order."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    T, K = ids.shape
+    if _u8(packed).size < T * K * row_bytes:
+        raise ValueError("packed smaller than T*K rows")
+    out = np.empty(T * K * row_bytes, dtype=np.uint8)
+    rv = _load().oracle_moe_unpack(_vp(packed), _vp(ids), ctypes.c_int64(T), ctypes.c_int(K),
+                                   ctypes.c_uint64(row_bytes), ctypes.c_int(num_experts), _vp(out))
+    if rv:
+        raise OracleError(rv)
+    return out
+
+
 def moe_exchange_layout(cnt: np.ndarray, experts_per_rank: int, row_bytes: int):
     """cnt uint64 [P, E] -> dict of the four [P, P] byte matrices of the exchange."""
     cnt = np.ascontiguousarray(cnt, dtype=np.uint64)

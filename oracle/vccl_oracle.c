@@ -27,7 +27,8 @@
  * Pins: every routine here is pinned by tests/test_oracle_*.py (identity at
  * P = 1, NumPy axis swap, NumPy roll, NumPy stable argsort / bincount,
  * involution, conservation, untouched gaps, hand-worked fixtures, exhaustive
- * tiny cases).  No routine is "parity unpinned".
+ * tiny cases; unpack(pack(x)) = each row K times and a hand-worked fixture for the
+ * un-permute).  No routine is "parity unpinned".
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -169,6 +170,31 @@ int oracle_moe_pack(const uint8_t *x, const int32_t *ids, int64_t T, int K, uint
         const uint8_t *row = x + (uint64_t)(order[j] / K) * row_bytes;
         uint8_t *out = packed + (uint64_t)j * row_bytes;
         for (uint64_t i = 0; i < row_bytes; ++i) out[i] = row[i];
+    }
+    return ORACLE_OK;
+}
+
+/* MoE combine, un-permute step: the inverse of oracle_moe_pack's row movement.
+ * `packed` holds T*K rows in the packed order that ids defines (stable sort of the
+ * pairs by expert id); row p = t*K + k of `out` receives the packed row at the
+ * position pair p has in that order.  The combine phase mirrors dispatch (paper
+ * Section 6); summing the K rows of a token is a reduction and not modelled. */
+int oracle_moe_unpack(const uint8_t *packed, const int32_t *ids, int64_t T, int K, uint64_t row_bytes,
+                      int E, uint8_t *out)
+{
+    if (T < 0 || K < 1 || E < 1) return ORACLE_ERR_ARG;
+    const int64_t npairs = T * (int64_t)K;
+    for (int64_t p = 0; p < npairs; ++p)
+        if (ids[p] < 0 || ids[p] >= E) return ORACLE_ERR_ARG;
+    int64_t j = 0;   /* position in the packed order */
+    for (int e = 0; e < E; ++e) {
+        for (int64_t p = 0; p < npairs; ++p) {
+            if (ids[p] != e) continue;
+            const uint8_t *row = packed + (uint64_t)j * row_bytes;
+            uint8_t *dst = out + (uint64_t)p * row_bytes;
+            for (uint64_t i = 0; i < row_bytes; ++i) dst[i] = row[i];
+            ++j;
+        }
     }
     return ORACLE_OK;
 }

@@ -302,6 +302,29 @@ def pin_moe_pack_is_stable_argsort():
         assert (np.diff(keys[order]) >= 0).all()
 
 
+def pin_moe_unpack_handworked():
+    g = _load("moe_dispatch_p2_handworked.json")
+    for s in range(g["P"]):
+        out = oracle.moe_unpack(_b(g["unpack_in"][s]), np.array(g["ids"][s], np.int32), g["row_bytes"], g["E"])
+        assert _s(out) == g["unpack_out"][s]
+
+
+def pin_moe_unpack_inverts_pack():
+    """unpack(pack(x)) gives every row K times (dispatch then its inverse replicates),
+    and unpack is a permutation of rows: NumPy's scatter with the stable argsort."""
+    for seed, (T, K, E, row) in enumerate(((1, 1, 1, 4), (33, 3, 7, 8), (500, 8, 256, 16))):
+        ids = wl.zipf_topk_expert_ids(70 + seed, 0, T, K, E)
+        x = wl.payload_bytes(71 + seed, 0, T * row)
+        packed, order, _ = oracle.moe_pack(x, ids, row, E)
+        back = oracle.moe_unpack(packed, ids, row, E)
+        assert np.array_equal(back.reshape(T * K, row), np.repeat(x.reshape(T, row), K, axis=0))
+        y = wl.payload_bytes(72 + seed, 1, T * K * row)          # arbitrary distinct rows
+        got = oracle.moe_unpack(y, ids, row, E).reshape(T * K, row)
+        want = np.empty_like(got)
+        want[np.argsort(ids.reshape(-1), kind="stable")] = y.reshape(T * K, row)
+        assert np.array_equal(got, want)
+
+
 def pin_moe_layout_properties():
     rng = np.random.Generator(np.random.PCG64(9))
     for P, epr, row in ((1, 4, 2), (2, 3, 10), (8, 32, 14336)):
@@ -352,6 +375,8 @@ ALL_PINS = [
     pin_staged_equals_direct,
     pin_moe_handworked,
     pin_moe_pack_is_stable_argsort,
+    pin_moe_unpack_handworked,
+    pin_moe_unpack_inverts_pack,
     pin_moe_layout_properties,
     pin_moe_rejects_bad_ids,
     pin_pp_message_size,

@@ -31,6 +31,8 @@ MUTANTS = [
     ("moe_unstable_order", "for (int64_t p = 0; p < npairs; ++p) {\n            if (ids[p] == e)", "for (int64_t p = npairs - 1; p >= 0; --p) {\n            if (ids[p] == e)", 0),
     ("moe_row_of_slot_not_token", "(order[j] / K) * row_bytes", "(order[j] % K) * row_bytes", 0),
     ("moe_no_id_check", "if (ids[p] < 0 || ids[p] >= E) return ORACLE_ERR_ARG;", "if (ids[p] < 0 || ids[p] >= E) continue;", 0),
+    ("unpack_runs_forward", "uint8_t *dst = out + (uint64_t)p * row_bytes;\n            for (uint64_t i = 0; i < row_bytes; ++i) dst[i] = row[i];", "uint8_t *dst = out + (uint64_t)j * row_bytes; const uint8_t *rr = packed + (uint64_t)p * row_bytes;\n            for (uint64_t i = 0; i < row_bytes; ++i) dst[i] = rr[i];", 0),
+    ("unpack_unstable", "for (int64_t p = 0; p < npairs; ++p) {\n            if (ids[p] != e) continue;", "for (int64_t p = npairs - 1; p >= 0; --p) {\n            if (ids[p] != e) continue;", 0),
     ("layout_expert_block_shifted", "for (int e = r * experts_per_rank; e < (r + 1) * experts_per_rank; ++e)", "for (int e = r; e < E; e += P)", 0),
     ("layout_recv_not_transposed", "recvcounts[(size_t)r * P + s] = sendcounts[(size_t)s * P + r];", "recvcounts[(size_t)r * P + s] = sendcounts[(size_t)r * P + s];", 0),
     ("layout_sdispl_inclusive", "sdispls[(size_t)s * P + r] = acc;\n            acc += sendcounts[(size_t)s * P + r];", "acc += sendcounts[(size_t)s * P + r];\n            sdispls[(size_t)s * P + r] = acc;", 0),
