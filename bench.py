@@ -229,6 +229,11 @@ def main():
             fx = lambda: v.vccl_alltoallv(packed, lay["sendcounts"], lay["sdispls"], rcv,
                                           lay["recvcounts"], lay["rdispls"], P, v.MODE_CU, st)
             wx, _ = time_calls(torch, fx, 5, 2)
+            outp = [torch.empty(T * K * row, dtype=torch.uint8, device="cuda") for _ in range(P)]
+            fu = lambda: v.vccl_moe_unpack(packed, ids, P, T, K, row, E, outp, st)
+            wu, _ = time_calls(torch, fu, 5, 2)
+            del outp
+            out["moe_combine_unpack"] = {"GBps": 2.0 * P * T * K * row / (wu / 5) / 1e9, "ms": wu / 5 * 1e3}
             out["moe_dispatch"] = {
                 "pack_GBps": pack_bytes / (w / 5) / 1e9, "pack_ms": w / 5 * 1e3,
                 "exchange_GBps": 2.0 * float(lay["sendcounts"].sum()) / (wx / 5) / 1e9,

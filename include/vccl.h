@@ -183,6 +183,17 @@ int vccl_moe_pack(const void *const *x, const int32_t *const *expert_ids, int P,
                   int topk, uint64_t row_bytes, int num_experts, void *const *packed,
                   uint64_t *counts_dev, uint64_t *counts_host, uint32_t *bad_ids_dev, void *stream);
 
+/* MoE combine, un-permute step (Section 6: the combine phase mirrors dispatch).  The
+ * inverse of vccl_moe_pack for all P ranks: packed[s] holds tokens*topk rows in the
+ * packed order defined by expert_ids[s] (for instance the rows that came back
+ * through vccl_alltoallv with the receive description used as the send description);
+ * row t*topk + k of out[s] receives the packed row that pair (t, k) had been sent
+ * to.  Rows of pairs with out-of-range ids are left untouched.  Pure data movement:
+ * the weighted sum over the topk rows of a token is a reduction and not part of
+ * this library.  Same alignment rules as vccl_moe_pack. */
+int vccl_moe_unpack(const void *const *packed, const int32_t *const *expert_ids, int P, int tokens,
+                    int topk, uint64_t row_bytes, int num_experts, void *const *out, void *stream);
+
 /* Host-side planner step between pack and exchange: from counts [P][num_experts]
  * (host) build the four [P][P] byte matrices for vccl_alltoallv.  Expert e lives on
  * rank e / experts_per_rank; sdispls / rdispls are exclusive prefix sums (packed

@@ -46,6 +46,8 @@ EXPORTS = {
     "vccl_moe_pack": (ctypes.c_int, [_vpp, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                      ctypes.c_uint64, ctypes.c_int, _vpp, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+    "vccl_moe_unpack": (ctypes.c_int, [_vpp, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                       ctypes.c_uint64, ctypes.c_int, _vpp, ctypes.c_void_p]),
     "vccl_moe_exchange_layout": (ctypes.c_int, [_u64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                 ctypes.c_uint64, _u64p, _u64p, _u64p, _u64p]),
     "vccl_fma_probe": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32,
@@ -212,6 +214,14 @@ def vccl_moe_pack(x, expert_ids, P: int, tokens: int, topk: int, row_bytes: int,
                                 num_experts, _ptrs(packed), ctypes.c_void_p(_addr(counts_dev)),
                                 ctypes.c_void_p(_addr(counts_host)),
                                 ctypes.c_void_p(_addr(bad_ids_dev)), _stream(stream)))
+
+
+def vccl_moe_unpack(packed, expert_ids, P: int, tokens: int, topk: int, row_bytes: int,
+                    num_experts: int, out, stream=None) -> None:
+    if len(packed) != P or len(expert_ids) != P or len(out) != P:
+        raise ValueError("per-rank arrays must have P entries")
+    _check(load().vccl_moe_unpack(_ptrs(packed), _ptrs(expert_ids), P, tokens, topk, int(row_bytes),
+                                  num_experts, _ptrs(out), _stream(stream)))
 
 
 def vccl_moe_exchange_layout(counts, P: int, num_experts: int, experts_per_rank: int, row_bytes: int):

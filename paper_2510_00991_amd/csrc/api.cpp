@@ -503,6 +503,31 @@ int vccl_moe_pack(const void *const *x, const int32_t *const *expert_ids, int P,
                            (hipStream_t)stream);
 }
 
+int vccl_moe_unpack(const void *const *packed, const int32_t *const *expert_ids, int P, int tokens,
+                    int topk, uint64_t row_bytes, int num_experts, void *const *out, void *stream) {
+    auto c = ctx_get();
+    int rv = check_common(c, P, packed, out);
+    if (rv) return rv;
+    if (!expert_ids) return fail(VCCL_ERR_ARG, "expert_ids is NULL");
+    if (tokens < 0 || topk < 1 || topk > 64)
+        return fail(VCCL_ERR_ARG, "tokens = %d, topk = %d (topk must be 1..64)", tokens, topk);
+    if (num_experts < 1 || num_experts > 1024)
+        return fail(VCCL_ERR_ARG, "num_experts = %d is outside 1..1024", num_experts);
+    if (row_bytes == 0 || (row_bytes & 15u))
+        return fail(VCCL_ERR_ARG, "row_bytes = %llu must be a positive multiple of 16",
+                    (unsigned long long)row_bytes);
+    if ((uint64_t)tokens * (uint64_t)topk > 0x7fffffffull)
+        return fail(VCCL_ERR_UNSUPPORTED, "more than 2^31 (token, slot) pairs per rank");
+    for (int s = 0; s < P; ++s) {
+        if (tokens && (!packed[s] || !expert_ids[s] || !out[s]))
+            return fail(VCCL_ERR_ARG, "NULL buffer for rank %d", s);
+        if ((reinterpret_cast<uintptr_t>(packed[s]) | reinterpret_cast<uintptr_t>(out[s])) & 15u)
+            return fail(VCCL_ERR_ARG, "packed / out of rank %d are not 16-byte aligned", s);
+    }
+    return launch_moe_unpack(c->moe, packed, expert_ids, P, tokens, topk, row_bytes, num_experts, out,
+                             (hipStream_t)stream);
+}
+
 int vccl_moe_exchange_layout(const uint64_t *counts, int P, int num_experts, int experts_per_rank,
                              uint64_t row_bytes, uint64_t *sendcounts, uint64_t *sdispls,
                              uint64_t *recvcounts, uint64_t *rdispls) {

@@ -146,6 +146,10 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
                     void *const *packed, uint64_t *counts_dev, uint64_t *counts_host,
                     uint32_t *bad_ids_dev, int gather_variant, hipStream_t stream);
 
+int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *const *ids, int P,
+                      int tokens, int topk, uint64_t row_bytes, int num_experts, void *const *out,
+                      hipStream_t stream);
+
 // ---- co-run probe
 int launch_fma_probe(float *out, uint32_t workgroups, uint32_t threads, uint64_t iters,
                      hipStream_t stream);

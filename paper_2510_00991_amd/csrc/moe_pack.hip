@@ -12,6 +12,8 @@
 //   3 rank        wavefront ballot matching gives each pair its stable position
 //   4 gather      one wavefront per token reads the row once into registers and
 //                 stores it to its K destinations (16 bytes per lane per access)
+// The combine direction (vccl_moe_unpack) reuses launches 1-3 and replaces the
+// gather by its inverse: row dest(t,k) of the packed buffer goes to row t*K+k.
 #include "common.h"
 
 namespace vccl {
@@ -174,6 +176,35 @@ __global__ __launch_bounds__(kMoeThreads) void moe_gather_kernel(MoePtrs ptrs, u
     }
 }
 
+// Inverse of the gather (combine direction): one workgroup per pair p = t*K + k
+// copies the packed row that pair was sent to back to row p of `out`.  Writes sweep
+// `out` front to back (the tight address window HBM likes), reads hop between
+// expert regions in 14 KiB rows; every row is read once and written once.
+__global__ __launch_bounds__(kMoeThreads) void moe_scatter_back_kernel(MoePtrs ptrs, uint32_t row_vecs,
+                                                                       const uint32_t *dest,
+                                                                       uint32_t npairs) {
+    constexpr int kV = 4;
+    const uint32_t rank = blockIdx.y;
+    const uint32_t p = blockIdx.x;
+    const uint32_t j = dest[(size_t)rank * npairs + p];
+    if (j == kDropped) return;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(ptrs.x[rank]) + (size_t)j * row_vecs;   // packed side
+    u32x4 *o = reinterpret_cast<u32x4 *>(ptrs.packed[rank]) + (size_t)p * row_vecs;          // token order
+    for (uint32_t v0 = 0; v0 < row_vecs; v0 += (uint32_t)kMoeThreads * kV) {
+        u32x4 r[kV];
+#pragma unroll
+        for (int u = 0; u < kV; ++u) {
+            const uint32_t v = v0 + u * kMoeThreads + threadIdx.x;
+            if (v < row_vecs) r[u] = __builtin_nontemporal_load(row + v);
+        }
+#pragma unroll
+        for (int u = 0; u < kV; ++u) {
+            const uint32_t v = v0 + u * kMoeThreads + threadIdx.x;
+            if (v < row_vecs) __builtin_nontemporal_store(r[u], o + v);
+        }
+    }
+}
+
 void MoeScratch::destroy() {
     if (done) {
         (void)hipEventSynchronize(done);
@@ -189,15 +220,17 @@ void MoeScratch::destroy() {
     hist_n = ptrs_n = 0;
 }
 
-int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P, int tokens,
-                    int topk, uint64_t row_bytes, int num_experts, void *const *packed,
-                    uint64_t *counts_dev, uint64_t *counts_host, uint32_t *bad_ids_dev,
-                    int gather_variant, hipStream_t stream) {
+// Launches 1-3: per-pair destination rows in the scratch.  `a` / `b` are the two
+// row buffers of every rank in the roles (read side, written side) of launch 4.
+static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *const *ids, int P,
+                           int tokens, int topk, int num_experts, void *const *b, uint64_t *counts_dev,
+                           uint32_t *bad_ids_dev, hipStream_t stream, MoePtrs *ptrs_out,
+                           uint32_t **dest_out) {
     const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
     const uint32_t nblk = npairs ? (npairs + kPairsPerBlock - 1) / kPairsPerBlock : 1;
     const size_t hist_n = (size_t)P * nblk * (size_t)num_experts;
-    const size_t need = hist_n + (size_t)P * npairs;   // histograms, then destination rows
-    std::lock_guard<std::mutex> lk(sc.mu);
+    const size_t counts_words = 2 * (size_t)P * num_experts;            // private uint64 counts
+    const size_t need = hist_n + (size_t)P * npairs + counts_words + 2;  // histograms, rows, counts
     if (!sc.done) VCCL_HIP(hipEventCreateWithFlags(&sc.done, hipEventDisableTiming));
     // The scratch is shared: a new call starts after the previous one has finished
     // with it on the device, and the pinned pointer staging is free again.
@@ -220,9 +253,9 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
         sc.ptrs_n = (size_t)3 * P;
     }
     for (int s = 0; s < P; ++s) {
-        sc.ptrs_host[s] = const_cast<void *>(x[s]);
+        sc.ptrs_host[s] = const_cast<void *>(a[s]);
         sc.ptrs_host[P + s] = const_cast<int32_t *>(ids[s]);
-        sc.ptrs_host[2 * P + s] = packed[s];
+        sc.ptrs_host[2 * P + s] = b[s];
     }
     VCCL_HIP(hipMemcpyAsync(sc.ptrs, sc.ptrs_host, (size_t)3 * P * sizeof(void *),
                             hipMemcpyHostToDevice, stream));
@@ -232,9 +265,12 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
     ptrs.packed = reinterpret_cast<uint8_t *const *>(sc.ptrs + 2 * P);
     uint32_t *hist = sc.hist;
     uint32_t *dest = sc.hist + hist_n;
+    if (!counts_dev) {   // the caller does not want the counts: keep them in the scratch (8-byte aligned)
+        uintptr_t p = reinterpret_cast<uintptr_t>(dest + (size_t)P * npairs);
+        counts_dev = reinterpret_cast<uint64_t *>((p + 7u) & ~(uintptr_t)7u);
+    }
     int ebits = 0;
     while ((1 << ebits) < num_experts) ++ebits;
-
     moe_hist_kernel<<<dim3(nblk, P), dim3(kMoeThreads), 0, stream>>>(ptrs, npairs, num_experts, nblk,
                                                                     hist, bad_ids_dev);
     VCCL_HIP(hipGetLastError());
@@ -244,6 +280,24 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
         moe_rank_kernel<<<dim3(nblk, P), dim3(kMoeThreads), 0, stream>>>(ptrs, npairs, num_experts,
                                                                         ebits, nblk, hist, dest);
         VCCL_HIP(hipGetLastError());
+    }
+    *ptrs_out = ptrs;
+    *dest_out = dest;
+    return VCCL_OK;
+}
+
+int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P, int tokens,
+                    int topk, uint64_t row_bytes, int num_experts, void *const *packed,
+                    uint64_t *counts_dev, uint64_t *counts_host, uint32_t *bad_ids_dev,
+                    int gather_variant, hipStream_t stream) {
+    const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
+    std::lock_guard<std::mutex> lk(sc.mu);
+    MoePtrs ptrs;
+    uint32_t *dest = nullptr;
+    int rc = moe_index_phase(sc, x, ids, P, tokens, topk, num_experts, packed, counts_dev, bad_ids_dev,
+                             stream, &ptrs, &dest);
+    if (rc) return rc;
+    if (npairs) {
         const uint32_t tok_blocks = ((uint32_t)tokens + kMoeThreads / 64 - 1) / (kMoeThreads / 64);
         const dim3 g(tok_blocks, P), b(kMoeThreads);
         const uint32_t rv = (uint32_t)(row_bytes >> 4);
@@ -259,6 +313,25 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
     if (counts_host)
         VCCL_HIP(hipMemcpyAsync(counts_host, counts_dev, (size_t)P * num_experts * sizeof(uint64_t),
                                 hipMemcpyDeviceToHost, stream));
+    VCCL_HIP(hipEventRecord(sc.done, stream));
+    return VCCL_OK;
+}
+
+int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *const *ids, int P,
+                      int tokens, int topk, uint64_t row_bytes, int num_experts, void *const *out,
+                      hipStream_t stream) {
+    const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
+    std::lock_guard<std::mutex> lk(sc.mu);
+    MoePtrs ptrs;
+    uint32_t *dest = nullptr;
+    int rc = moe_index_phase(sc, packed, ids, P, tokens, topk, num_experts, out, nullptr, nullptr, stream,
+                             &ptrs, &dest);
+    if (rc) return rc;
+    if (npairs) {
+        moe_scatter_back_kernel<<<dim3(npairs, P), dim3(kMoeThreads), 0, stream>>>(
+            ptrs, (uint32_t)(row_bytes >> 4), dest, npairs);
+        VCCL_HIP(hipGetLastError());
+    }
     VCCL_HIP(hipEventRecord(sc.done, stream));
     return VCCL_OK;
 }

@@ -116,6 +116,86 @@ def test_out_of_range_ids_are_counted_and_dropped(vccl):
     assert counts.cpu().numpy().sum() == keep.sum()
 
 
+def _combine(torch, v, P, T, K, E, row, seed, mode):
+    """Dispatch then combine: pack, exchange, exchange back with the receive
+    description as the send description, un-permute; against the oracle chain."""
+    epr = E // P
+    x_np = [wl.payload_bytes(seed, s, T * row) for s in range(P)]
+    ids_np = [wl.zipf_topk_expert_ids(seed, s, T, K, E) for s in range(P)]
+    st = stream_handle(torch)
+    x = [to_dev(torch, a) for a in x_np]
+    ids = [torch.from_numpy(a.reshape(-1).copy()).cuda() for a in ids_np]
+    packed = [torch.zeros(T * K * row, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    counts_dev = torch.zeros((P, E), dtype=torch.int64, device="cuda")
+    counts_host = torch.zeros((P, E), dtype=torch.int64).pin_memory()
+    v.vccl_moe_pack(x, ids, P, T, K, row, E, packed, counts_dev, counts_host, None, st)
+    torch.cuda.synchronize()
+    lay = v.vccl_moe_exchange_layout(counts_host.numpy().astype(np.uint64), P, E, epr, row)
+    rsz = [int(lay["recvcounts"][r].sum()) for r in range(P)]
+    recv = [torch.zeros(max(16, rsz[r]), dtype=torch.uint8, device="cuda") for r in range(P)]
+    v.vccl_alltoallv(packed, lay["sendcounts"], lay["sdispls"], recv, lay["recvcounts"], lay["rdispls"],
+                     P, mode, st)
+    # "expert computation": flip every byte on the receiving rank, so that the way back carries new data
+    for r in range(P):
+        recv[r].bitwise_not_()
+    back = [torch.full((T * K * row,), SENTINEL, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    v.vccl_alltoallv(recv, lay["recvcounts"], lay["rdispls"], back, lay["sendcounts"], lay["sdispls"],
+                     P, mode, st)
+    out = [torch.full((T * K * row + 16,), SENTINEL, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    v.vccl_moe_unpack(back, ids, P, T, K, row, E, out, st)
+    torch.cuda.synchronize()
+    # oracle chain
+    opk = [oracle.moe_pack(x_np[s], ids_np[s], row, E) for s in range(P)]
+    olay = oracle.moe_exchange_layout(np.stack([o[2] for o in opk]), epr, row)
+    orecv = [np.zeros(max(16, rsz[r]), np.uint8) for r in range(P)]
+    oracle.alltoallv([o[0] for o in opk], olay["sendcounts"], olay["sdispls"], orecv, olay["recvcounts"],
+                     olay["rdispls"])
+    orecv = [np.bitwise_not(a) for a in orecv]
+    oback = [np.full(T * K * row, SENTINEL, np.uint8) for _ in range(P)]
+    oracle.alltoallv(orecv, olay["recvcounts"], olay["rdispls"], oback, olay["sendcounts"], olay["sdispls"])
+    for s in range(P):
+        assert_same(to_host(back[s]), oback[s], f"combine exchange, rank {s}")
+        want = oracle.moe_unpack(oback[s], ids_np[s], row, E)
+        got = to_host(out[s])
+        assert_same(got[:T * K * row], want, f"unpack, rank {s}")
+        assert (got[T * K * row:] == SENTINEL).all()
+        # dispatch . expert . combine = every token's row, K times, with the expert's change applied
+        assert np.array_equal(want.reshape(T * K, row),
+                              np.repeat(np.bitwise_not(x_np[s]).reshape(T, row), K, axis=0))
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1, 16), (2, 77, 2, 6, 48), (4, 1000, 4, 64, 14336),
+                                   (8, 2049, 8, 256, 272)])
+def test_combine_roundtrip(vccl, shape):
+    torch = require_gpu()
+    P, T, K, E, row = shape
+    _combine(torch, vccl, P, T, K, E, row, 900 + T, vccl.MODE_CU)
+
+
+def test_combine_roundtrip_copy_engine(vccl):
+    torch = require_gpu()
+    _combine(torch, vccl, 4, 600, 8, 64, 2048, 901, vccl.MODE_CE)
+
+
+def test_unpack_leaves_rows_of_dropped_pairs_untouched(vccl):
+    torch = require_gpu()
+    T, K, E, row = 40, 2, 4, 32
+    ids_np = wl.zipf_topk_expert_ids(5, 0, T, K, E).copy()
+    ids_np[7, 0] = 99
+    packed_np = wl.payload_bytes(8, 0, T * K * row)
+    packed = to_dev(torch, packed_np)
+    ids = torch.from_numpy(ids_np.reshape(-1).copy()).cuda()
+    out = torch.full((T * K * row,), SENTINEL, dtype=torch.uint8, device="cuda")
+    vccl.vccl_moe_unpack([packed], [ids], 1, T, K, row, E, [out], stream_handle(torch))
+    torch.cuda.synchronize()
+    keys = ids_np.reshape(-1)
+    keep = (keys >= 0) & (keys < E)
+    order = np.argsort(np.where(keep, keys, E), kind="stable")[:keep.sum()]
+    want = np.full((T * K, row), SENTINEL, np.uint8)
+    want[order] = packed_np.reshape(T * K, row)[:keep.sum()]
+    assert_same(to_host(out), want.reshape(-1), "unpack with a dropped pair")
+
+
 def test_config3_moe_dispatch_full_size(vccl):
     """P = 8, 8192 tokens x 7168 bf16 N(0,1) per rank, top-8 of 256 experts with
     Zipf(1.2) ids: pack (65 536 rows of 14 336 B per rank) then AlltoAllv."""
