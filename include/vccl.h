@@ -212,6 +212,33 @@ int vccl_moe_exchange_layout(const uint64_t *counts, int P, int num_experts, int
 int vccl_fma_probe(float *out_dev, uint32_t workgroups, uint32_t threads, uint64_t iters,
                    void *stream);
 
+/* Window-based bandwidth monitor (Section 3.4), host-only and usable on its own:
+ * feed it the post and completion times of messages (nanoseconds on any monotonic
+ * clock, calls in non-decreasing time order) and it returns, per completion, the
+ * per-message estimate bytes/(t2-t1), the sliding-window estimate (sum of the bytes
+ * of the last `window` completed messages over the span from their earliest post to
+ * their latest completion; the paper deploys window = 8), the bytes still
+ * outstanding, and the anomaly flag: window estimate below half the mean of the
+ * estimates of the `history_ns` that precede the current window AND outstanding
+ * bytes above twice the largest amount seen in that span (the paper uses about
+ * 10 ms).  Bandwidths are in bytes per second.  vccl_monitor_create returns NULL on
+ * bad arguments.  The copy-engine proxy runs one monitor per primitive over the
+ * operations it issues (vccl_proxy_monitor: primitive 0 = SendRecv, 1 = AlltoAll(v)). */
+typedef struct vccl_monitor vccl_monitor;
+typedef struct {
+    uint64_t t_ns;
+    double bw_message;
+    double bw_window;
+    uint64_t outstanding;
+    int anomaly;
+} vccl_monitor_sample;
+vccl_monitor *vccl_monitor_create(int window, uint64_t history_ns);
+void vccl_monitor_destroy(vccl_monitor *m);
+int vccl_monitor_post(vccl_monitor *m, uint64_t id, uint64_t bytes, uint64_t t_post_ns);
+int vccl_monitor_complete(vccl_monitor *m, uint64_t id, uint64_t t_done_ns, vccl_monitor_sample *out);
+int vccl_monitor_totals(vccl_monitor *m, uint64_t *messages, uint64_t *anomalies, vccl_monitor_sample *last);
+int vccl_proxy_monitor(int primitive, uint64_t *messages, uint64_t *anomalies, vccl_monitor_sample *last);
+
 /* Counters of the copy-engine proxy since vccl_init: operations, copies issued,
  * bytes, and nanoseconds the proxy spent issuing.  Any pointer may be NULL. */
 int vccl_proxy_stats(uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t *issue_ns);

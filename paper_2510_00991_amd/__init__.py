@@ -15,4 +15,6 @@ from .binding import (  # noqa: F401
     vccl_alltoall, vccl_alltoallv, vccl_plan_alltoallv,
     vccl_moe_pack, vccl_moe_unpack, vccl_moe_exchange_layout,
     vccl_fma_probe, vccl_proxy_stats, vccl_device_cu_count,
+    vccl_monitor_create, vccl_monitor_destroy, vccl_monitor_post, vccl_monitor_complete,
+    vccl_monitor_totals, vccl_proxy_monitor,
 )

@@ -52,6 +52,12 @@ EXPORTS = {
                                                 ctypes.c_uint64, _u64p, _u64p, _u64p, _u64p]),
     "vccl_fma_probe": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32,
                                       ctypes.c_uint64, ctypes.c_void_p]),
+    "vccl_monitor_create": (ctypes.c_void_p, [ctypes.c_int, ctypes.c_uint64]),
+    "vccl_monitor_destroy": (None, [ctypes.c_void_p]),
+    "vccl_monitor_post": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64]),
+    "vccl_monitor_complete": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_void_p]),
+    "vccl_monitor_totals": (ctypes.c_int, [ctypes.c_void_p, _u64p, _u64p, ctypes.c_void_p]),
+    "vccl_proxy_monitor": (ctypes.c_int, [ctypes.c_int, _u64p, _u64p, ctypes.c_void_p]),
     "vccl_proxy_stats": (ctypes.c_int, [_u64p, _u64p, _u64p, _u64p]),
     "vccl_device_cu_count": (ctypes.c_int, []),
 }
@@ -230,6 +236,48 @@ def vccl_moe_exchange_layout(counts, P: int, num_experts: int, experts_per_rank:
     _check(load().vccl_moe_exchange_layout(_p64(cnt), P, num_experts, experts_per_rank,
                                            int(row_bytes), *[_p64(o) for o in out]))
     return {"sendcounts": out[0], "sdispls": out[1], "recvcounts": out[2], "rdispls": out[3]}
+
+
+class MonitorSample(ctypes.Structure):
+    _fields_ = [("t_ns", ctypes.c_uint64), ("bw_message", ctypes.c_double), ("bw_window", ctypes.c_double),
+                ("outstanding", ctypes.c_uint64), ("anomaly", ctypes.c_int)]
+
+    def as_dict(self):
+        return {"t_ns": self.t_ns, "bw_message": self.bw_message, "bw_window": self.bw_window,
+                "outstanding": self.outstanding, "anomaly": bool(self.anomaly)}
+
+
+def vccl_monitor_create(window: int = 8, history_ns: int = 10_000_000) -> int:
+    h = load().vccl_monitor_create(window, history_ns)
+    if not h:
+        raise VcclError(-1, vccl_last_error())
+    return h
+
+
+def vccl_monitor_destroy(handle: int) -> None:
+    load().vccl_monitor_destroy(handle)
+
+
+def vccl_monitor_post(handle: int, msg_id: int, nbytes: int, t_post_ns: int) -> None:
+    _check(load().vccl_monitor_post(handle, msg_id, nbytes, t_post_ns))
+
+
+def vccl_monitor_complete(handle: int, msg_id: int, t_done_ns: int) -> dict:
+    s = MonitorSample()
+    _check(load().vccl_monitor_complete(handle, msg_id, t_done_ns, ctypes.byref(s)))
+    return s.as_dict()
+
+
+def vccl_monitor_totals(handle: int) -> dict:
+    a, b, s = ctypes.c_uint64(), ctypes.c_uint64(), MonitorSample()
+    _check(load().vccl_monitor_totals(handle, ctypes.byref(a), ctypes.byref(b), ctypes.byref(s)))
+    return {"messages": a.value, "anomalies": b.value, "last": s.as_dict()}
+
+
+def vccl_proxy_monitor(primitive: int) -> dict:
+    a, b, s = ctypes.c_uint64(), ctypes.c_uint64(), MonitorSample()
+    _check(load().vccl_proxy_monitor(primitive, ctypes.byref(a), ctypes.byref(b), ctypes.byref(s)))
+    return {"messages": a.value, "anomalies": b.value, "last": s.as_dict()}
 
 
 def vccl_fma_probe(out_dev, workgroups: int, threads: int, iters: int, stream=None) -> None:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvccl.so")
-SOURCES = ["api.cpp", "proxy.cpp", "copy_kernel.hip", "moe_pack.hip", "fifo_kernel.hip", "probe.hip"]
+SOURCES = ["api.cpp", "proxy.cpp", "monitor.cpp", "copy_kernel.hip", "moe_pack.hip", "fifo_kernel.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",

@@ -626,6 +626,14 @@ int vccl_proxy_stats(uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t 
     return VCCL_OK;
 }
 
+int vccl_proxy_monitor(int primitive, uint64_t *messages, uint64_t *anomalies, vccl_monitor_sample *last) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    vccl_monitor *m = proxy_monitor(c->proxy, primitive);
+    if (!m) return fail(VCCL_ERR_ARG, "primitive must be 0 (SendRecv) or 1 (AlltoAll(v))");
+    return vccl_monitor_totals(m, messages, anomalies, last);
+}
+
 int vccl_p2p_reginfo(int receiver_rank, uint64_t *receiver_ready, uint64_t *copy_started,
                      uint64_t *copy_done, void **receiver_reg_addr) {
     auto c = ctx_get();

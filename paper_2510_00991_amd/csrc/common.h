@@ -177,6 +177,7 @@ int proxy_drain(Proxy *p);
 bool proxy_sdma_available(Proxy *p, const char **why);
 int proxy_engine_count(Proxy *p);
 uint64_t proxy_sdma_errors(Proxy *p);
+vccl_monitor *proxy_monitor(Proxy *p, int primitive);
 void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t *issue_ns);
 
 }  // namespace vccl

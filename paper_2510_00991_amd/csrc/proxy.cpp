@@ -70,6 +70,8 @@ struct Op {
     uint64_t *done_word = nullptr;             // signal memory, waited on by the caller's stream
     hsa_signal_t left = {0};                   // outstanding copies
     uint64_t seq = 0;
+    int primitive = 1;                         // 0 SendRecv, 1 AlltoAll(v): which monitor sees the op
+    uint64_t monitor_id = 0;
     bool host_sync = false;                    // no stream memory operations: the caller blocks
     int max_engines = 0;
     bool sdma_failed = false;
@@ -101,6 +103,13 @@ public:
     int nengines = 0;
     unsigned next_engine = 0;
     void *warm = nullptr;
+    // one window monitor per primitive over the operations issued (Section 3.4)
+    vccl_monitor *monitor[2] = {nullptr, nullptr};
+    uint64_t next_monitor_id = 0;
+    static uint64_t now_ns() {
+        return (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+                   std::chrono::steady_clock::now().time_since_epoch()).count();
+    }
 
     void run();
     void issue_events(Op *op);
@@ -294,6 +303,8 @@ void Proxy::issue_events(Op *op) {
     }
     cv_issued.notify_all();
     if (err == hipSuccess) {
+        op->monitor_id = ++next_monitor_id;
+        (void)vccl_monitor_post(monitor[op->primitive], op->monitor_id, bytes, now_ns());
         pending.push_back(op);
     } else {
         std::lock_guard<std::mutex> lk(mu);
@@ -333,11 +344,14 @@ bool Proxy::issue_sdma(Op *op) {
     n_bytes.fetch_add(bytes, std::memory_order_relaxed);
     issue_ns.fetch_add((uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(t1 - t0).count(),
                        std::memory_order_relaxed);
+    op->monitor_id = ++next_monitor_id;
+    (void)vccl_monitor_post(monitor[op->primitive], op->monitor_id, bytes, now_ns());
     pending.push_back(op);
     return true;
 }
 
 void Proxy::finish(Op *op) {
+    (void)vccl_monitor_complete(monitor[op->primitive], op->monitor_id, now_ns(), nullptr);
     for (auto &c : op->conns) reg[c.first].copyDone.store(c.second, std::memory_order_release);
     if (op->kind == VCCL_CE_SDMA) {
         if (op->sdma_failed) sdma_errors.fetch_add(1, std::memory_order_relaxed);
@@ -429,6 +443,8 @@ Proxy *proxy_create(int device, int max_streams) {
         }
     }
     p->setup_sdma();
+    p->monitor[0] = vccl_monitor_create(8, 10000000ull);   // window 8, 10 ms: the paper's values
+    p->monitor[1] = vccl_monitor_create(8, 10000000ull);
     p->th = std::thread([p] { p->run(); });
     return p;
 }
@@ -468,6 +484,8 @@ void proxy_destroy(Proxy *p) {
         if (op->left.handle) hsa_signal_destroy(op->left);
         delete op;
     }
+    vccl_monitor_destroy(p->monitor[0]);
+    vccl_monitor_destroy(p->monitor[1]);
     if (p->warm) (void)hipFree(p->warm);
     if (p->hsa_up) hsa_shut_down();
     delete p;
@@ -495,6 +513,7 @@ int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hip
     op->want_streams = opt.ce_streams;
     op->kind = opt.ce_kind;
     op->max_engines = opt.ce_max_engines;
+    op->primitive = receivers ? 0 : 1;
     if (op->kind == VCCL_CE_SDMA) return submit_sdma(p, op, stream, receivers);
 
     hipError_t e = hipEventRecord(op->ready, stream);
@@ -631,6 +650,10 @@ void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uin
 }
 
 uint64_t proxy_sdma_errors(Proxy *p) { return p->sdma_errors.load(); }
+
+vccl_monitor *proxy_monitor(Proxy *p, int primitive) {
+    return (primitive == 0 || primitive == 1) ? p->monitor[primitive] : nullptr;
+}
 
 int proxy_reginfo(Proxy *p, int receiver, uint64_t *ready, uint64_t *started, uint64_t *done,
                   void **addr) {

@@ -135,3 +135,35 @@ def test_ce_handshake_record_advances(vccl):
             assert addr == recv[r].data_ptr()
     st = vccl.vccl_proxy_stats()
     assert st["ops"] >= 3 and st["bytes"] >= 3 * P * n
+
+
+def test_proxy_window_monitor_sees_copy_engine_operations(vccl):
+    """The proxy feeds one window monitor per primitive with the operations it
+    issues: message counts advance and the window estimate is a sane copy rate."""
+    torch = require_gpu()
+    P, n = 4, 8 << 20
+    to, frm = wl.ring_peers(P)
+    send = [to_dev(torch, wl.payload_bytes(18, s, n)) for s in range(P)]
+    recv = [to_dev(torch, np.zeros(n, np.uint8)) for _ in range(P)]
+    before = [vccl.vccl_proxy_monitor(k) for k in (0, 1)]
+    st = stream_handle(torch)
+    for _ in range(12):
+        vccl.vccl_sendrecv(send, [n] * P, to, recv, [n] * P, frm, P, vccl.MODE_CE, st)
+    for _ in range(5):
+        vccl.vccl_alltoall(send, recv, n // P, P, vccl.MODE_CE, st)
+    torch.cuda.synchronize()
+    import time
+    deadline = time.time() + 5
+    while time.time() < deadline:
+        after = [vccl.vccl_proxy_monitor(k) for k in (0, 1)]
+        if after[0]["messages"] == before[0]["messages"] + 12 and after[1]["messages"] == before[1]["messages"] + 5:
+            break
+        time.sleep(0.001)
+    assert after[0]["messages"] == before[0]["messages"] + 12
+    assert after[1]["messages"] == before[1]["messages"] + 5
+    for k in (0, 1):
+        bw = after[k]["last"]["bw_window"]
+        assert 1e9 < bw < 2e12, bw            # between 1 GB/s and 2 TB/s of copy rate
+        assert after[k]["last"]["outstanding"] == 0
+    with pytest.raises(vccl.VcclError):
+        vccl.vccl_proxy_monitor(2)
