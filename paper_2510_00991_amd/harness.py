@@ -4,7 +4,7 @@ effect the paper describes in Appendix E), the pipeline SendRecv ring and the
 P = 64 message-size sweep.  PyTorch is used for device memory, streams and
 events only; every byte is moved by libvccl.
 
-CLI:  python -m paper_2510_00991_amd.harness ring|sweep|all  [--json FILE]
+CLI:  python -m paper_2510_00991_amd.harness ring|sweep|pipeline|all  [--json FILE]
 """
 from __future__ import annotations
 
@@ -205,9 +205,117 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
     return {"workload": f"AlltoAll sweep, P={P}, per-peer 4 KiB..4 MiB", "rows": rows}
 
 
+def _schedule_1f1b(stages, micro):
+    """Per stage, the 1F1B order of ("F", m) / ("B", m) steps (warm-up forwards,
+    then one forward one backward, then the remaining backwards)."""
+    out = []
+    for i in range(stages):
+        w = min(stages - 1 - i, micro)
+        ops = [("F", m) for m in range(w)]
+        for j in range(micro - w):
+            ops += [("F", w + j), ("B", j)]
+        ops += [("B", m) for m in range(micro - w, micro)]
+        out.append(ops)
+    return out
+
+
+def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000, reps=5):
+    """Emulation of the paper's pipeline figure (1F1B, 8 microbatches, 4 workers) on
+    one device: every stage computes on its own stream with the FMA probe sized to a
+    quarter of the compute units (forward = fwd_iters rounds, backward twice that),
+    activations go to the next stage and gradients to the previous one through
+    vccl_sendrecv on per-link streams.  Reports the iteration time per transfer mode
+    and without any transfer, and the paper's gain I = (T_n - T_v) / (T_v + alpha)
+    with alpha = 0 (no data-parallel traffic here), T_n the compute-unit path."""
+    cu = v.vccl_device_cu_count()
+    wg = max(1, cu // stages)
+    sched = _schedule_1f1b(stages, micro)
+    comp = [torch.cuda.Stream() for _ in range(stages)]
+    link_f = [torch.cuda.Stream() for _ in range(stages)]     # stage i -> i+1
+    link_b = [torch.cuda.Stream() for _ in range(stages)]     # stage i -> i-1
+    outs = [torch.zeros(wg * 256, dtype=torch.float32, device="cuda") for _ in range(stages)]
+    src_f = [[torch.zeros(act_bytes, dtype=torch.uint8, device="cuda") for _ in range(2)] for _ in range(stages)]
+    dst_f = [[torch.zeros(act_bytes, dtype=torch.uint8, device="cuda") for _ in range(2)] for _ in range(stages)]
+    src_b = [[torch.zeros(act_bytes, dtype=torch.uint8, device="cuda") for _ in range(2)] for _ in range(stages)]
+    dst_b = [[torch.zeros(act_bytes, dtype=torch.uint8, device="cuda") for _ in range(2)] for _ in range(stages)]
+    null = torch.zeros(16, dtype=torch.uint8, device="cuda")
+
+    def transfer(mode, src, dst, stream):
+        v.vccl_sendrecv([src, null], [act_bytes, 0], [1, 0], [null, dst], [0, act_bytes], [1, 0], 2, mode,
+                        int(stream.cuda_stream))
+
+    def iteration(mode):
+        """Enqueue one whole iteration; returns the wall time from the first launch to
+        the completion of every stream."""
+        done = {}                      # (kind, stage, m) -> event after the step's compute
+        arrived = {}                   # (kind, stage, m) -> event after the step's input has landed
+        pos = [0] * stages
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        progress = True
+        while progress:
+            progress = False
+            for i in range(stages):
+                while pos[i] < len(sched[i]):
+                    kind, m = sched[i][pos[i]]
+                    need = None
+                    if kind == "F" and i > 0:
+                        need = ("F", i, m)
+                    if kind == "B" and i < stages - 1:
+                        need = ("B", i, m)
+                    if need is not None and mode is not None and need not in arrived:
+                        break
+                    if need is not None and mode is None:
+                        dep = ("F", i - 1, m) if kind == "F" else ("B", i + 1, m)
+                        if dep not in done:
+                            break
+                        comp[i].wait_event(done[dep])
+                    elif need is not None:
+                        comp[i].wait_event(arrived[need])
+                    v.vccl_fma_probe(outs[i], wg, 256, fwd_iters * (1 if kind == "F" else 2),
+                                     int(comp[i].cuda_stream))
+                    e = torch.cuda.Event()
+                    e.record(comp[i])
+                    done[(kind, i, m)] = e
+                    if mode is not None:
+                        if kind == "F" and i < stages - 1:
+                            link_f[i].wait_event(e)
+                            transfer(mode, src_f[i][m % 2], dst_f[i][m % 2], link_f[i])
+                            a = torch.cuda.Event()
+                            a.record(link_f[i])
+                            arrived[("F", i + 1, m)] = a
+                        if kind == "B" and i > 0:
+                            link_b[i].wait_event(e)
+                            transfer(mode, src_b[i][m % 2], dst_b[i][m % 2], link_b[i])
+                            a = torch.cuda.Event()
+                            a.record(link_b[i])
+                            arrived[("B", i - 1, m)] = a
+                    pos[i] += 1
+                    progress = True
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    rows = {}
+    for name, mode, opts in (("no_transfer", None, {}), ("cu_path", v.MODE_CU, {}),
+                             ("cu_path_capped_32wg", v.MODE_CU, {"cu_max_wg": 32, "cu_unroll": 8}),
+                             ("copy_engine", v.MODE_CE, {})):
+        saved = _set(opts)
+        try:
+            iteration(mode)
+            rows[name] = statistics.median(iteration(mode) for _ in range(reps)) * 1e3
+        finally:
+            _set(saved)
+    t_n, t_v = rows["cu_path"], rows["copy_engine"]
+    return {"workload": f"1F1B, {stages} stages x {micro} microbatches, {act_bytes >> 20} MiB per transfer, "
+                        f"FMA probe {wg} workgroups per stage, forward {fwd_iters} rounds",
+            "iteration_ms": rows, "gain_I_pct": 100.0 * (t_n - t_v) / t_v,
+            "overhead_vs_no_transfer_pct": {k: 100.0 * (val - rows["no_transfer"]) / rows["no_transfer"]
+                                            for k, val in rows.items() if k != "no_transfer"}}
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
-    ap.add_argument("what", choices=["ring", "sweep", "all"])
+    ap.add_argument("what", choices=["ring", "sweep", "pipeline", "all"])
     ap.add_argument("--json", default=None)
     ap.add_argument("--no-corun", action="store_true")
     args = ap.parse_args(argv)
@@ -222,6 +330,13 @@ def main(argv=None):
         if args.what in ("ring", "all"):
             out["ring"] = ring_corun(torch)
             print(json.dumps(out["ring"]), flush=True)
+        if args.what in ("pipeline", "all"):
+            # 4 stages need 12 streams, which share this box's 4 hardware queues; the
+            # 2-stage runs (4 streams) show the schedule without that false sharing
+            out["pipeline"] = [pipeline_1f1b(torch, stages=4, fwd_iters=4000),
+                               pipeline_1f1b(torch, stages=2, fwd_iters=4000),
+                               pipeline_1f1b(torch, stages=2, fwd_iters=40000)]
+            print(json.dumps(out["pipeline"]), flush=True)
         if args.what in ("sweep", "all"):
             out["sweep"] = sweep_p64(torch, with_corun=not args.no_corun)
             print(json.dumps(out["sweep"]), flush=True)
