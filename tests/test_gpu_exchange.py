@@ -142,6 +142,34 @@ def test_config5_p64_sweep_points(vccl, mode, c):
         assert_same(to_host(recv[r]), recv_np[r], f"recv[{r}]")
 
 
+def test_config5_p64_1mib_sampled_destinations(vccl):
+    """P = 64 at 1 MiB per peer (4 GiB sent, the launch shape the sweep times): the
+    receive buffers of sampled destination ranks are checked in full against the
+    oracle, which is run on the reduced exchange "everything bound for rank r"."""
+    torch = require_gpu()
+    P, c = 64, 1 << 20
+    seed = wl.config_seed(5)
+    send_np = [wl.payload_bytes(seed, s, P * c) for s in range(P)]
+    send = [torch.from_numpy(a).cuda() for a in send_np]
+    for mode in ("cu", "ce"):
+        recv = [torch.full((P * c,), SENTINEL, dtype=torch.uint8, device="cuda") for _ in range(P)]
+        vccl.vccl_alltoall(send, recv, c, P, _mode(vccl, mode), stream_handle(torch))
+        torch.cuda.synchronize()
+        for r in (0, 17, 63):
+            counts = np.zeros((P, P), dtype=np.uint64)
+            counts[:, r] = c
+            sd = np.zeros((P, P), dtype=np.uint64)
+            sd[:, r] = r * c
+            rd = np.zeros((P, P), dtype=np.uint64)
+            rd[r, :] = np.arange(P, dtype=np.uint64) * np.uint64(c)
+            want = [np.zeros(16, np.uint8) for _ in range(P)]
+            want[r] = np.full(P * c, SENTINEL, dtype=np.uint8)
+            oracle.alltoallv(send_np, counts, sd, want, counts.T.copy(), rd, threads=1)
+            assert_same(to_host(recv[r]), want[r], f"{mode} recv[{r}]")
+        del recv
+        torch.cuda.empty_cache()
+
+
 def _with_options(v, opts, fn):
     saved = {k: v.vccl_get_option(k) for k in opts}
     for k, val in opts.items():
