@@ -370,3 +370,47 @@ def _stream_ordering_body(torch, vccl, m):
             got = to_host(snap[r]).reshape(P, c)
             for s in range(P):
                 assert (got[s] == it * 10 + s).all(), (m, it, r, s)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_concurrent_callers_on_their_own_streams(vccl, mode):
+    """Four host threads, each with its own stream and buffers, call the library at
+    the same time (the C boundary promises thread safety); every result is right."""
+    import threading
+    torch = require_gpu()
+    P, c, nthreads, rounds = 12, 96 << 10, 4, 6       # 144 descriptors: the shared staging ring is used
+    m = _mode(vccl, mode)
+    data = []
+    for t in range(nthreads):
+        lay = wl.random_layout(3000 + t, P, c, align=16, zero_fraction=0.1)
+        send_np = [wl.payload_bytes(40 + t, s, int(lay["send_sizes"][s])) for s in range(P)]
+        want = [np.full(int(lay["recv_sizes"][r]), SENTINEL, dtype=np.uint8) for r in range(P)]
+        oracle.alltoallv(send_np, lay["sendcounts"], lay["sdispls"], want, lay["recvcounts"], lay["rdispls"])
+        send = [to_dev(torch, a) for a in send_np]
+        recv = [to_dev(torch, np.full(int(lay["recv_sizes"][r]), SENTINEL, dtype=np.uint8)) for r in range(P)]
+        data.append((lay, send, recv, want, torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(t):
+        try:
+            lay, send, recv, want, stream = data[t]
+            for _ in range(rounds):
+                vccl.vccl_alltoallv(send, lay["sendcounts"], lay["sdispls"], recv, lay["recvcounts"],
+                                    lay["rdispls"], P, m, stream_handle(torch, stream))
+            stream.synchronize()
+        except Exception as e:          # noqa: BLE001 - reported below
+            errors.append((t, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(nthreads)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=60)
+    assert not errors, errors
+    assert not any(th.is_alive() for th in threads)
+    torch.cuda.synchronize()
+    for t in range(nthreads):
+        lay, send, recv, want, _ = data[t]
+        for r in range(P):
+            assert_same(to_host(recv[r]), want[r], f"thread {t} recv[{r}]")
