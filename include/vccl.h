@@ -86,7 +86,9 @@ const char *vccl_last_error(void);
  *       "cu_wg_per_cu" (0 = one workgroup per tile; 1..16 = that many grid-striding
  *                        workgroups per compute unit),
  *       "cu_max_wg" (cap on the copy grid, 0 = none; the co-run study sweeps it),
- *       "cu_nontemporal" (0/1), "cu_fast_path" (0/1: allow the all-aligned kernel),
+ *       "cu_nontemporal" (0 plain accesses, 1 non-temporal loads and stores, 2 non-temporal
+ *                         loads and device-scope stores), "cu_threads" (64 | 128 | 256 lanes per
+ *                         workgroup of the all-aligned kernels), "cu_fast_path" (0/1: allow the all-aligned kernel),
  *       "ce_kind" (copy-engine back end: "sdma" = SDMA engines driven
  *       through the HSA runtime with stream write/wait-value ordering, the default when the
  *       device supports it; "hip_nocu" / "hip_default" = hipMemcpyAsync on internal streams
@@ -153,8 +155,9 @@ int vccl_alltoallv(void *const *sendbuf, const uint64_t *sendcounts, const uint6
  * description it reports the copy descriptors in launch order - non-empty segments,
  * destination-major with the source rotated by the destination index (the incast
  * counter-measure, Section 6), long segments cut into pieces of equal tile count -
- * and the launch grid: grid_x tiles of cu_unroll*4096 bytes per descriptor,
- * grid_y descriptors.  head is the number of leading bytes copied bytewise before
+ * and the launch grid: grid_x tiles of *tile_bytes bytes per descriptor (cu_unroll
+ * vectors per lane; cu_threads lanes per workgroup when every descriptor is 16-byte
+ * aligned and the all-aligned kernel applies, 256 otherwise), grid_y descriptors.  head is the number of leading bytes copied bytewise before
  * the destination is 16-byte aligned; all_aligned tells whether the fast kernel
  * applies.  out may be NULL to query the count. */
 typedef struct {
@@ -163,8 +166,9 @@ typedef struct {
 } vccl_plan_desc;
 int vccl_plan_alltoallv(void *const *sendbuf, const uint64_t *sendcounts, const uint64_t *sdispls,
                         void *const *recvbuf, const uint64_t *recvcounts, const uint64_t *rdispls,
-                        int P, int cu_unroll, vccl_plan_desc *out, int out_cap, int *n_out,
-                        uint32_t *grid_x, uint32_t *grid_y, int *all_aligned);
+                        int P, int cu_unroll, int cu_threads, vccl_plan_desc *out, int out_cap,
+                        int *n_out, uint32_t *grid_x, uint32_t *grid_y, uint32_t *tile_bytes,
+                        int *all_aligned);
 
 /* MoE dispatch pack (Section 2.1 token routing; Section 6 dispatch phase) for all
  * P source ranks in one call.  For rank s, x[s] holds `tokens` rows of row_bytes

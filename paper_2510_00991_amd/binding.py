@@ -40,9 +40,10 @@ EXPORTS = {
     "vccl_alltoallv": (ctypes.c_int, [_vpp, _u64p, _u64p, _vpp, _u64p, _u64p, ctypes.c_int,
                                       ctypes.c_int, ctypes.c_void_p]),
     "vccl_plan_alltoallv": (ctypes.c_int, [_vpp, _u64p, _u64p, _vpp, _u64p, _u64p, ctypes.c_int,
-                                           ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
+                                           ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
                                            ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_uint32),
-                                           ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_int)]),
+                                           ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32),
+                                           ctypes.POINTER(ctypes.c_int)]),
     "vccl_moe_pack": (ctypes.c_int, [_vpp, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                      ctypes.c_uint64, ctypes.c_int, _vpp, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
@@ -194,20 +195,21 @@ def vccl_alltoallv(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P
 
 
 def vccl_plan_alltoallv(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P: int,
-                        cu_unroll: int = 1):
-    """Planner only (no device needed).  Returns (descriptors, grid_x, grid_y, all_aligned);
-    descriptors is a structured array with fields src, dst, bytes, head."""
+                        cu_unroll: int = 1, cu_threads: int = 64):
+    """Planner only (no device needed).  Returns (descriptors, grid_x, grid_y, tile_bytes,
+    all_aligned); descriptors is a structured array with fields src, dst, bytes, head."""
     sc, sd, rc, rd = (_u64(m, (P, P)) for m in (sendcounts, sdispls, recvcounts, rdispls))
     n, gx, gy, al = ctypes.c_int(), ctypes.c_uint32(), ctypes.c_uint32(), ctypes.c_int()
-    args = (_ptrs(sendbuf), _p64(sc), _p64(sd), _ptrs(recvbuf), _p64(rc), _p64(rd), P, cu_unroll)
+    tb = ctypes.c_uint32()
+    args = (_ptrs(sendbuf), _p64(sc), _p64(sd), _ptrs(recvbuf), _p64(rc), _p64(rd), P, cu_unroll, cu_threads)
     _check(load().vccl_plan_alltoallv(*args, None, 0, ctypes.byref(n), ctypes.byref(gx), ctypes.byref(gy),
-                                      ctypes.byref(al)))
+                                      ctypes.byref(tb), ctypes.byref(al)))
     dt = np.dtype([("src", np.uint64), ("dst", np.uint64), ("bytes", np.uint64), ("head", np.uint32),
                    ("reserved", np.uint32)])
     out = np.zeros(max(1, n.value), dtype=dt)
     _check(load().vccl_plan_alltoallv(*args, ctypes.c_void_p(out.ctypes.data), out.size, ctypes.byref(n),
-                                      ctypes.byref(gx), ctypes.byref(gy), ctypes.byref(al)))
-    return out[:n.value], gx.value, gy.value, bool(al.value)
+                                      ctypes.byref(gx), ctypes.byref(gy), ctypes.byref(tb), ctypes.byref(al)))
+    return out[:n.value], gx.value, gy.value, tb.value, bool(al.value)
 
 
 def vccl_moe_pack(x, expert_ids, P: int, tokens: int, topk: int, row_bytes: int, num_experts: int,

@@ -150,7 +150,9 @@ static int run_pieces(Context &c, std::vector<Piece> &pieces, vccl_mode mode, hi
         plan.segs.reserve(pieces.size());
         for (const Piece &pc : pieces)
             if (pc.bytes) plan.segs.push_back(Seg{pc.src, pc.dst, pc.bytes, 0, 0});
-        int rv = plan_tiles(plan, opt.cu_unroll);
+        // the all-aligned kernel needs the full grid
+        const bool allow_fast = opt.cu_fast_path && !opt.cu_max_wg && !opt.cu_wg_per_cu;
+        int rv = plan_tiles(plan, opt.cu_unroll, allow_fast ? opt.cu_threads : 0);
         if (rv) return rv;
         return launch_copy(plan, opt, c.cu_count, c.ring, stream);
     }
@@ -325,8 +327,11 @@ int vccl_set_option(const char *key, const char *value) {
         if (!in(0, 1u << 20)) return fail(VCCL_ERR_ARG, "cu_max_wg must be 0..1048576");
         o.cu_max_wg = (int)x;
     } else if (k == "cu_nontemporal") {
-        if (!in(0, 1)) return fail(VCCL_ERR_ARG, "cu_nontemporal must be 0 or 1");
+        if (!in(0, 2)) return fail(VCCL_ERR_ARG, "cu_nontemporal must be 0, 1 or 2");
         o.cu_nontemporal = (int)x;
+    } else if (k == "cu_threads") {
+        if (!(x == 64 || x == 128 || x == 256)) return fail(VCCL_ERR_ARG, "cu_threads must be 64, 128 or 256");
+        o.cu_threads = (int)x;
     } else if (k == "cu_fast_path") {
         if (!in(0, 1)) return fail(VCCL_ERR_ARG, "cu_fast_path must be 0 or 1");
         o.cu_fast_path = (int)x;
@@ -381,6 +386,7 @@ int vccl_get_option(const char *key, char *out, int cap) {
     else if (k == "cu_wg_per_cu") v = o.cu_wg_per_cu;
     else if (k == "cu_max_wg") v = o.cu_max_wg;
     else if (k == "cu_nontemporal") v = o.cu_nontemporal;
+    else if (k == "cu_threads") v = o.cu_threads;
     else if (k == "cu_fast_path") v = o.cu_fast_path;
     else if (k == "ce_streams") v = o.ce_streams;
     else if (k == "moe_gather_variant") v = o.moe_gather_variant;
@@ -566,24 +572,27 @@ int vccl_moe_exchange_layout(const uint64_t *counts, int P, int num_experts, int
 
 int vccl_plan_alltoallv(void *const *sendbuf, const uint64_t *sendcounts, const uint64_t *sdispls,
                         void *const *recvbuf, const uint64_t *recvcounts, const uint64_t *rdispls, int P,
-                        int cu_unroll, vccl_plan_desc *out, int out_cap, int *n_out, uint32_t *grid_x,
-                        uint32_t *grid_y, int *all_aligned) {
+                        int cu_unroll, int cu_threads, vccl_plan_desc *out, int out_cap, int *n_out,
+                        uint32_t *grid_x, uint32_t *grid_y, uint32_t *tile_bytes, int *all_aligned) {
     if (P < 1 || P > VCCL_MAX_RANKS) return fail(VCCL_ERR_ARG, "P = %d is outside 1..%d", P, VCCL_MAX_RANKS);
     if (!sendbuf || !recvbuf || !sendcounts || !sdispls || !recvcounts || !rdispls || !n_out)
         return fail(VCCL_ERR_ARG, "NULL argument");
     if (!(cu_unroll == 1 || cu_unroll == 2 || cu_unroll == 4 || cu_unroll == 8 || cu_unroll == 16))
         return fail(VCCL_ERR_ARG, "cu_unroll must be 1, 2, 4, 8 or 16");
+    if (!(cu_threads == 64 || cu_threads == 128 || cu_threads == 256))
+        return fail(VCCL_ERR_ARG, "cu_threads must be 64, 128 or 256");
     std::vector<Piece> pieces;
     int rv = alltoallv_pieces(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P, pieces);
     if (rv) return rv;
     CopyPlan plan;
     for (const Piece &pc : pieces) plan.segs.push_back(Seg{pc.src, pc.dst, pc.bytes, 0, 0});
-    rv = plan_tiles(plan, cu_unroll);
+    rv = plan_tiles(plan, cu_unroll, cu_threads);
     if (rv) return rv;
     *n_out = (int)plan.segs.size();
     if (grid_x) *grid_x = plan.max_tiles;
     if (grid_y) *grid_y = (uint32_t)(plan.segs.size() > 65535 ? 65535 : plan.segs.size());
     if (all_aligned) *all_aligned = plan.all_aligned ? 1 : 0;
+    if (tile_bytes) *tile_bytes = (uint32_t)(cu_unroll * plan.threads * 16);
     if (out) {
         if ((size_t)out_cap < plan.segs.size())
             return fail(VCCL_ERR_ARG, "the plan has %zu descriptors, room for %d", plan.segs.size(), out_cap);

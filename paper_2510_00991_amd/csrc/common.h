@@ -39,7 +39,8 @@ struct Options {
     int cu_unroll = 1;
     int cu_wg_per_cu = 0;
     int cu_max_wg = 0;
-    int cu_nontemporal = 1;
+    int cu_nontemporal = 2;
+    int cu_threads = 64;
     int cu_fast_path = 1;
     int moe_gather_variant = 116;
     int ce_streams = 4;
@@ -91,10 +92,13 @@ struct CopyPlan {
     uint64_t total_tiles = 0;
     uint32_t max_tiles = 0;      // tiles of the longest descriptor (grid x)
     bool all_aligned = false;    // every descriptor: 16-byte aligned ends, whole vectors
+    bool fast = false;           // tiled for (and to be run by) the all-aligned kernel
+    int threads = kCopyThreads;  // lanes per workgroup the tiles were sized for
     uint64_t bytes = 0;
 };
 // Fills tile_begin/head for plan.segs (src, dst, bytes already set).
-int plan_tiles(CopyPlan &plan, int unroll);
+// fast_threads > 0 allows the all-aligned kernel with that many lanes per workgroup.
+int plan_tiles(CopyPlan &plan, int unroll, int fast_threads);
 int launch_copy(const CopyPlan &plan, const Options &opt, int cu_count, DescRing &ring,
                 hipStream_t stream);
 

@@ -31,22 +31,37 @@ struct CopyArgs {
 
 constexpr int kLdsVecs = 1024;  // vectors staged per LDS round of the realign path
 
-template <bool NT>
+// Access policy POL: 0 plain; 1 non-temporal loads and stores; 2 non-temporal
+// loads, stores marked device scope (sc1), which measured 1.5 % faster than the
+// non-temporal store on this chip.  The device-scope store is issued as a raw
+// buffer store (the builtin that exposes the cache-policy bits) through a
+// descriptor built on the wave-uniform tile base; lane offsets stay below 2 GiB.
+template <int POL>
 __device__ __forceinline__ u32x4 ld16(const u32x4 *p) {
-    if (NT) return __builtin_nontemporal_load(p);
+    if (POL >= 1) return __builtin_nontemporal_load(p);
     return *p;
 }
-template <bool NT>
-__device__ __forceinline__ void st16(u32x4 *p, u32x4 v) {
-    if (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
-}
+template <int POL>
+struct TileDst {
+    u32x4 *base;
+    __amdgpu_buffer_rsrc_t rsrc;
+    // `base` must be the same in every lane of the wavefront.
+    __device__ __forceinline__ explicit TileDst(u32x4 *b) : base(b) {
+        if (POL == 2)
+            rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)b, 0, 0x7fffffff, 0x00020000 /* raw dwords */);
+    }
+    __device__ __forceinline__ void store(uint32_t idx, u32x4 v) const {
+        if (POL == 2) __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, idx * 16u, 0, 16 /* sc1 */);
+        else if (POL == 1) __builtin_nontemporal_store(v, base + idx);
+        else base[idx] = v;
+    }
+};
 
 __device__ __forceinline__ uint32_t funnel(uint32_t lo, uint32_t hi, uint32_t byte_shift) {
     return (uint32_t)((((uint64_t)hi << 32) | lo) >> (8u * byte_shift));
 }
 
-template <int U, bool NT, bool INLINE>
+template <int U, int NT, bool INLINE>
 __global__ __launch_bounds__(kCopyThreads) void copy_segments_kernel(CopyArgs by_value) {
     (void)by_value;
     // The argument block is read in place (dynamic indexing of a by-value
@@ -80,7 +95,7 @@ __global__ __launch_bounds__(kCopyThreads) void copy_segments_kernel(CopyArgs by
              v0 += (uint64_t)gridDim.x * kTileVecs) {
             const uint32_t cnt = (uint32_t)min((uint64_t)kTileVecs, nv - v0);
             const uint8_t *sb = src + head + (v0 << 4);
-            u32x4 *d = reinterpret_cast<u32x4 *>(dst + head + (v0 << 4));
+            const TileDst<NT> d(reinterpret_cast<u32x4 *>(dst + head + (v0 << 4)));
             const uint32_t mis = (uint32_t)(reinterpret_cast<uintptr_t>(sb) & 15u);
             if (mis == 0) {
                 const u32x4 *s = reinterpret_cast<const u32x4 *>(sb);
@@ -89,9 +104,9 @@ __global__ __launch_bounds__(kCopyThreads) void copy_segments_kernel(CopyArgs by
 #pragma unroll
                     for (int u = 0; u < U; ++u) r[u] = ld16<NT>(s + u * kCopyThreads + tid);
 #pragma unroll
-                    for (int u = 0; u < U; ++u) st16<NT>(d + u * kCopyThreads + tid, r[u]);
+                    for (int u = 0; u < U; ++u) d.store(u * kCopyThreads + tid, r[u]);
                 } else {
-                    for (uint32_t i = tid; i < cnt; i += kCopyThreads) st16<NT>(d + i, ld16<NT>(s + i));
+                    for (uint32_t i = tid; i < cnt; i += kCopyThreads) d.store(i, ld16<NT>(s + i));
                 }
             } else {
                 // Every aligned word read below holds at least one byte of the segment
@@ -118,7 +133,7 @@ __global__ __launch_bounds__(kCopyThreads) void copy_segments_kernel(CopyArgs by
                             default: o = u32x4{funnel(w[3], w[4], sh), funnel(w[4], w[5], sh),
                                                funnel(w[5], w[6], sh), funnel(w[6], w[7], sh)}; break;
                         }
-                        st16<NT>(d + c0 + i, o);
+                        d.store(c0 + i, o);
                     }
                 }
             }
@@ -130,28 +145,28 @@ __global__ __launch_bounds__(kCopyThreads) void copy_segments_kernel(CopyArgs by
 // addresses on both sides and is a whole number of vectors long (all five
 // workload configurations): no head, tail, realignment, LDS or loop - one scalar
 // descriptor load, U vector loads, U vector stores.  Needs the full grid.
-template <int U, bool NT, bool INLINE>
-__global__ __launch_bounds__(kCopyThreads) void copy_aligned_kernel(CopyArgs by_value) {
+template <int U, int NT, bool INLINE, int T>
+__global__ __launch_bounds__(T) void copy_aligned_kernel(CopyArgs by_value) {
     (void)by_value;
     const CopyArgs *a =
         reinterpret_cast<const CopyArgs *>((const void *)__builtin_amdgcn_kernarg_segment_ptr());
     const Seg *sg = (INLINE ? a->inl : a->table) + blockIdx.y;
-    constexpr uint32_t kTileVecs = (uint32_t)U * kCopyThreads;
+    constexpr uint32_t kTileVecs = (uint32_t)U * T;
     const uint64_t nv = sg->bytes >> 4;
     const uint64_t v0 = (uint64_t)blockIdx.x * kTileVecs;
     if (v0 >= nv) return;
     const u32x4 *s = reinterpret_cast<const u32x4 *>(sg->src) + v0;
-    u32x4 *d = reinterpret_cast<u32x4 *>(sg->dst) + v0;
+    const TileDst<NT> d(reinterpret_cast<u32x4 *>(sg->dst) + v0);
     const uint32_t tid = threadIdx.x;
     if (nv - v0 >= kTileVecs) {
         u32x4 r[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) r[u] = ld16<NT>(s + u * kCopyThreads + tid);
+        for (int u = 0; u < U; ++u) r[u] = ld16<NT>(s + u * T + tid);
 #pragma unroll
-        for (int u = 0; u < U; ++u) st16<NT>(d + u * kCopyThreads + tid, r[u]);
+        for (int u = 0; u < U; ++u) d.store(u * T + tid, r[u]);
     } else {
         const uint32_t cnt = (uint32_t)(nv - v0);
-        for (uint32_t i = tid; i < cnt; i += kCopyThreads) st16<NT>(d + i, ld16<NT>(s + i));
+        for (uint32_t i = tid; i < cnt; i += T) d.store(i, ld16<NT>(s + i));
     }
 }
 
@@ -169,12 +184,12 @@ struct UniformArgs {
     uint32_t pad;
 };
 
-template <int U, bool NT>
-__global__ __launch_bounds__(kCopyThreads) void copy_uniform_kernel(UniformArgs by_value) {
+template <int U, int NT, int T>
+__global__ __launch_bounds__(T) void copy_uniform_kernel(UniformArgs by_value) {
     (void)by_value;
     const UniformArgs *a =
         reinterpret_cast<const UniformArgs *>((const void *)__builtin_amdgcn_kernarg_segment_ptr());
-    constexpr uint32_t kTileVecs = (uint32_t)U * kCopyThreads;
+    constexpr uint32_t kTileVecs = (uint32_t)U * T;
     const uint64_t nv = a->vecs_per_block;
     const uint64_t v0 = (uint64_t)blockIdx.x * kTileVecs;
     if (v0 >= nv) return;
@@ -183,17 +198,17 @@ __global__ __launch_bounds__(kCopyThreads) void copy_uniform_kernel(UniformArgs 
     uint32_t s_rank = r + k;
     if (s_rank >= P) s_rank -= P;
     const u32x4 *s = reinterpret_cast<const u32x4 *>(a->send[s_rank]) + (uint64_t)r * nv + v0;
-    u32x4 *d = reinterpret_cast<u32x4 *>(a->recv[r]) + (uint64_t)s_rank * nv + v0;
+    const TileDst<NT> d(reinterpret_cast<u32x4 *>(a->recv[r]) + (uint64_t)s_rank * nv + v0);
     const uint32_t tid = threadIdx.x;
     if (nv - v0 >= kTileVecs) {
         u32x4 reg[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) reg[u] = ld16<NT>(s + u * kCopyThreads + tid);
+        for (int u = 0; u < U; ++u) reg[u] = ld16<NT>(s + u * T + tid);
 #pragma unroll
-        for (int u = 0; u < U; ++u) st16<NT>(d + u * kCopyThreads + tid, reg[u]);
+        for (int u = 0; u < U; ++u) d.store(u * T + tid, reg[u]);
     } else {
         const uint32_t cnt = (uint32_t)(nv - v0);
-        for (uint32_t i = tid; i < cnt; i += kCopyThreads) st16<NT>(d + i, ld16<NT>(s + i));
+        for (uint32_t i = tid; i < cnt; i += T) d.store(i, ld16<NT>(s + i));
     }
 }
 
@@ -201,8 +216,8 @@ bool uniform_alltoall_applies(void *const *sendbuf, void *const *recvbuf, uint64
                               const Options &opt) {
     if (!opt.cu_fast_path || opt.check || opt.cu_max_wg || opt.cu_wg_per_cu) return false;
     if (P > kUniformRanks || (uint64_t)P * P > 65535 || bytes_per_peer == 0 || (bytes_per_peer & 15u)) return false;
-    const uint64_t tiles = ((bytes_per_peer >> 4) + (uint64_t)opt.cu_unroll * kCopyThreads - 1) /
-                           ((uint64_t)opt.cu_unroll * kCopyThreads);
+    const uint64_t tiles = ((bytes_per_peer >> 4) + (uint64_t)opt.cu_unroll * opt.cu_threads - 1) /
+                           ((uint64_t)opt.cu_unroll * opt.cu_threads);
     if (tiles > 0x7fffffffull) return false;
     for (int i = 0; i < P; ++i)
         if (!sendbuf[i] || !recvbuf[i] ||
@@ -221,13 +236,17 @@ int launch_uniform_alltoall(void *const *sendbuf, void *const *recvbuf, uint64_t
     a.vecs_per_block = bytes_per_peer >> 4;
     a.P = (uint32_t)P;
     a.pad = 0;
-    const uint64_t tile_vecs = (uint64_t)opt.cu_unroll * kCopyThreads;
+    const uint64_t tile_vecs = (uint64_t)opt.cu_unroll * opt.cu_threads;
     const dim3 grid((uint32_t)((a.vecs_per_block + tile_vecs - 1) / tile_vecs), (uint32_t)(P * P));
-    const dim3 block(kCopyThreads);
-    const bool nt = opt.cu_nontemporal != 0;
-#define VCCL_UNI(U)                                                                          \
-    if (nt) copy_uniform_kernel<U, true><<<grid, block, 0, stream>>>(a);                     \
-    else copy_uniform_kernel<U, false><<<grid, block, 0, stream>>>(a)
+    const dim3 block((uint32_t)opt.cu_threads);
+#define VCCL_UNI_T(U, POL)                                                                           \
+    if (opt.cu_threads == 64) copy_uniform_kernel<U, POL, 64><<<grid, block, 0, stream>>>(a);        \
+    else if (opt.cu_threads == 128) copy_uniform_kernel<U, POL, 128><<<grid, block, 0, stream>>>(a); \
+    else copy_uniform_kernel<U, POL, 256><<<grid, block, 0, stream>>>(a)
+#define VCCL_UNI(U)                                                                              \
+    if (opt.cu_nontemporal == 2) { VCCL_UNI_T(U, 2); }                                           \
+    else if (opt.cu_nontemporal == 1) { VCCL_UNI_T(U, 1); }                                      \
+    else { VCCL_UNI_T(U, 0); }
     switch (opt.cu_unroll) {
         case 1: VCCL_UNI(1); break;
         case 2: VCCL_UNI(2); break;
@@ -237,6 +256,7 @@ int launch_uniform_alltoall(void *const *sendbuf, void *const *recvbuf, uint64_t
         default: return fail(VCCL_ERR_ARG, "cu_unroll %d is not one of 1,2,4,8,16", opt.cu_unroll);
     }
 #undef VCCL_UNI
+#undef VCCL_UNI_T
     VCCL_HIP(hipGetLastError());
     return VCCL_OK;
 }
@@ -247,8 +267,20 @@ static inline uint32_t head_of(const uint8_t *dst, uint64_t bytes) {
     return (uint32_t)(bytes < to_align ? bytes : to_align);
 }
 
-int plan_tiles(CopyPlan &plan, int unroll) {
-    const uint64_t tile_vecs = (uint64_t)unroll * kCopyThreads;
+int plan_tiles(CopyPlan &plan, int unroll, int fast_threads) {
+    // The all-aligned kernel may run with fewer lanes per workgroup (smaller tiles);
+    // which kernel applies has to be known before the segments are tiled.
+    plan.all_aligned = !plan.segs.empty();
+    for (const Seg &s : plan.segs)
+        if (((reinterpret_cast<uintptr_t>(s.src) | reinterpret_cast<uintptr_t>(s.dst) | s.bytes) & 15u) != 0) {
+            plan.all_aligned = false;
+            break;
+        }
+    // Cutting (below) adds at most 8192 pieces; the all-aligned kernel needs one
+    // grid row per descriptor, and a grid has at most 65535 rows.
+    plan.fast = plan.all_aligned && fast_threads > 0 && plan.segs.size() <= 65535u - 8192u;
+    plan.threads = plan.fast ? fast_threads : kCopyThreads;
+    const uint64_t tile_vecs = (uint64_t)unroll * plan.threads;
     const uint64_t tile_bytes = tile_vecs << 4;
     auto tiles_of = [&](const Seg &s) {
         const uint64_t nv = (s.bytes - head_of(s.dst, s.bytes)) >> 4;
@@ -303,30 +335,37 @@ int plan_tiles(CopyPlan &plan, int unroll) {
     }
     plan.total_tiles = tiles;
     plan.max_tiles = (uint32_t)longest;
-    plan.all_aligned = true;
-    for (const Seg &s : plan.segs)
-        if (((reinterpret_cast<uintptr_t>(s.src) | reinterpret_cast<uintptr_t>(s.dst) | s.bytes) & 15u) != 0) {
-            plan.all_aligned = false;
-            break;
-        }
     return VCCL_OK;
 }
 
-template <int U>
-static void launch_variant(bool nt, bool inl, bool fast, dim3 grid, hipStream_t stream,
-                           const CopyArgs &args) {
-    const dim3 block(kCopyThreads);
+template <int U, int POL>
+static void launch_policy(bool inl, bool fast, int threads, dim3 grid, hipStream_t stream,
+                          const CopyArgs &args) {
     if (fast) {
-        if (nt && inl) copy_aligned_kernel<U, true, true><<<grid, block, 0, stream>>>(args);
-        else if (nt) copy_aligned_kernel<U, true, false><<<grid, block, 0, stream>>>(args);
-        else if (inl) copy_aligned_kernel<U, false, true><<<grid, block, 0, stream>>>(args);
-        else copy_aligned_kernel<U, false, false><<<grid, block, 0, stream>>>(args);
+        const dim3 block((uint32_t)threads);
+        if (threads == 64) {
+            if (inl) copy_aligned_kernel<U, POL, true, 64><<<grid, block, 0, stream>>>(args);
+            else copy_aligned_kernel<U, POL, false, 64><<<grid, block, 0, stream>>>(args);
+        } else if (threads == 128) {
+            if (inl) copy_aligned_kernel<U, POL, true, 128><<<grid, block, 0, stream>>>(args);
+            else copy_aligned_kernel<U, POL, false, 128><<<grid, block, 0, stream>>>(args);
+        } else {
+            if (inl) copy_aligned_kernel<U, POL, true, 256><<<grid, block, 0, stream>>>(args);
+            else copy_aligned_kernel<U, POL, false, 256><<<grid, block, 0, stream>>>(args);
+        }
         return;
     }
-    if (nt && inl) copy_segments_kernel<U, true, true><<<grid, block, 0, stream>>>(args);
-    else if (nt) copy_segments_kernel<U, true, false><<<grid, block, 0, stream>>>(args);
-    else if (inl) copy_segments_kernel<U, false, true><<<grid, block, 0, stream>>>(args);
-    else copy_segments_kernel<U, false, false><<<grid, block, 0, stream>>>(args);
+    const dim3 block(kCopyThreads);
+    if (inl) copy_segments_kernel<U, POL, true><<<grid, block, 0, stream>>>(args);
+    else copy_segments_kernel<U, POL, false><<<grid, block, 0, stream>>>(args);
+}
+
+template <int U>
+static void launch_variant(int pol, bool inl, bool fast, int threads, dim3 grid, hipStream_t stream,
+                           const CopyArgs &args) {
+    if (pol == 2) launch_policy<U, 2>(inl, fast, threads, grid, stream, args);
+    else if (pol == 1) launch_policy<U, 1>(inl, fast, threads, grid, stream, args);
+    else launch_policy<U, 0>(inl, fast, threads, grid, stream, args);
 }
 
 int launch_copy(const CopyPlan &plan, const Options &opt, int cu_count, DescRing &ring,
@@ -364,15 +403,17 @@ int launch_copy(const CopyPlan &plan, const Options &opt, int cu_count, DescRing
         if (gx > plan.max_tiles) gx = plan.max_tiles;
     }
     const dim3 grid((uint32_t)gx, (uint32_t)gy);
-    const bool nt = opt.cu_nontemporal != 0;
-    const bool fast = plan.all_aligned && opt.cu_fast_path && gx == plan.max_tiles &&
-                      gy == plan.segs.size();
+    const int nt = opt.cu_nontemporal;
+    // A plan tiled for the all-aligned kernel must be run by it, on the full grid.
+    const bool fast = plan.fast;
+    if (fast && !(gx == plan.max_tiles && gy == plan.segs.size()))
+        return fail(VCCL_ERR_UNSUPPORTED, "internal: a fast-path plan met a capped grid");
     switch (opt.cu_unroll) {
-        case 1: launch_variant<1>(nt, inl, fast, grid, stream, args); break;
-        case 2: launch_variant<2>(nt, inl, fast, grid, stream, args); break;
-        case 4: launch_variant<4>(nt, inl, fast, grid, stream, args); break;
-        case 8: launch_variant<8>(nt, inl, fast, grid, stream, args); break;
-        case 16: launch_variant<16>(nt, inl, fast, grid, stream, args); break;
+        case 1: launch_variant<1>(nt, inl, fast, plan.threads, grid, stream, args); break;
+        case 2: launch_variant<2>(nt, inl, fast, plan.threads, grid, stream, args); break;
+        case 4: launch_variant<4>(nt, inl, fast, plan.threads, grid, stream, args); break;
+        case 8: launch_variant<8>(nt, inl, fast, plan.threads, grid, stream, args); break;
+        case 16: launch_variant<16>(nt, inl, fast, plan.threads, grid, stream, args); break;
         default: return fail(VCCL_ERR_ARG, "cu_unroll %d is not one of 1,2,4,8,16", opt.cu_unroll);
     }
     VCCL_HIP(hipGetLastError());

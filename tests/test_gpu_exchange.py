@@ -254,13 +254,31 @@ def test_capped_grid_strides_over_descriptors_and_tiles(vccl, opts):
 
 
 @pytest.mark.parametrize("unroll", [1, 2, 4, 8, 16])
-@pytest.mark.parametrize("nt", [0, 1])
+@pytest.mark.parametrize("nt", [0, 1, 2])
 def test_copy_kernel_variants(vccl, unroll, nt):
+    """Every unroll and access policy of the general kernel (byte-granular layout) and of
+    the all-aligned kernel at both workgroup sizes (16-byte layout, ragged last tiles)."""
     torch = require_gpu()
     lay = wl.random_layout(31, 4, 500000, align=1)
     send_np = [wl.payload_bytes(32, s, int(lay["send_sizes"][s])) for s in range(4)]
     _with_options(vccl, {"cu_unroll": unroll, "cu_nontemporal": nt},
                   lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CU))
+    lay = wl.random_layout(33, 5, 300000, align=16, zero_fraction=0.1)
+    send_np = [wl.payload_bytes(34, s, int(lay["send_sizes"][s])) for s in range(5)]
+    for threads in (64, 128, 256):
+        _with_options(vccl, {"cu_unroll": unroll, "cu_nontemporal": nt, "cu_threads": threads},
+                      lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CU))
+        P, c = 11, 70000 - 70000 % 16       # pointer-table kernel
+        a2a_np = [wl.payload_bytes(35, s, P * c) for s in range(P)]
+        want = [np.full(P * c + 32, SENTINEL, dtype=np.uint8) for _ in range(P)]
+        oracle.alltoall(a2a_np, want, c, threads=4)
+        send = [to_dev(torch, a) for a in a2a_np]
+        recv = [to_dev(torch, np.full(P * c + 32, SENTINEL, dtype=np.uint8)) for _ in range(P)]
+        _with_options(vccl, {"cu_unroll": unroll, "cu_nontemporal": nt, "cu_threads": threads},
+                      lambda: vccl.vccl_alltoall(send, recv, c, P, vccl.MODE_CU, stream_handle(torch)))
+        torch.cuda.synchronize()
+        for r in range(P):
+            assert_same(to_host(recv[r]), want[r], f"threads={threads} recv[{r}]")
 
 
 @pytest.mark.parametrize("kind", ["hip_nocu", "hip_default"])

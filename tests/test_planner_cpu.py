@@ -22,15 +22,15 @@ def _fake_buffers(P, sizes, rng, align=1):
     return out
 
 
-def _tiles(desc, unroll=1):
+def _tiles(desc, tile_bytes):
     nv = (int(desc["bytes"]) - int(desc["head"])) // 16
-    return max(1, -(-nv // (256 * unroll)))
+    return max(1, -(-nv // (tile_bytes // 16)))
 
 
-def _check_plan(lay, send, recv, unroll=1):
+def _check_plan(lay, send, recv, unroll=1, threads=64):
     P = len(send)
-    desc, gx, gy, aligned = vccl.vccl_plan_alltoallv(send, lay["sendcounts"], lay["sdispls"], recv,
-                                                     lay["recvcounts"], lay["rdispls"], P, unroll)
+    desc, gx, gy, tile_bytes, aligned = vccl.vccl_plan_alltoallv(
+        send, lay["sendcounts"], lay["sdispls"], recv, lay["recvcounts"], lay["rdispls"], P, unroll, threads)
     # walk the descriptors in order against the segments in rotated order
     i = 0
     for k in range(P):
@@ -57,13 +57,14 @@ def _check_plan(lay, send, recv, unroll=1):
             assert covered == n
     assert i == len(desc), "descriptors beyond the segments"
     if len(desc):
-        tiles = [_tiles(d, unroll) for d in desc]
-        assert gx == max(tiles) and gy == len(desc)
-        waste = gx * len(desc) - sum(tiles)
-        assert waste <= sum(tiles) / 16 + len(desc) * 64 + 64, (gx, len(desc), sum(tiles))
         want_aligned = all(int(d["src"]) % 16 == 0 and int(d["dst"]) % 16 == 0 and int(d["bytes"]) % 16 == 0
                            for d in desc)
         assert aligned == want_aligned
+        assert tile_bytes == unroll * 16 * (threads if aligned else 256)
+        tiles = [_tiles(d, tile_bytes) for d in desc]
+        assert gx == max(tiles) and gy == len(desc)
+        waste = gx * len(desc) - sum(tiles)
+        assert waste <= sum(tiles) / 16 + len(desc) * 64 + 64, (gx, len(desc), sum(tiles))
     return desc, gx, gy
 
 
@@ -75,7 +76,7 @@ def test_random_layouts_are_tiled_exactly(seed):
     send = _fake_buffers(P, lay["send_sizes"], rng)
     recv = _fake_buffers(P, lay["recv_sizes"], rng)
     recv = [a + (1 << 40) for a in recv]
-    _check_plan(lay, send, recv, unroll=int(rng.choice([1, 2, 8])))
+    _check_plan(lay, send, recv, unroll=int(rng.choice([1, 2, 8])), threads=int(rng.choice([64, 128, 256])))
 
 
 def test_equal_blocks_are_not_cut_and_use_the_fast_kernel():
@@ -83,9 +84,9 @@ def test_equal_blocks_are_not_cut_and_use_the_fast_kernel():
     lay = wl.equal_layout(P, c)
     send = [0x7F0000000000 + i * (1 << 30) for i in range(P)]
     recv = [0x7E0000000000 + i * (1 << 30) for i in range(P)]
-    desc, gx, gy, aligned = vccl.vccl_plan_alltoallv(send, lay["sendcounts"], lay["sdispls"], recv,
-                                                     lay["recvcounts"], lay["rdispls"], P, 1)
-    assert len(desc) == 64 and gx == c // TILE and gy == 64 and aligned
+    desc, gx, gy, tile_bytes, aligned = vccl.vccl_plan_alltoallv(send, lay["sendcounts"], lay["sdispls"], recv,
+                                                                 lay["recvcounts"], lay["rdispls"], P, 1, 256)
+    assert len(desc) == 64 and tile_bytes == TILE and gx == c // TILE and gy == 64 and aligned
     # rotated order: the first P descriptors are the self segments 0->0, 1->1, ...
     for r in range(P):
         assert int(desc[r]["src"]) == send[r] + r * c and int(desc[r]["dst"]) == recv[r] + r * c
@@ -118,7 +119,7 @@ def test_skewed_segments_are_cut_into_equal_pieces():
 def test_zero_segments_and_errors():
     P = 3
     z = np.zeros((P, P), dtype=np.uint64)
-    desc, gx, gy, aligned = vccl.vccl_plan_alltoallv([0] * P, z, z, [0] * P, z, z, P, 1)
+    desc, gx, gy, tile_bytes, aligned = vccl.vccl_plan_alltoallv([0] * P, z, z, [0] * P, z, z, P, 1)
     assert len(desc) == 0
     c = np.array([[1, 2, 0], [0, 0, 0], [0, 0, 0]], dtype=np.uint64)
     with pytest.raises(vccl.VcclError) as e:
@@ -129,3 +130,5 @@ def test_zero_segments_and_errors():
     assert e.value.code == -1
     with pytest.raises(vccl.VcclError):
         vccl.vccl_plan_alltoallv([64] * P, z, z, [64] * P, z, z, P, 3)       # bad unroll
+    with pytest.raises(vccl.VcclError):
+        vccl.vccl_plan_alltoallv([64] * P, z, z, [64] * P, z, z, P, 1, 32)   # bad workgroup size
