@@ -92,14 +92,16 @@ def measured_traffic():
     when there is no summary or the kernel source has changed since it was taken."""
     import hashlib
     path = os.path.join(ROOT, "profiles", "copy_aligned_kernel_alltoall_p8_16MiB_pmc.txt")
-    src = os.path.join(ROOT, "paper_2510_00991_amd", "csrc", "copy_kernel.hip")
+    csrc = os.path.join(ROOT, "paper_2510_00991_amd", "csrc")
     try:
         fields = {}
         for line in open(path):
             if ":" in line:
                 k, val = line.split(":", 1)
                 fields[k.strip()] = val.strip()
-        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
+        # the kernel and the header with its load / store helpers, concatenated
+        digest = hashlib.sha256(b"".join(open(os.path.join(csrc, n), "rb").read()
+                                         for n in ("copy_kernel.hip", "device_util.h"))).hexdigest()
         if fields.get("kernel_source_sha256") != digest:
             return None
         return float(fields["traffic_bytes_per_launch"])

@@ -101,6 +101,13 @@ const char *vccl_last_error(void);
  *       "ce_engines" (read-only: SDMA engines found),
  *       "ce_max_engines" (0 = all; else use only that many engines),
  *       "check" (0/1 overlap validation),
+ *       "moe_gather_variant" (row gather of vccl_moe_pack: 208 / 308 = one workgroup of 8
+ *       wavefronts per 2 KiB piece of a token's row, one wavefront per slot, non-temporal /
+ *       plain stores; 4, 8, 16 = one wavefront per token holding that many vectors per lane,
+ *       non-temporal stores; 108, 116 = the same with plain stores),
+ *       "moe_unpack_variant" (row un-permute of vccl_moe_unpack: 0 = one workgroup per row,
+ *       1 / 2 = one wavefront per 1 KiB tile with non-temporal / device-scope stores,
+ *       3 = one wavefront per two tiles, device-scope stores),
  *       "fifo_chunk_bytes", "fifo_slots", "fifo_wg_per_conn",
  *       "fifo_spin_limit" (polls before a staged wait gives up).
  * vccl_get_option writes the current value as text into out[0..cap). */

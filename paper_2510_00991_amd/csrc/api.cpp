@@ -339,9 +339,12 @@ int vccl_set_option(const char *key, const char *value) {
         if (!in(1, 8)) return fail(VCCL_ERR_ARG, "ce_streams must be 1..8");
         o.ce_streams = (int)x;
     } else if (k == "moe_gather_variant") {
-        if (!(x == 4 || x == 8 || x == 16 || x == 108 || x == 116))
-            return fail(VCCL_ERR_ARG, "moe_gather_variant must be 4, 8, 16, 108 or 116");
+        if (!(x == 4 || x == 8 || x == 16 || x == 108 || x == 116 || x == 208 || x == 308))
+            return fail(VCCL_ERR_ARG, "moe_gather_variant must be 4, 8, 16, 108, 116, 208 or 308");
         o.moe_gather_variant = (int)x;
+    } else if (k == "moe_unpack_variant") {
+        if (!in(0, 3)) return fail(VCCL_ERR_ARG, "moe_unpack_variant must be 0..3");
+        o.moe_unpack_variant = (int)x;
     } else if (k == "ce_max_engines") {
         if (!in(0, 16)) return fail(VCCL_ERR_ARG, "ce_max_engines must be 0..16");
         o.ce_max_engines = (int)x;
@@ -390,6 +393,7 @@ int vccl_get_option(const char *key, char *out, int cap) {
     else if (k == "cu_fast_path") v = o.cu_fast_path;
     else if (k == "ce_streams") v = o.ce_streams;
     else if (k == "moe_gather_variant") v = o.moe_gather_variant;
+    else if (k == "moe_unpack_variant") v = o.moe_unpack_variant;
     else if (k == "ce_max_engines") v = o.ce_max_engines;
     else if (k == "check") v = o.check;
     else if (k == "fifo_chunk_bytes") v = o.fifo_chunk_bytes;
@@ -531,7 +535,7 @@ int vccl_moe_unpack(const void *const *packed, const int32_t *const *expert_ids,
             return fail(VCCL_ERR_ARG, "packed / out of rank %d are not 16-byte aligned", s);
     }
     return launch_moe_unpack(c->moe, packed, expert_ids, P, tokens, topk, row_bytes, num_experts, out,
-                             (hipStream_t)stream);
+                             options_of(*c).moe_unpack_variant, (hipStream_t)stream);
 }
 
 int vccl_moe_exchange_layout(const uint64_t *counts, int P, int num_experts, int experts_per_rank,

@@ -42,7 +42,8 @@ struct Options {
     int cu_nontemporal = 2;
     int cu_threads = 64;
     int cu_fast_path = 1;
-    int moe_gather_variant = 116;
+    int moe_gather_variant = 208;
+    int moe_unpack_variant = 2;
     int ce_streams = 4;
     int ce_kind = 0;   // VCCL_CE_*
     int ce_max_engines = 0;
@@ -152,7 +153,7 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
 
 int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *const *ids, int P,
                       int tokens, int topk, uint64_t row_bytes, int num_experts, void *const *out,
-                      hipStream_t stream);
+                      int unpack_variant, hipStream_t stream);
 
 // ---- co-run probe
 int launch_fma_probe(float *out, uint32_t workgroups, uint32_t threads, uint64_t iters,

@@ -10,15 +10,16 @@
 //   2 scan        per expert: exclusive sum over blocks; across experts: exclusive
 //                 sum with a wavefront shuffle scan  -> first row of (block, expert)
 //   3 rank        wavefront ballot matching gives each pair its stable position
-//   4 gather      one wavefront per token reads the row once into registers and
-//                 stores it to its K destinations (16 bytes per lane per access)
+//   4 gather      a workgroup of 8 wavefronts per 2 KiB piece of a token's row: every
+//                 wavefront loads the piece (the CU's vector cache serves the
+//                 repeats, HBM is read once) and stores it to the destination of
+//                 its own slot k (16 bytes per lane per access)
 // The combine direction (vccl_moe_unpack) reuses launches 1-3 and replaces the
 // gather by its inverse: row dest(t,k) of the packed buffer goes to row t*K+k.
 #include "common.h"
+#include "device_util.h"
 
 namespace vccl {
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kPairsPerBlock = 2048;
 constexpr int kMoeThreads = 256;
@@ -176,6 +177,50 @@ __global__ __launch_bounds__(kMoeThreads) void moe_gather_kernel(MoePtrs ptrs, u
     }
 }
 
+// Gather, shared-piece form.  Scattered 14 KiB-row writes cap HBM at about
+// 5.5 TB/s whatever the workgroup shape; what this form removes is the long
+// per-wavefront store sequence of the token-major kernel above (a wavefront there
+// holds a row and issues K x 14 stores): here a wavefront loads at most two
+// vectors per lane and stores them once.  Workgroup id = (token, piece, slot group);
+// wavefront w of the workgroup serves slot k = 8*group + w.
+constexpr int kPieceVecs = 128;   // 2 KiB
+constexpr int kSlotWaves = 8;
+template <bool NT>
+__global__ __launch_bounds__(kSlotWaves * 64) void moe_gather_shared_kernel(MoePtrs ptrs, uint32_t tokens, int K,
+                                                                            uint32_t row_vecs, uint32_t pieces,
+                                                                            uint32_t kgroups, const uint32_t *dest,
+                                                                            uint32_t npairs) {
+    const uint32_t rank = blockIdx.y;
+    const uint32_t per_token = pieces * kgroups;
+    const uint32_t t = blockIdx.x / per_token;
+    const uint32_t rem = blockIdx.x - t * per_token;
+    const uint32_t piece = rem / kgroups;
+    // the wavefront index is the same in all lanes: say so, which makes the
+    // destination-row lookup a scalar load
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t k = (rem - piece * kgroups) * kSlotWaves + wave;
+    if (t >= tokens || k >= (uint32_t)K) return;
+    const uint32_t v0 = piece * kPieceVecs + (threadIdx.x & 63u), v1 = v0 + 64u;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(ptrs.x[rank]) + (size_t)t * row_vecs;
+    // Row loads go out before the destination row is known (for a dropped pair they
+    // are wasted, which is rare).  Cached loads on purpose: the other 7 wavefronts
+    // read the same piece.
+    u32x4 r0 = {0, 0, 0, 0}, r1 = {0, 0, 0, 0};
+    if (v0 < row_vecs) r0 = row[v0];
+    if (v1 < row_vecs) r1 = row[v1];
+    const uint32_t j = dest[(size_t)rank * npairs + (size_t)t * K + k];
+    if (j == kDropped) return;
+    u32x4 *o = reinterpret_cast<u32x4 *>(ptrs.packed[rank]) + (size_t)j * row_vecs;
+    if (v0 < row_vecs) {
+        if (NT) __builtin_nontemporal_store(r0, o + v0);
+        else o[v0] = r0;
+    }
+    if (v1 < row_vecs) {
+        if (NT) __builtin_nontemporal_store(r1, o + v1);
+        else o[v1] = r1;
+    }
+}
+
 // Inverse of the gather (combine direction): one workgroup per pair p = t*K + k
 // copies the packed row that pair was sent to back to row p of `out`.  Writes sweep
 // `out` front to back (the tight address window HBM likes), reads hop between
@@ -203,6 +248,30 @@ __global__ __launch_bounds__(kMoeThreads) void moe_scatter_back_kernel(MoePtrs p
             if (v < row_vecs) __builtin_nontemporal_store(r[u], o + v);
         }
     }
+}
+
+// Combine direction, tile form: one single-wavefront workgroup per 1 KiB tile of
+// `out`, in address order - the launch shape of the exchange copy kernel, which
+// HBM serves best; the reads hop between expert regions row by row.
+template <int POL, int TILES>
+__global__ __launch_bounds__(64) void moe_scatter_back_tiles_kernel(MoePtrs ptrs, uint32_t row_vecs,
+                                                                    uint32_t groups_per_row, const uint32_t *dest,
+                                                                    uint32_t npairs) {
+    const uint32_t rank = blockIdx.y;
+    const uint32_t p = blockIdx.x / groups_per_row;
+    const uint32_t v0 = (blockIdx.x - p * groups_per_row) * (64u * TILES);
+    if (p >= npairs) return;
+    const uint32_t j = dest[(size_t)rank * npairs + p];
+    if (j == kDropped) return;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(ptrs.x[rank]) + (size_t)j * row_vecs + v0;   // packed side
+    const TileDst<POL> o(reinterpret_cast<u32x4 *>(ptrs.packed[rank]) + (size_t)p * row_vecs + v0);
+    u32x4 r[TILES];
+#pragma unroll
+    for (int u = 0; u < TILES; ++u)
+        if (v0 + u * 64u + threadIdx.x < row_vecs) r[u] = ld16<POL>(row + u * 64u + threadIdx.x);
+#pragma unroll
+    for (int u = 0; u < TILES; ++u)
+        if (v0 + u * 64u + threadIdx.x < row_vecs) o.store(u * 64u + threadIdx.x, r[u]);
 }
 
 void MoeScratch::destroy() {
@@ -301,7 +370,14 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
         const uint32_t tok_blocks = ((uint32_t)tokens + kMoeThreads / 64 - 1) / (kMoeThreads / 64);
         const dim3 g(tok_blocks, P), b(kMoeThreads);
         const uint32_t rv = (uint32_t)(row_bytes >> 4);
+        const uint32_t pieces = (rv + kPieceVecs - 1) / kPieceVecs;
+        const uint32_t kgroups = ((uint32_t)topk + kSlotWaves - 1) / kSlotWaves;
+        const uint64_t shared_grid = (uint64_t)tokens * pieces * kgroups;
+        if ((gather_variant == 208 || gather_variant == 308) && shared_grid > 0x7fffffffull) gather_variant = 116;
+        const dim3 gs((uint32_t)shared_grid, P), bs(kSlotWaves * 64);
         switch (gather_variant) {
+            case 208: moe_gather_shared_kernel<true><<<gs, bs, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, dest, npairs); break;
+            case 308: moe_gather_shared_kernel<false><<<gs, bs, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, dest, npairs); break;
             case 4: moe_gather_kernel<4, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
             case 16: moe_gather_kernel<16, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
             case 108: moe_gather_kernel<8, false><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
@@ -319,7 +395,7 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
 
 int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *const *ids, int P,
                       int tokens, int topk, uint64_t row_bytes, int num_experts, void *const *out,
-                      hipStream_t stream) {
+                      int unpack_variant, hipStream_t stream) {
     const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
     std::lock_guard<std::mutex> lk(sc.mu);
     MoePtrs ptrs;
@@ -328,8 +404,18 @@ int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *
                              &ptrs, &dest);
     if (rc) return rc;
     if (npairs) {
-        moe_scatter_back_kernel<<<dim3(npairs, P), dim3(kMoeThreads), 0, stream>>>(
-            ptrs, (uint32_t)(row_bytes >> 4), dest, npairs);
+        const uint32_t rv = (uint32_t)(row_bytes >> 4);
+        const uint32_t tiles = unpack_variant == 3 ? 2u : 1u;   // 1 KiB tiles per wavefront
+        const uint32_t groups_per_row = (rv + 64u * tiles - 1u) / (64u * tiles);
+        const uint64_t tile_grid = (uint64_t)npairs * groups_per_row;
+        if (unpack_variant != 0 && tile_grid <= 0x7fffffffull && rv) {
+            const dim3 g((uint32_t)tile_grid, P), b(64);
+            if (unpack_variant == 3) moe_scatter_back_tiles_kernel<2, 2><<<g, b, 0, stream>>>(ptrs, rv, groups_per_row, dest, npairs);
+            else if (unpack_variant == 2) moe_scatter_back_tiles_kernel<2, 1><<<g, b, 0, stream>>>(ptrs, rv, groups_per_row, dest, npairs);
+            else moe_scatter_back_tiles_kernel<1, 1><<<g, b, 0, stream>>>(ptrs, rv, groups_per_row, dest, npairs);
+        } else {
+            moe_scatter_back_kernel<<<dim3(npairs, P), dim3(kMoeThreads), 0, stream>>>(ptrs, rv, dest, npairs);
+        }
         VCCL_HIP(hipGetLastError());
     }
     VCCL_HIP(hipEventRecord(sc.done, stream));

@@ -177,6 +177,25 @@ def test_combine_roundtrip_copy_engine(vccl):
     _combine(torch, vccl, 4, 600, 8, 64, 2048, 901, vccl.MODE_CE)
 
 
+@pytest.mark.parametrize("gather,unpack", [(116, 0), (208, 1), (308, 2), (8, 3)])
+@pytest.mark.parametrize("shape", [(2, 333, 11, 22, 2064), (3, 257, 8, 9, 4096 + 16), (2, 100, 17, 18, 16)])
+def test_kernel_variants_roundtrip(vccl, gather, unpack, shape):
+    """Every gather / un-permute kernel form on shapes with more than 8 slots per token
+    (two slot groups of the shared-piece gather), rows that end inside a 2 KiB piece and
+    inside a 1 KiB tile, and a one-vector row."""
+    torch = require_gpu()
+    P, T, K, E, row = shape
+    E = max(P, (E // P) * P)
+    saved = (vccl.vccl_get_option("moe_gather_variant"), vccl.vccl_get_option("moe_unpack_variant"))
+    vccl.vccl_set_option("moe_gather_variant", gather)
+    vccl.vccl_set_option("moe_unpack_variant", unpack)
+    try:
+        _combine(torch, vccl, P, T, K, E, row, 1200 + T, vccl.MODE_CU)
+    finally:
+        vccl.vccl_set_option("moe_gather_variant", saved[0])
+        vccl.vccl_set_option("moe_unpack_variant", saved[1])
+
+
 def test_unpack_leaves_rows_of_dropped_pairs_untouched(vccl):
     torch = require_gpu()
     T, K, E, row = 40, 2, 4, 32
