@@ -184,13 +184,16 @@ def main():
             co = CoRun(torch)
             cor_cu = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes, kern)
             # the same path with its grid capped to one workgroup per compute unit
+            # (4 wavefronts of 8 vectors per lane each, so that 256 workgroups can keep HBM busy)
             v.vccl_set_option("cu_max_wg", co.cu)
             v.vccl_set_option("cu_unroll", 8)
+            v.vccl_set_option("cu_threads", 256)
             wcap, _ = time_calls(torch, a2a_cu, 5, 2)
             cor_cap = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes, wcap / 5)
             cor_cap["GBps_alone"] = algo_bytes / (wcap / 5) / 1e9
             v.vccl_set_option("cu_max_wg", 0)
             v.vccl_set_option("cu_unroll", 1)
+            v.vccl_set_option("cu_threads", 64)
             wce, _ = time_calls(torch, a2a_ce, 3, 1)
             cor_ce = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CE, sh), algo_bytes, wce / 3)
             out["corun"] = {"probe": f"FMA kernel, {co.cu} workgroups x {co.threads} threads, "

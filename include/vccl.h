@@ -88,7 +88,7 @@ const char *vccl_last_error(void);
  *       "cu_max_wg" (cap on the copy grid, 0 = none; the co-run study sweeps it),
  *       "cu_nontemporal" (0 plain accesses, 1 non-temporal loads and stores, 2 non-temporal
  *                         loads and device-scope stores), "cu_threads" (64 | 128 | 256 lanes per
- *                         workgroup of the all-aligned kernels), "cu_fast_path" (0/1: allow the all-aligned kernel),
+ *                         workgroup of the copy kernels), "cu_fast_path" (0/1: allow the all-aligned kernel),
  *       "ce_kind" (copy-engine back end: "sdma" = SDMA engines driven
  *       through the HSA runtime with stream write/wait-value ordering, the default when the
  *       device supports it; "hip_nocu" / "hip_default" = hipMemcpyAsync on internal streams
@@ -162,14 +162,17 @@ int vccl_alltoallv(void *const *sendbuf, const uint64_t *sendcounts, const uint6
  * description it reports the copy descriptors in launch order - non-empty segments,
  * destination-major with the source rotated by the destination index (the incast
  * counter-measure, Section 6), long segments cut into pieces of equal tile count -
- * and the launch grid: grid_x tiles of *tile_bytes bytes per descriptor (cu_unroll
- * vectors per lane; cu_threads lanes per workgroup when every descriptor is 16-byte
- * aligned and the all-aligned kernel applies, 256 otherwise), grid_y descriptors.  head is the number of leading bytes copied bytewise before
- * the destination is 16-byte aligned; all_aligned tells whether the fast kernel
- * applies.  out may be NULL to query the count. */
+ * and the launch grid: grid_x tiles of *tile_bytes = 16 * cu_unroll * cu_threads
+ * bytes per descriptor, grid_y descriptors.
+ * head is the number of leading bytes copied bytewise before the destination is
+ * 16-byte aligned.  Tiles are cut where the destination address is a multiple of
+ * *tile_bytes: lead is the number of 16-byte vectors between the last such multiple
+ * and dst + head, and a descriptor has ceil(((bytes - head) / 16 + lead) /
+ * (*tile_bytes / 16)) tiles, at least one.  all_aligned tells whether the fast
+ * kernel applies.  out may be NULL to query the count. */
 typedef struct {
     uint64_t src, dst, bytes;
-    uint32_t head, reserved;
+    uint32_t head, lead;
 } vccl_plan_desc;
 int vccl_plan_alltoallv(void *const *sendbuf, const uint64_t *sendcounts, const uint64_t *sdispls,
                         void *const *recvbuf, const uint64_t *recvcounts, const uint64_t *rdispls,

@@ -197,7 +197,7 @@ def vccl_alltoallv(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P
 def vccl_plan_alltoallv(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdispls, P: int,
                         cu_unroll: int = 1, cu_threads: int = 64):
     """Planner only (no device needed).  Returns (descriptors, grid_x, grid_y, tile_bytes,
-    all_aligned); descriptors is a structured array with fields src, dst, bytes, head."""
+    all_aligned); descriptors is a structured array with fields src, dst, bytes, head, lead."""
     sc, sd, rc, rd = (_u64(m, (P, P)) for m in (sendcounts, sdispls, recvcounts, rdispls))
     n, gx, gy, al = ctypes.c_int(), ctypes.c_uint32(), ctypes.c_uint32(), ctypes.c_int()
     tb = ctypes.c_uint32()
@@ -205,7 +205,7 @@ def vccl_plan_alltoallv(sendbuf, sendcounts, sdispls, recvbuf, recvcounts, rdisp
     _check(load().vccl_plan_alltoallv(*args, None, 0, ctypes.byref(n), ctypes.byref(gx), ctypes.byref(gy),
                                       ctypes.byref(tb), ctypes.byref(al)))
     dt = np.dtype([("src", np.uint64), ("dst", np.uint64), ("bytes", np.uint64), ("head", np.uint32),
-                   ("reserved", np.uint32)])
+                   ("lead", np.uint32)])
     out = np.zeros(max(1, n.value), dtype=dt)
     _check(load().vccl_plan_alltoallv(*args, ctypes.c_void_p(out.ctypes.data), out.size, ctypes.byref(n),
                                       ctypes.byref(gx), ctypes.byref(gy), ctypes.byref(tb), ctypes.byref(al)))

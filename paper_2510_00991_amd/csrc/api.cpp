@@ -152,7 +152,7 @@ static int run_pieces(Context &c, std::vector<Piece> &pieces, vccl_mode mode, hi
             if (pc.bytes) plan.segs.push_back(Seg{pc.src, pc.dst, pc.bytes, 0, 0});
         // the all-aligned kernel needs the full grid
         const bool allow_fast = opt.cu_fast_path && !opt.cu_max_wg && !opt.cu_wg_per_cu;
-        int rv = plan_tiles(plan, opt.cu_unroll, allow_fast ? opt.cu_threads : 0);
+        int rv = plan_tiles(plan, opt.cu_unroll, opt.cu_threads, allow_fast);
         if (rv) return rv;
         return launch_copy(plan, opt, c.cu_count, c.ring, stream);
     }
@@ -590,7 +590,7 @@ int vccl_plan_alltoallv(void *const *sendbuf, const uint64_t *sendcounts, const 
     if (rv) return rv;
     CopyPlan plan;
     for (const Piece &pc : pieces) plan.segs.push_back(Seg{pc.src, pc.dst, pc.bytes, 0, 0});
-    rv = plan_tiles(plan, cu_unroll, cu_threads);
+    rv = plan_tiles(plan, cu_unroll, cu_threads, true);
     if (rv) return rv;
     *n_out = (int)plan.segs.size();
     if (grid_x) *grid_x = plan.max_tiles;
@@ -605,7 +605,7 @@ int vccl_plan_alltoallv(void *const *sendbuf, const uint64_t *sendcounts, const 
             out[i].dst = reinterpret_cast<uintptr_t>(plan.segs[i].dst);
             out[i].bytes = plan.segs[i].bytes;
             out[i].head = plan.segs[i].head;
-            out[i].reserved = 0;
+            out[i].lead = plan.segs[i].lead;
         }
     }
     return VCCL_OK;

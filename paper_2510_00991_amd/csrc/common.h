@@ -19,13 +19,15 @@ namespace vccl {
 
 // One contiguous piece of an exchange: `bytes` bytes from src to dst.  head is the
 // number of leading bytes copied bytewise so that the vector body starts at a
-// 16-byte aligned destination.
+// 16-byte aligned destination; lead is the number of 16-byte vectors between the
+// last multiple of the tile size and that body start (tiles are cut at
+// destination multiples of the tile size, the first one is short by `lead`).
 struct Seg {
     const uint8_t *src;
     uint8_t *dst;
     uint64_t bytes;
     uint32_t head;
-    uint32_t reserved;
+    uint32_t lead;
 };
 static_assert(sizeof(Seg) == 32, "descriptor layout");
 
@@ -33,7 +35,6 @@ static_assert(sizeof(Seg) == 32, "descriptor layout");
 enum { VCCL_CE_SDMA = 0, VCCL_CE_HIP_NOCU = 1, VCCL_CE_HIP_DEFAULT = 2 };
 
 constexpr int kInlineSegs = 64;     // descriptors carried in the kernel arguments
-constexpr int kCopyThreads = 256;   // 4 wavefronts per workgroup
 
 struct Options {
     int cu_unroll = 1;
@@ -94,12 +95,13 @@ struct CopyPlan {
     uint32_t max_tiles = 0;      // tiles of the longest descriptor (grid x)
     bool all_aligned = false;    // every descriptor: 16-byte aligned ends, whole vectors
     bool fast = false;           // tiled for (and to be run by) the all-aligned kernel
-    int threads = kCopyThreads;  // lanes per workgroup the tiles were sized for
+    int threads = 64;            // lanes per workgroup the tiles were sized for
     uint64_t bytes = 0;
 };
 // Fills tile_begin/head for plan.segs (src, dst, bytes already set).
-// fast_threads > 0 allows the all-aligned kernel with that many lanes per workgroup.
-int plan_tiles(CopyPlan &plan, int unroll, int fast_threads);
+// Tiles are unroll * threads vectors; allow_fast lets an all-aligned plan select the
+// kernel without head / tail / realignment code (it needs the full grid).
+int plan_tiles(CopyPlan &plan, int unroll, int threads, bool allow_fast);
 int launch_copy(const CopyPlan &plan, const Options &opt, int cu_count, DescRing &ring,
                 hipStream_t stream);
 

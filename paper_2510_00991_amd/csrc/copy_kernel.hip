@@ -6,16 +6,18 @@
 //
 // Work decomposition: a segment is split into a bytewise head (until the
 // destination is 16-byte aligned), a body of 16-byte vectors cut into tiles of
-// U*256 vectors, and a bytewise tail.  The grid is two-dimensional: blockIdx.y
+// U*T vectors (T lanes per workgroup, 64 by default) at destination addresses
+// that are multiples of the tile size, and a bytewise tail.  The grid is
+// two-dimensional: blockIdx.y
 // names the descriptor, blockIdx.x the tile inside it, so a workgroup finds its
 // work with one scalar load and no search.  The host planner cuts long segments
 // into pieces so that all descriptors have about the same number of tiles.
 // One small tile per workgroup keeps the set of addresses in flight at any
 // moment inside a few MiB that sweep forward through the buffers, which is what
 // HBM rewards; a capped grid (for the co-run study) strides over tiles instead.
-// When source and destination of a body disagree modulo 16 the tile goes
-// through LDS: aligned 16-byte global loads, a byte funnel shift in registers,
-// aligned 16-byte stores.
+// When source and destination of a body disagree modulo 16 each lane loads the
+// two aligned words that cover its vector and funnel-shifts them in registers:
+// aligned 16-byte loads, aligned 16-byte stores.
 #include "common.h"
 #include "device_util.h"
 
@@ -29,14 +31,33 @@ struct CopyArgs {
     Seg inl[kInlineSegs];
 };
 
-constexpr int kLdsVecs = 1024;  // vectors staged per LDS round of the realign path
-
 __device__ __forceinline__ uint32_t funnel(uint32_t lo, uint32_t hi, uint32_t byte_shift) {
     return (uint32_t)((((uint64_t)hi << 32) | lo) >> (8u * byte_shift));
 }
 
-template <int U, int NT, bool INLINE>
-__global__ __launch_bounds__(kCopyThreads) void copy_segments_kernel(CopyArgs by_value) {
+// Output vector made of bytes [mis, mis + 16) of the 32 bytes lo:hi (0 < mis < 16).
+__device__ __forceinline__ u32x4 realign(u32x4 lo, u32x4 hi, uint32_t q, uint32_t sh) {
+    const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    switch (q) {  // wave-uniform
+        case 0: return u32x4{funnel(w[0], w[1], sh), funnel(w[1], w[2], sh), funnel(w[2], w[3], sh),
+                             funnel(w[3], w[4], sh)};
+        case 1: return u32x4{funnel(w[1], w[2], sh), funnel(w[2], w[3], sh), funnel(w[3], w[4], sh),
+                             funnel(w[4], w[5], sh)};
+        case 2: return u32x4{funnel(w[2], w[3], sh), funnel(w[3], w[4], sh), funnel(w[4], w[5], sh),
+                             funnel(w[5], w[6], sh)};
+        default: return u32x4{funnel(w[3], w[4], sh), funnel(w[4], w[5], sh), funnel(w[5], w[6], sh),
+                              funnel(w[6], w[7], sh)};
+    }
+}
+
+// General kernel: any byte alignment, any grid (workgroups stride over descriptors
+// and tiles when the grid is capped).  A segment is head bytes (until the
+// destination is 16-byte aligned), body vectors, tail bytes.  When the body's
+// source is not 16-byte aligned each lane loads the two aligned words that cover
+// its output vector (the second is its neighbour's first and comes from cache) and
+// funnel-shifts them in registers: aligned loads, aligned stores, no LDS, no barrier.
+template <int U, int NT, bool INLINE, int T>
+__global__ __launch_bounds__(T) void copy_segments_kernel(CopyArgs by_value) {
     (void)by_value;
     // The argument block is read in place (dynamic indexing of a by-value
     // aggregate could otherwise be spilled to private memory).
@@ -45,9 +66,7 @@ __global__ __launch_bounds__(kCopyThreads) void copy_segments_kernel(CopyArgs by
     const Seg *segs = INLINE ? a->inl : a->table;
     const uint32_t nseg = a->nseg;
     const uint32_t tid = threadIdx.x;
-    constexpr uint32_t kTileVecs = (uint32_t)U * kCopyThreads;
-
-    __shared__ u32x4 stage[kLdsVecs + 1];
+    constexpr uint32_t kTileVecs = (uint32_t)U * T;
 
     for (uint32_t si = blockIdx.y; si < nseg; si += gridDim.y) {
         const uint8_t *src = segs[si].src;
@@ -60,14 +79,20 @@ __global__ __launch_bounds__(kCopyThreads) void copy_segments_kernel(CopyArgs by
             const uint32_t tail = (uint32_t)(body & 15u);
             if (tid < head) {
                 dst[tid] = src[tid];
-            } else if (tid >= 64u && tid < 64u + tail) {
-                const uint64_t o = head + (nv << 4) + (tid - 64u);
+            } else if (tid >= 16u && tid < 16u + tail) {
+                const uint64_t o = head + (nv << 4) + (tid - 16u);
                 dst[o] = src[o];
             }
         }
-        for (uint64_t v0 = (uint64_t)blockIdx.x * kTileVecs; v0 < nv;
-             v0 += (uint64_t)gridDim.x * kTileVecs) {
-            const uint32_t cnt = (uint32_t)min((uint64_t)kTileVecs, nv - v0);
+        // Tiles are cut at destination addresses that are multiples of the tile size
+        // (`lead` vectors precede the segment's body inside its first tile), so a
+        // wavefront's stores cover whole cache lines whatever the buffer offset.
+        const uint32_t lead = segs[si].lead;
+        const uint64_t ntiles = (nv + lead + kTileVecs - 1) / kTileVecs;
+        for (uint64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+            const uint64_t end = (tile + 1) * kTileVecs - lead;   // >= 1
+            const uint64_t v0 = tile ? tile * kTileVecs - lead : 0;
+            const uint32_t cnt = (uint32_t)(min(end, nv) - v0);
             const uint8_t *sb = src + head + (v0 << 4);
             const TileDst<NT> d(reinterpret_cast<u32x4 *>(dst + head + (v0 << 4)));
             const uint32_t mis = (uint32_t)(reinterpret_cast<uintptr_t>(sb) & 15u);
@@ -76,39 +101,30 @@ __global__ __launch_bounds__(kCopyThreads) void copy_segments_kernel(CopyArgs by
                 if (cnt == kTileVecs) {
                     u32x4 r[U];
 #pragma unroll
-                    for (int u = 0; u < U; ++u) r[u] = ld16<NT>(s + u * kCopyThreads + tid);
+                    for (int u = 0; u < U; ++u) r[u] = ld16<NT>(s + u * T + tid);
 #pragma unroll
-                    for (int u = 0; u < U; ++u) d.store(u * kCopyThreads + tid, r[u]);
+                    for (int u = 0; u < U; ++u) d.store(u * T + tid, r[u]);
                 } else {
-                    for (uint32_t i = tid; i < cnt; i += kCopyThreads) d.store(i, ld16<NT>(s + i));
+                    for (uint32_t i = tid; i < cnt; i += T) d.store(i, ld16<NT>(s + i));
                 }
             } else {
-                // Every aligned word read below holds at least one byte of the segment
-                // (mis > 0), so it lies on a page the segment itself touches.
+                // Output vector i is bytes [mis, mis + 16) of aligned words i and i + 1.
+                // Both hold at least one byte of the segment (0 < mis < 16), so they lie
+                // on pages the segment itself touches.
                 const u32x4 *sa = reinterpret_cast<const u32x4 *>(sb - mis);
                 const uint32_t q = mis >> 2, sh = mis & 3u;
-                for (uint32_t c0 = 0; c0 < cnt; c0 += kLdsVecs) {
-                    const uint32_t m = min((uint32_t)kLdsVecs, cnt - c0);
-                    __syncthreads();
-                    for (uint32_t i = tid; i < m; i += kCopyThreads) stage[i] = ld16<NT>(sa + c0 + i);
-                    if (tid == 0) stage[m] = ld16<NT>(sa + c0 + m);
-                    __syncthreads();
-                    for (uint32_t i = tid; i < m; i += kCopyThreads) {
-                        const u32x4 lo = stage[i], hi = stage[i + 1];
-                        const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                        u32x4 o;
-                        switch (q) {  // wave-uniform
-                            case 0: o = u32x4{funnel(w[0], w[1], sh), funnel(w[1], w[2], sh),
-                                              funnel(w[2], w[3], sh), funnel(w[3], w[4], sh)}; break;
-                            case 1: o = u32x4{funnel(w[1], w[2], sh), funnel(w[2], w[3], sh),
-                                              funnel(w[3], w[4], sh), funnel(w[4], w[5], sh)}; break;
-                            case 2: o = u32x4{funnel(w[2], w[3], sh), funnel(w[3], w[4], sh),
-                                              funnel(w[4], w[5], sh), funnel(w[5], w[6], sh)}; break;
-                            default: o = u32x4{funnel(w[3], w[4], sh), funnel(w[4], w[5], sh),
-                                               funnel(w[5], w[6], sh), funnel(w[6], w[7], sh)}; break;
-                        }
-                        d.store(c0 + i, o);
+                if (cnt == kTileVecs) {
+                    u32x4 lo[U], hi[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        lo[u] = ld16<NT>(sa + u * T + tid);
+                        hi[u] = ld16<0>(sa + u * T + tid + 1);
                     }
+#pragma unroll
+                    for (int u = 0; u < U; ++u) d.store(u * T + tid, realign(lo[u], hi[u], q, sh));
+                } else {
+                    for (uint32_t i = tid; i < cnt; i += T)
+                        d.store(i, realign(ld16<NT>(sa + i), ld16<0>(sa + i + 1), q, sh));
                 }
             }
         }
@@ -127,19 +143,23 @@ __global__ __launch_bounds__(T) void copy_aligned_kernel(CopyArgs by_value) {
     const Seg *sg = (INLINE ? a->inl : a->table) + blockIdx.y;
     constexpr uint32_t kTileVecs = (uint32_t)U * T;
     const uint64_t nv = sg->bytes >> 4;
-    const uint64_t v0 = (uint64_t)blockIdx.x * kTileVecs;
+    // tile 0 holds the `lead` vectors' worth of room before the segment, so that
+    // every later tile starts on a destination address that is a multiple of the tile
+    const uint32_t lead = sg->lead;
+    const uint64_t end = ((uint64_t)blockIdx.x + 1) * kTileVecs - lead;
+    const uint64_t v0 = blockIdx.x ? (uint64_t)blockIdx.x * kTileVecs - lead : 0;
     if (v0 >= nv) return;
     const u32x4 *s = reinterpret_cast<const u32x4 *>(sg->src) + v0;
     const TileDst<NT> d(reinterpret_cast<u32x4 *>(sg->dst) + v0);
     const uint32_t tid = threadIdx.x;
-    if (nv - v0 >= kTileVecs) {
+    if (end - v0 == kTileVecs && end <= nv) {
         u32x4 r[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) r[u] = ld16<NT>(s + u * T + tid);
 #pragma unroll
         for (int u = 0; u < U; ++u) d.store(u * T + tid, r[u]);
     } else {
-        const uint32_t cnt = (uint32_t)(nv - v0);
+        const uint32_t cnt = (uint32_t)(min(end, nv) - v0);
         for (uint32_t i = tid; i < cnt; i += T) d.store(i, ld16<NT>(s + i));
     }
 }
@@ -165,23 +185,27 @@ __global__ __launch_bounds__(T) void copy_uniform_kernel(UniformArgs by_value) {
         reinterpret_cast<const UniformArgs *>((const void *)__builtin_amdgcn_kernarg_segment_ptr());
     constexpr uint32_t kTileVecs = (uint32_t)U * T;
     const uint64_t nv = a->vecs_per_block;
-    const uint64_t v0 = (uint64_t)blockIdx.x * kTileVecs;
-    if (v0 >= nv) return;
     const uint32_t P = a->P;
     const uint32_t k = blockIdx.y / P, r = blockIdx.y - k * P;
     uint32_t s_rank = r + k;
     if (s_rank >= P) s_rank -= P;
+    u32x4 *dseg = reinterpret_cast<u32x4 *>(a->recv[r]) + (uint64_t)s_rank * nv;
+    // destination-aligned tiles, as in the descriptor kernels
+    const uint32_t lead = (uint32_t)((reinterpret_cast<uintptr_t>(dseg) >> 4) & (kTileVecs - 1u));
+    const uint64_t end = ((uint64_t)blockIdx.x + 1) * kTileVecs - lead;
+    const uint64_t v0 = blockIdx.x ? (uint64_t)blockIdx.x * kTileVecs - lead : 0;
+    if (v0 >= nv) return;
     const u32x4 *s = reinterpret_cast<const u32x4 *>(a->send[s_rank]) + (uint64_t)r * nv + v0;
-    const TileDst<NT> d(reinterpret_cast<u32x4 *>(a->recv[r]) + (uint64_t)s_rank * nv + v0);
+    const TileDst<NT> d(dseg + v0);
     const uint32_t tid = threadIdx.x;
-    if (nv - v0 >= kTileVecs) {
+    if (end - v0 == kTileVecs && end <= nv) {
         u32x4 reg[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) reg[u] = ld16<NT>(s + u * T + tid);
 #pragma unroll
         for (int u = 0; u < U; ++u) d.store(u * T + tid, reg[u]);
     } else {
-        const uint32_t cnt = (uint32_t)(nv - v0);
+        const uint32_t cnt = (uint32_t)(min(end, nv) - v0);
         for (uint32_t i = tid; i < cnt; i += T) d.store(i, ld16<NT>(s + i));
     }
 }
@@ -192,7 +216,7 @@ bool uniform_alltoall_applies(void *const *sendbuf, void *const *recvbuf, uint64
     if (P > kUniformRanks || (uint64_t)P * P > 65535 || bytes_per_peer == 0 || (bytes_per_peer & 15u)) return false;
     const uint64_t tiles = ((bytes_per_peer >> 4) + (uint64_t)opt.cu_unroll * opt.cu_threads - 1) /
                            ((uint64_t)opt.cu_unroll * opt.cu_threads);
-    if (tiles > 0x7fffffffull) return false;
+    if (tiles + 1 > 0x7fffffffull) return false;
     for (int i = 0; i < P; ++i)
         if (!sendbuf[i] || !recvbuf[i] ||
             ((reinterpret_cast<uintptr_t>(sendbuf[i]) | reinterpret_cast<uintptr_t>(recvbuf[i])) & 15u))
@@ -210,8 +234,16 @@ int launch_uniform_alltoall(void *const *sendbuf, void *const *recvbuf, uint64_t
     a.vecs_per_block = bytes_per_peer >> 4;
     a.P = (uint32_t)P;
     a.pad = 0;
-    const uint64_t tile_vecs = (uint64_t)opt.cu_unroll * opt.cu_threads;
-    const dim3 grid((uint32_t)((a.vecs_per_block + tile_vecs - 1) / tile_vecs), (uint32_t)(P * P));
+    const uint64_t tile_vecs = (uint64_t)opt.cu_unroll * opt.cu_threads;   // a power of two
+    // destination-aligned tiles: the longest lead over all blocks sizes the grid
+    uint64_t max_lead = 0;
+    for (int r = 0; r < P && max_lead + 1 < tile_vecs; ++r)
+        for (int sr = 0; sr < P; ++sr) {
+            const uint64_t lead =
+                ((reinterpret_cast<uintptr_t>(recvbuf[r]) >> 4) + (uint64_t)sr * a.vecs_per_block) & (tile_vecs - 1);
+            if (lead > max_lead) max_lead = lead;
+        }
+    const dim3 grid((uint32_t)((a.vecs_per_block + max_lead + tile_vecs - 1) / tile_vecs), (uint32_t)(P * P));
     const dim3 block((uint32_t)opt.cu_threads);
 #define VCCL_UNI_T(U, POL)                                                                           \
     if (opt.cu_threads == 64) copy_uniform_kernel<U, POL, 64><<<grid, block, 0, stream>>>(a);        \
@@ -241,9 +273,7 @@ static inline uint32_t head_of(const uint8_t *dst, uint64_t bytes) {
     return (uint32_t)(bytes < to_align ? bytes : to_align);
 }
 
-int plan_tiles(CopyPlan &plan, int unroll, int fast_threads) {
-    // The all-aligned kernel may run with fewer lanes per workgroup (smaller tiles);
-    // which kernel applies has to be known before the segments are tiled.
+int plan_tiles(CopyPlan &plan, int unroll, int threads, bool allow_fast) {
     plan.all_aligned = !plan.segs.empty();
     for (const Seg &s : plan.segs)
         if (((reinterpret_cast<uintptr_t>(s.src) | reinterpret_cast<uintptr_t>(s.dst) | s.bytes) & 15u) != 0) {
@@ -252,13 +282,17 @@ int plan_tiles(CopyPlan &plan, int unroll, int fast_threads) {
         }
     // Cutting (below) adds at most 8192 pieces; the all-aligned kernel needs one
     // grid row per descriptor, and a grid has at most 65535 rows.
-    plan.fast = plan.all_aligned && fast_threads > 0 && plan.segs.size() <= 65535u - 8192u;
-    plan.threads = plan.fast ? fast_threads : kCopyThreads;
+    plan.fast = plan.all_aligned && allow_fast && plan.segs.size() <= 65535u - 8192u;
+    plan.threads = threads;
     const uint64_t tile_vecs = (uint64_t)unroll * plan.threads;
     const uint64_t tile_bytes = tile_vecs << 4;
+    // vectors between the last tile-size multiple and the first body vector of the destination
+    auto lead_of = [&](const Seg &s) {
+        return (uint64_t)((reinterpret_cast<uintptr_t>(s.dst + head_of(s.dst, s.bytes)) >> 4) % tile_vecs);
+    };
     auto tiles_of = [&](const Seg &s) {
         const uint64_t nv = (s.bytes - head_of(s.dst, s.bytes)) >> 4;
-        const uint64_t nt = (nv + tile_vecs - 1) / tile_vecs;
+        const uint64_t nt = (nv + lead_of(s) + tile_vecs - 1) / tile_vecs;
         return nt ? nt : (uint64_t)1;
     };
     uint64_t total = 0, longest = 0;
@@ -272,8 +306,8 @@ int plan_tiles(CopyPlan &plan, int unroll, int fast_threads) {
     // The launch is (tiles of the longest descriptor) x (descriptors); workgroups past
     // the end of a shorter descriptor leave at once.  If that would waste more than
     // 1/16 of the grid, or the grid would not fit, long segments are cut into pieces
-    // of `limit` tiles (cuts fall on 16-byte destination boundaries after the head,
-    // so a piece is itself a segment with an empty head).
+    // of `limit` tiles (cuts fall on destination addresses that are multiples of the
+    // tile size, so a later piece is itself a segment with an empty head and no lead).
     uint64_t limit = longest;
     const uint64_t nseg = plan.segs.size();
     if (nseg && (limit * nseg > total + total / 16 || limit > 0x7fffffffull)) {
@@ -285,12 +319,12 @@ int plan_tiles(CopyPlan &plan, int unroll, int fast_threads) {
         pieces.reserve((size_t)(total / limit + nseg));
         for (const Seg &s : plan.segs) {
             const uint32_t head = head_of(s.dst, s.bytes);
-            const uint64_t first = head + limit * tile_bytes;   // bytes in the first piece
+            const uint64_t first = head + limit * tile_bytes - (lead_of(s) << 4);   // bytes in the first piece
             if (s.bytes <= first) {
                 pieces.push_back(s);
                 continue;
             }
-            pieces.push_back(Seg{s.src, s.dst, first, 0, 0});
+            pieces.push_back(Seg{s.src, s.dst, first, 0, 0});   // head and lead are filled in below
             for (uint64_t off = first; off < s.bytes; off += limit * tile_bytes) {
                 const uint64_t n = s.bytes - off < limit * tile_bytes ? s.bytes - off : limit * tile_bytes;
                 pieces.push_back(Seg{s.src + off, s.dst + off, n, 0, 0});
@@ -302,8 +336,8 @@ int plan_tiles(CopyPlan &plan, int unroll, int fast_threads) {
     longest = 0;
     for (Seg &s : plan.segs) {
         s.head = head_of(s.dst, s.bytes);
+        s.lead = (uint32_t)lead_of(s);
         const uint64_t nt = tiles_of(s);
-        s.reserved = 0;
         tiles += nt;
         if (nt > longest) longest = nt;
     }
@@ -312,26 +346,24 @@ int plan_tiles(CopyPlan &plan, int unroll, int fast_threads) {
     return VCCL_OK;
 }
 
+template <int U, int POL, int T>
+static void launch_threads(bool inl, bool fast, dim3 grid, hipStream_t stream, const CopyArgs &args) {
+    const dim3 block(T);
+    if (fast) {
+        if (inl) copy_aligned_kernel<U, POL, true, T><<<grid, block, 0, stream>>>(args);
+        else copy_aligned_kernel<U, POL, false, T><<<grid, block, 0, stream>>>(args);
+    } else {
+        if (inl) copy_segments_kernel<U, POL, true, T><<<grid, block, 0, stream>>>(args);
+        else copy_segments_kernel<U, POL, false, T><<<grid, block, 0, stream>>>(args);
+    }
+}
+
 template <int U, int POL>
 static void launch_policy(bool inl, bool fast, int threads, dim3 grid, hipStream_t stream,
                           const CopyArgs &args) {
-    if (fast) {
-        const dim3 block((uint32_t)threads);
-        if (threads == 64) {
-            if (inl) copy_aligned_kernel<U, POL, true, 64><<<grid, block, 0, stream>>>(args);
-            else copy_aligned_kernel<U, POL, false, 64><<<grid, block, 0, stream>>>(args);
-        } else if (threads == 128) {
-            if (inl) copy_aligned_kernel<U, POL, true, 128><<<grid, block, 0, stream>>>(args);
-            else copy_aligned_kernel<U, POL, false, 128><<<grid, block, 0, stream>>>(args);
-        } else {
-            if (inl) copy_aligned_kernel<U, POL, true, 256><<<grid, block, 0, stream>>>(args);
-            else copy_aligned_kernel<U, POL, false, 256><<<grid, block, 0, stream>>>(args);
-        }
-        return;
-    }
-    const dim3 block(kCopyThreads);
-    if (inl) copy_segments_kernel<U, POL, true><<<grid, block, 0, stream>>>(args);
-    else copy_segments_kernel<U, POL, false><<<grid, block, 0, stream>>>(args);
+    if (threads == 64) launch_threads<U, POL, 64>(inl, fast, grid, stream, args);
+    else if (threads == 128) launch_threads<U, POL, 128>(inl, fast, grid, stream, args);
+    else launch_threads<U, POL, 256>(inl, fast, grid, stream, args);
 }
 
 template <int U>

@@ -158,7 +158,7 @@ def ring_corun(torch, P=8, nbytes=64 << 20, cu_grids=(8, 16, 32, 64, 256), steps
 
     run("cu_direct", v.MODE_CU, 1.0)
     for g in cu_grids:
-        run(f"cu_direct_grid{g}", v.MODE_CU, 1.0, {"cu_max_wg": g, "cu_unroll": 8})
+        run(f"cu_direct_grid{g}", v.MODE_CU, 1.0, {"cu_max_wg": g, "cu_unroll": 8, "cu_threads": 256})
     run("cu_staged_fifo", v.MODE_CU_STAGED, 2.0)
     run("copy_engine", v.MODE_CE, 1.0)
     return {"workload": f"SendRecv ring, {P} stages x {nbytes >> 20} MiB, FMA probe on all CUs",
@@ -297,7 +297,7 @@ def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000,
 
     rows = {}
     for name, mode, opts in (("no_transfer", None, {}), ("cu_path", v.MODE_CU, {}),
-                             ("cu_path_capped_32wg", v.MODE_CU, {"cu_max_wg": 32, "cu_unroll": 8}),
+                             ("cu_path_capped_32wg", v.MODE_CU, {"cu_max_wg": 32, "cu_unroll": 8, "cu_threads": 256}),
                              ("copy_engine", v.MODE_CE, {})):
         saved = _set(opts)
         try:

@@ -281,6 +281,38 @@ def test_copy_kernel_variants(vccl, unroll, nt):
             assert_same(to_host(recv[r]), want[r], f"threads={threads} recv[{r}]")
 
 
+@pytest.mark.parametrize("shift_send,shift_recv", [(16, 16), (528, 0), (0, 1008), (48, 4080)])
+def test_buffers_off_the_tile_boundary(vccl, shift_send, shift_recv):
+    """16-byte aligned buffers that start between tile boundaries: tiles are cut at
+    destination multiples of the tile size, so the first tile of a segment is short
+    (all-aligned kernel, general kernel, and the pointer-table kernel)."""
+    torch = require_gpu()
+    P = 5
+    lay = wl.random_layout(71, P, 300000, align=16, zero_fraction=0.1)
+    send_np = [wl.payload_bytes(72, s, int(lay["send_sizes"][s])) for s in range(P)]
+    ms, mr = [shift_send] * P, [shift_recv] * P
+    for threads in (64, 256):
+        _with_options(vccl, {"cu_threads": threads},
+                      lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CU, ms, mr))
+    _with_options(vccl, {"cu_fast_path": 0}, lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CU, ms, mr))
+    _with_options(vccl, {"cu_unroll": 4}, lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CU, ms, mr))
+    lay1 = wl.random_layout(73, P, 200000, align=1)          # byte-granular counts on shifted buffers
+    send1 = [wl.payload_bytes(74, s, int(lay1["send_sizes"][s])) for s in range(P)]
+    _run_v(torch, vccl, lay1, send1, vccl.MODE_CU, ms, mr)
+    P, c = 11, 70000 - 70000 % 16                             # pointer-table kernel
+    a2a_np = [wl.payload_bytes(75, s, P * c) for s in range(P)]
+    want = [np.full(P * c + 32, SENTINEL, dtype=np.uint8) for _ in range(P)]
+    oracle.alltoall(a2a_np, want, c, threads=4)
+    send = [to_dev(torch, a, shift_send) for a in a2a_np]
+    for unroll in (1, 2):
+        recv = [to_dev(torch, np.full(P * c + 32, SENTINEL, dtype=np.uint8), shift_recv) for _ in range(P)]
+        _with_options(vccl, {"cu_unroll": unroll},
+                      lambda: vccl.vccl_alltoall(send, recv, c, P, vccl.MODE_CU, stream_handle(torch)))
+        torch.cuda.synchronize()
+        for r in range(P):
+            assert_same(to_host(recv[r]), want[r], f"unroll={unroll} recv[{r}]")
+
+
 @pytest.mark.parametrize("kind", ["hip_nocu", "hip_default"])
 def test_event_ordered_copy_backends_are_bit_exact_too(vccl, kind):
     """The hipMemcpyAsync back ends of the copy-engine mode (event ordering)."""

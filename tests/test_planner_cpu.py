@@ -1,6 +1,7 @@
 """Host logic of the compute-unit path, on the CPU: the planner's descriptors must
 tile every non-empty segment exactly once, in the rotated order, with cuts on
-16-byte destination boundaries and a launch grid that wastes little."""
+destination addresses that are multiples of the tile size and a launch grid that
+wastes little."""
 import numpy as np
 import pytest
 
@@ -23,8 +24,13 @@ def _fake_buffers(P, sizes, rng, align=1):
 
 
 def _tiles(desc, tile_bytes):
+    """Tiles start where the destination is a multiple of the tile size; `lead`
+    vectors of the first tile lie before the body of the segment."""
+    tv = tile_bytes // 16
     nv = (int(desc["bytes"]) - int(desc["head"])) // 16
-    return max(1, -(-nv // (tile_bytes // 16)))
+    lead = ((int(desc["dst"]) + int(desc["head"])) // 16) % tv
+    assert int(desc["lead"]) == lead
+    return max(1, -(-(nv + lead) // tv))
 
 
 def _check_plan(lay, send, recv, unroll=1, threads=64):
@@ -50,7 +56,7 @@ def _check_plan(lay, send, recv, unroll=1, threads=64):
                 want_head = min(int(d["bytes"]), (16 - (int(d["dst"]) % 16)) % 16)
                 assert int(d["head"]) == want_head
                 if not first:
-                    assert int(d["dst"]) % 16 == 0 and want_head == 0, "cuts fall on 16-byte boundaries"
+                    assert int(d["dst"]) % tile_bytes == 0 and want_head == 0, "cuts fall on tile boundaries"
                 covered += int(d["bytes"])
                 first = False
                 i += 1
@@ -60,7 +66,7 @@ def _check_plan(lay, send, recv, unroll=1, threads=64):
         want_aligned = all(int(d["src"]) % 16 == 0 and int(d["dst"]) % 16 == 0 and int(d["bytes"]) % 16 == 0
                            for d in desc)
         assert aligned == want_aligned
-        assert tile_bytes == unroll * 16 * (threads if aligned else 256)
+        assert tile_bytes == unroll * 16 * threads
         tiles = [_tiles(d, tile_bytes) for d in desc]
         assert gx == max(tiles) and gy == len(desc)
         waste = gx * len(desc) - sum(tiles)
@@ -114,6 +120,28 @@ def test_skewed_segments_are_cut_into_equal_pieces():
     assert len(desc) > 64, "the long segment must have been cut"
     assert gx < (1 << 30) // TILE, "the grid must not be sized by the uncut long segment"
     assert len(desc) <= 8192 + 64
+
+
+@pytest.mark.parametrize("shift", [16, 528, 1008, 4080])
+@pytest.mark.parametrize("threads", [64, 256])
+def test_shifted_buffers_keep_tiles_on_destination_multiples(shift, threads):
+    """16-byte aligned buffers that do not start on a tile boundary: the fast kernel still
+    applies, every descriptor carries its lead, and cuts of the skewed segment land on
+    multiples of the tile size."""
+    P = 4
+    counts = np.full((P, P), (3 << 20) + 48, dtype=np.uint64)
+    counts[1, 2] = (200 << 20) + 16
+    disp = np.zeros((P, P), dtype=np.uint64)
+    rdisp = np.zeros((P, P), dtype=np.uint64)
+    for a in range(P):
+        disp[a] = np.cumsum(counts[a]) - counts[a]
+        rdisp[a] = np.cumsum(counts.T[a]) - counts.T[a]
+    lay = {"sendcounts": counts, "sdispls": disp, "recvcounts": counts.T.copy(), "rdispls": rdisp}
+    send = [0x7F0000000000 + i * (1 << 32) + shift for i in range(P)]
+    recv = [0x7E0000000000 + i * (1 << 32) + 2 * shift for i in range(P)]
+    desc, gx, gy = _check_plan(lay, send, recv, unroll=1, threads=threads)
+    assert len(desc) > 16, "the long segment must have been cut"
+    assert any(int(d["lead"]) for d in desc)
 
 
 def test_zero_segments_and_errors():
