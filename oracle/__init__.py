@@ -10,6 +10,7 @@ from .oracle import (  # noqa: F401
     sendrecv,
     sendrecv_staged,
     moe_pack,
+    moe_pack_dedup,
     moe_unpack,
     moe_exchange_layout,
     OracleError,

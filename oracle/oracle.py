@@ -162,6 +162,31 @@ def moe_unpack(packed: np.ndarray, ids: np.ndarray, row_bytes: int, num_experts:
     return out
 
 
+def moe_pack_dedup(x: np.ndarray, ids: np.ndarray, row_bytes: int, num_experts: int, experts_per_rank: int):
+    """One row per (token, destination rank).  Returns (packed uint8 [rows*row_bytes],
+    row_token int64 [rows], cnt uint64 [R], slot_row int64 [T*K])."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    T, K = ids.shape
+    if _u8(x).size < T * row_bytes:
+        raise ValueError("x smaller than T rows")
+    if experts_per_rank < 1 or num_experts % experts_per_rank:
+        raise OracleError(-1)
+    R = num_experts // experts_per_rank
+    packed = np.empty(T * min(K, R) * row_bytes, dtype=np.uint8)
+    row_token = np.empty(T * min(K, R), dtype=np.int64)
+    cnt = np.zeros(R, dtype=np.uint64)
+    slot_row = np.full(T * K, -1, dtype=np.int64)
+    rows = ctypes.c_int64(0)
+    rv = _load().oracle_moe_pack_dedup(_vp(x), _vp(ids), ctypes.c_int64(T), ctypes.c_int(K),
+                                       ctypes.c_uint64(row_bytes), ctypes.c_int(num_experts),
+                                       ctypes.c_int(experts_per_rank), _vp(packed), _vp(row_token),
+                                       _vp(cnt), _vp(slot_row), ctypes.byref(rows))
+    if rv:
+        raise OracleError(rv)
+    n = int(rows.value)
+    return packed[:n * row_bytes], row_token[:n], cnt, slot_row
+
+
 def moe_exchange_layout(cnt: np.ndarray, experts_per_rank: int, row_bytes: int):
     """cnt uint64 [P, E] -> dict of the four [P, P] byte matrices of the exchange."""
     cnt = np.ascontiguousarray(cnt, dtype=np.uint64)

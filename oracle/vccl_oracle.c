@@ -28,7 +28,9 @@
  * P = 1, NumPy axis swap, NumPy roll, NumPy stable argsort / bincount,
  * involution, conservation, untouched gaps, hand-worked fixtures, exhaustive
  * tiny cases; unpack(pack(x)) = each row K times and a hand-worked fixture for the
- * un-permute).  No routine is "parity unpinned".
+ * un-permute; the per-rank pack against NumPy's unique over (rank, token) keys, its
+ * reduction to the per-expert pack when no two slots share a rank, and a hand-worked
+ * fixture).  No routine is "parity unpinned".
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -196,6 +198,46 @@ int oracle_moe_unpack(const uint8_t *packed, const int32_t *ids, int64_t T, int 
             ++j;
         }
     }
+    return ORACLE_OK;
+}
+
+/* MoE dispatch pack with one row per (token, destination rank): the reading of
+ * the dispatch phase (paper Section 6) in which a token whose experts share a
+ * rank crosses the fabric once.  Expert e lives on rank e / experts_per_rank;
+ * R = E / experts_per_rank destination ranks.  For r = 0..R-1 in turn and, inside,
+ * t = 0..T-1 in turn: if any of the K slots of token t routes to rank r, the row
+ * of t is appended to `packed`.  row_token[j] is the token of packed row j,
+ * cnt[r] the number of rows bound for rank r, slot_row[t*K + k] the packed row
+ * that serves slot k of token t, *rows the total. */
+int oracle_moe_pack_dedup(const uint8_t *x, const int32_t *ids, int64_t T, int K, uint64_t row_bytes,
+                          int E, int experts_per_rank, uint8_t *packed, int64_t *row_token,
+                          uint64_t *cnt, int64_t *slot_row, int64_t *rows)
+{
+    if (T < 0 || K < 1 || E < 1 || experts_per_rank < 1 || E % experts_per_rank) return ORACLE_ERR_ARG;
+    const int R = E / experts_per_rank;
+    for (int64_t p = 0; p < T * (int64_t)K; ++p)
+        if (ids[p] < 0 || ids[p] >= E) return ORACLE_ERR_ARG;
+    int64_t j = 0;
+    for (int r = 0; r < R; ++r) {
+        cnt[r] = 0;
+        for (int64_t t = 0; t < T; ++t) {
+            int hit = 0;
+            for (int k = 0; k < K; ++k) {
+                if (ids[t * K + k] / experts_per_rank == r) {
+                    hit = 1;
+                    slot_row[t * K + k] = j;
+                }
+            }
+            if (!hit) continue;
+            const uint8_t *row = x + (uint64_t)t * row_bytes;
+            uint8_t *out = packed + (uint64_t)j * row_bytes;
+            for (uint64_t i = 0; i < row_bytes; ++i) out[i] = row[i];
+            row_token[j] = t;
+            ++cnt[r];
+            ++j;
+        }
+    }
+    *rows = j;
     return ORACLE_OK;
 }
 

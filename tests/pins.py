@@ -325,6 +325,74 @@ def pin_moe_unpack_inverts_pack():
         assert np.array_equal(got, want)
 
 
+def pin_moe_dedup_handworked():
+    g = _load("moe_dispatch_dedup_handworked.json")
+    packed, row_token, cnt, slot_row = oracle.moe_pack_dedup(_b(g["x"]), np.array(g["ids"], np.int32),
+                                                             g["row_bytes"], g["E"], g["experts_per_rank"])
+    assert _s(packed) == g["packed"]
+    assert row_token.tolist() == g["row_token"]
+    assert cnt.tolist() == g["cnt"]
+    assert slot_row.tolist() == g["slot_row"]
+
+
+def pin_moe_dedup_is_unique_over_rank_token_keys():
+    """Rows sorted by (destination rank, token) with duplicates removed is NumPy's
+    unique over the keys rank*T + token; the slot map inverts it; a slot's row holds
+    its token's bytes and lies in its rank's block."""
+    for seed, (T, K, E, epr, row) in enumerate(((1, 1, 1, 1, 3), (7, 3, 6, 2, 4), (300, 8, 256, 32, 8),
+                                                (129, 4, 12, 1, 16), (64, 5, 10, 10, 2))):
+        ids = wl.zipf_topk_expert_ids(80 + seed, 0, T, K, E)
+        x = wl.payload_bytes(81 + seed, 0, T * row)
+        packed, row_token, cnt, slot_row = oracle.moe_pack_dedup(x, ids, row, E, epr)
+        R = E // epr
+        rank = (ids // epr).astype(np.int64)
+        keys = (rank * T + np.arange(T, dtype=np.int64)[:, None]).reshape(-1)
+        u, inv = np.unique(keys, return_inverse=True)
+        assert np.array_equal(row_token, u % T)
+        assert np.array_equal(cnt, np.bincount(u // T, minlength=R).astype(np.uint64))
+        assert np.array_equal(slot_row, inv.reshape(-1))
+        rows = packed.reshape(-1, row)
+        assert rows.shape[0] == u.size == int(cnt.sum())
+        assert np.array_equal(rows, x.reshape(T, row)[row_token])
+        assert np.array_equal(rows[slot_row], np.repeat(x.reshape(T, row), K, axis=0))
+        first = np.concatenate(([0], np.cumsum(cnt.astype(np.int64))))
+        assert ((slot_row >= first[rank.reshape(-1)]) & (slot_row < first[rank.reshape(-1) + 1])).all()
+        # every token appears once per distinct destination rank
+        distinct = np.array([len(set(r)) for r in rank.tolist()])
+        assert np.array_equal(np.bincount(row_token, minlength=T), distinct)
+
+
+def pin_moe_dedup_special_cases():
+    # (a) no two slots of a token share a rank: the per-expert pack with rank ids
+    T, K, P, row = 200, 3, 8, 8
+    rng = np.random.Generator(np.random.PCG64(5))
+    ranks = np.stack([rng.permutation(P)[:K] for _ in range(T)]).astype(np.int32)
+    epr = 4
+    ids = (ranks * epr + rng.integers(0, epr, size=(T, K))).astype(np.int32)
+    x = wl.payload_bytes(90, 0, T * row)
+    packed, row_token, cnt, slot_row = oracle.moe_pack_dedup(x, ids, row, P * epr, epr)
+    pk, order, c = oracle.moe_pack(x, ranks, row, P)
+    assert np.array_equal(packed, pk) and np.array_equal(cnt, c)
+    assert np.array_equal(row_token, order // K)
+    inv = np.empty(T * K, dtype=np.int64)
+    inv[order] = np.arange(T * K)
+    assert np.array_equal(slot_row, inv)
+    # (b) every expert on one rank: each token once, in order - the identity
+    ids = wl.zipf_topk_expert_ids(91, 0, 50, 4, 16)
+    x = wl.payload_bytes(92, 0, 50 * 6)
+    packed, row_token, cnt, slot_row = oracle.moe_pack_dedup(x, ids, 6, 16, 16)
+    assert np.array_equal(packed, x) and cnt.tolist() == [50]
+    assert np.array_equal(slot_row, np.repeat(np.arange(50), 4))
+    # (c) bad arguments
+    for bad in (lambda: oracle.moe_pack_dedup(x, ids, 6, 16, 5),
+                lambda: oracle.moe_pack_dedup(x, np.full((50, 4), 16, np.int32), 6, 16, 4)):
+        try:
+            bad()
+        except oracle.OracleError:
+            continue
+        raise AssertionError("bad argument accepted")
+
+
 def pin_moe_layout_properties():
     rng = np.random.Generator(np.random.PCG64(9))
     for P, epr, row in ((1, 4, 2), (2, 3, 10), (8, 32, 14336)):
@@ -377,6 +445,9 @@ ALL_PINS = [
     pin_moe_pack_is_stable_argsort,
     pin_moe_unpack_handworked,
     pin_moe_unpack_inverts_pack,
+    pin_moe_dedup_handworked,
+    pin_moe_dedup_is_unique_over_rank_token_keys,
+    pin_moe_dedup_special_cases,
     pin_moe_layout_properties,
     pin_moe_rejects_bad_ids,
     pin_pp_message_size,

@@ -33,6 +33,13 @@ MUTANTS = [
     ("moe_no_id_check", "if (ids[p] < 0 || ids[p] >= E) return ORACLE_ERR_ARG;", "if (ids[p] < 0 || ids[p] >= E) continue;", 0),
     ("unpack_runs_forward", "uint8_t *dst = out + (uint64_t)p * row_bytes;\n            for (uint64_t i = 0; i < row_bytes; ++i) dst[i] = row[i];", "uint8_t *dst = out + (uint64_t)j * row_bytes; const uint8_t *rr = packed + (uint64_t)p * row_bytes;\n            for (uint64_t i = 0; i < row_bytes; ++i) dst[i] = rr[i];", 0),
     ("unpack_unstable", "for (int64_t p = 0; p < npairs; ++p) {\n            if (ids[p] != e) continue;", "for (int64_t p = npairs - 1; p >= 0; --p) {\n            if (ids[p] != e) continue;", 0),
+    ("dedup_rank_by_modulo", "if (ids[t * K + k] / experts_per_rank == r) {", "if (ids[t * K + k] % (E / experts_per_rank) == r) {", 0),
+    ("dedup_row_for_every_token", "            if (!hit) continue;\n", "", 0),
+    ("dedup_first_slot_only", "hit = 1;\n                    slot_row[t * K + k] = j;", "if (!hit) slot_row[t * K + k] = j;\n                    hit = 1;", 0),
+    ("dedup_token_major", "row_token[j] = t;\n            ++cnt[r];", "row_token[j] = T - 1 - t;\n            ++cnt[r];", 0),
+    ("dedup_slot_row_off_by_one", "slot_row[t * K + k] = j;", "slot_row[t * K + k] = j + 1;", 0),
+    ("dedup_copies_wrong_row", "const uint8_t *row = x + (uint64_t)t * row_bytes;\n            uint8_t *out = packed + (uint64_t)j * row_bytes;", "const uint8_t *row = x + (uint64_t)j * row_bytes;\n            uint8_t *out = packed + (uint64_t)j * row_bytes;", 0),
+    ("dedup_no_id_check", "if (ids[p] < 0 || ids[p] >= E) return ORACLE_ERR_ARG;\n    int64_t j = 0;\n    for (int r = 0; r < R; ++r) {", "if (ids[p] < 0) return ORACLE_ERR_ARG;\n    int64_t j = 0;\n    for (int r = 0; r < R; ++r) {", 0),
     ("layout_expert_block_shifted", "for (int e = r * experts_per_rank; e < (r + 1) * experts_per_rank; ++e)", "for (int e = r; e < E; e += P)", 0),
     ("layout_recv_not_transposed", "recvcounts[(size_t)r * P + s] = sendcounts[(size_t)s * P + r];", "recvcounts[(size_t)r * P + s] = sendcounts[(size_t)r * P + s];", 0),
     ("layout_sdispl_inclusive", "sdispls[(size_t)s * P + r] = acc;\n            acc += sendcounts[(size_t)s * P + r];", "acc += sendcounts[(size_t)s * P + r];\n            sdispls[(size_t)s * P + r] = acc;", 0),
