@@ -244,6 +244,23 @@ def main():
                 "exchange_GBps": 2.0 * float(lay["sendcounts"].sum()) / (wx / 5) / 1e9,
                 "exchange_ms": wx / 5 * 1e3,
                 "recv_bytes_per_rank": [int(lay["recvcounts"][r].sum()) for r in range(P)]}
+            # the same dispatch with one row per (token, destination rank)
+            counts_r = torch.zeros((P, P), dtype=torch.int64, device="cuda")
+            counts_rh = torch.zeros((P, P), dtype=torch.int64).pin_memory()
+            fr = lambda: v.vccl_moe_pack_per_rank(x, ids, P, T, K, row, E, E // P, packed, counts_r, counts_rh,
+                                                  None, None, st)
+            wr, _ = time_calls(torch, fr, 5, 2)
+            rows_r = int(counts_rh.numpy().sum())
+            lay_r = v.vccl_moe_exchange_layout(counts_rh.numpy().astype(np.uint64), P, P, 1, row)
+            fxr = lambda: v.vccl_alltoallv(packed, lay_r["sendcounts"], lay_r["sdispls"], rcv,
+                                           lay_r["recvcounts"], lay_r["rdispls"], P, v.MODE_CU, st)
+            wxr, _ = time_calls(torch, fxr, 5, 2)
+            out["moe_dispatch_per_rank"] = {
+                "rows": rows_r, "rows_per_slot_form": P * T * K,
+                "pack_GBps": (P * (T * row + T * K * 4) + rows_r * row) / (wr / 5) / 1e9, "pack_ms": wr / 5 * 1e3,
+                "exchange_GBps": 2.0 * float(lay_r["sendcounts"].sum()) / (wxr / 5) / 1e9,
+                "exchange_ms": wxr / 5 * 1e3,
+                "recv_bytes_per_rank": [int(lay_r["recvcounts"][r].sum()) for r in range(P)]}
             del x, ids, packed, rcv
             torch.cuda.empty_cache()
     finally:

@@ -197,6 +197,26 @@ int vccl_moe_pack(const void *const *x, const int32_t *const *expert_ids, int P,
                   int topk, uint64_t row_bytes, int num_experts, void *const *packed,
                   uint64_t *counts_dev, uint64_t *counts_host, uint32_t *bad_ids_dev, void *stream);
 
+/* MoE dispatch pack with one row per (token, destination rank): the reading of the
+ * dispatch phase (Section 6) in which a token whose experts share a rank crosses the
+ * fabric once.  Expert e lives on rank e / experts_per_rank (experts_per_rank divides
+ * num_experts; R = num_experts / experts_per_rank destination ranks).  For every
+ * source rank s the (token, rank) pairs with at least one slot routed to that rank
+ * are ordered by rank, then token, and packed[s] (room for tokens * min(topk, R)
+ * rows) receives the token's row for each.  counts_dev (device uint64 [P][R]) and
+ * the optional pinned counts_host receive the rows per destination rank - with
+ * vccl_moe_exchange_layout(counts, P, R, 1, row_bytes) they describe the exchange
+ * that follows.  slot_row may be NULL; else it is a host array of P device pointers
+ * (entries may be NULL), each to tokens*topk uint32: slot_row[s][t*topk + k] = the
+ * packed row that serves slot k of token t (0xffffffff for an out-of-range id), which
+ * is what the receiving side needs to fan a row out to its experts.  Out-of-range
+ * ids are counted in *bad_ids_dev (may be NULL) and dropped.  Other arguments and
+ * stream semantics as vccl_moe_pack. */
+int vccl_moe_pack_per_rank(const void *const *x, const int32_t *const *expert_ids, int P, int tokens,
+                           int topk, uint64_t row_bytes, int num_experts, int experts_per_rank,
+                           void *const *packed, uint64_t *counts_dev, uint64_t *counts_host,
+                           uint32_t *const *slot_row, uint32_t *bad_ids_dev, void *stream);
+
 /* MoE combine, un-permute step (Section 6: the combine phase mirrors dispatch).  The
  * inverse of vccl_moe_pack for all P ranks: packed[s] holds tokens*topk rows in the
  * packed order defined by expert_ids[s] (for instance the rows that came back

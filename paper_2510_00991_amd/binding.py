@@ -47,6 +47,10 @@ EXPORTS = {
     "vccl_moe_pack": (ctypes.c_int, [_vpp, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                      ctypes.c_uint64, ctypes.c_int, _vpp, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+    "vccl_moe_pack_per_rank": (ctypes.c_int, [_vpp, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_uint64, ctypes.c_int, ctypes.c_int, _vpp,
+                                              ctypes.c_void_p, ctypes.c_void_p, _vpp, ctypes.c_void_p,
+                                              ctypes.c_void_p]),
     "vccl_moe_unpack": (ctypes.c_int, [_vpp, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                        ctypes.c_uint64, ctypes.c_int, _vpp, ctypes.c_void_p]),
     "vccl_moe_exchange_layout": (ctypes.c_int, [_u64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -222,6 +226,21 @@ def vccl_moe_pack(x, expert_ids, P: int, tokens: int, topk: int, row_bytes: int,
                                 num_experts, _ptrs(packed), ctypes.c_void_p(_addr(counts_dev)),
                                 ctypes.c_void_p(_addr(counts_host)),
                                 ctypes.c_void_p(_addr(bad_ids_dev)), _stream(stream)))
+
+
+def vccl_moe_pack_per_rank(x, expert_ids, P: int, tokens: int, topk: int, row_bytes: int, num_experts: int,
+                           experts_per_rank: int, packed, counts_dev, counts_host=None, slot_row=None,
+                           bad_ids_dev=None, stream=None) -> None:
+    """One row per (token, destination rank).  counts_dev: device uint64 [P, R] (int64 storage),
+    R = num_experts // experts_per_rank; slot_row: None or P device tensors of tokens*topk uint32
+    (int32 storage)."""
+    if len(x) != P or len(expert_ids) != P or len(packed) != P or (slot_row is not None and len(slot_row) != P):
+        raise ValueError("per-rank arrays must have P entries")
+    _check(load().vccl_moe_pack_per_rank(_ptrs(x), _ptrs(expert_ids), P, tokens, topk, int(row_bytes),
+                                         num_experts, experts_per_rank, _ptrs(packed),
+                                         ctypes.c_void_p(_addr(counts_dev)), ctypes.c_void_p(_addr(counts_host)),
+                                         _ptrs(slot_row) if slot_row is not None else None,
+                                         ctypes.c_void_p(_addr(bad_ids_dev)), _stream(stream)))
 
 
 def vccl_moe_unpack(packed, expert_ids, P: int, tokens: int, topk: int, row_bytes: int,

@@ -486,9 +486,10 @@ int vccl_sendrecv(void *const *sendbuf, const uint64_t *sendbytes, const int *se
                       mode == VCCL_MODE_CE ? &receivers : nullptr);
 }
 
-int vccl_moe_pack(const void *const *x, const int32_t *const *expert_ids, int P, int tokens, int topk,
-                  uint64_t row_bytes, int num_experts, void *const *packed, uint64_t *counts_dev,
-                  uint64_t *counts_host, uint32_t *bad_ids_dev, void *stream) {
+static int moe_pack_common(const void *const *x, const int32_t *const *expert_ids, int P, int tokens, int topk,
+                           uint64_t row_bytes, int num_experts, int experts_per_rank, void *const *packed,
+                           uint64_t *counts_dev, uint64_t *counts_host, uint32_t *const *slot_row,
+                           uint32_t *bad_ids_dev, void *stream) {
     auto c = ctx_get();
     int rv = check_common(c, P, x, packed);
     if (rv) return rv;
@@ -508,9 +509,27 @@ int vccl_moe_pack(const void *const *x, const int32_t *const *expert_ids, int P,
         if ((reinterpret_cast<uintptr_t>(x[s]) | reinterpret_cast<uintptr_t>(packed[s])) & 15u)
             return fail(VCCL_ERR_ARG, "x / packed of rank %d are not 16-byte aligned", s);
     }
-    return launch_moe_pack(c->moe, x, expert_ids, P, tokens, topk, row_bytes, num_experts, packed,
-                           counts_dev, counts_host, bad_ids_dev, options_of(*c).moe_gather_variant,
-                           (hipStream_t)stream);
+    return launch_moe_pack(c->moe, x, expert_ids, P, tokens, topk, row_bytes, num_experts, experts_per_rank,
+                           packed, counts_dev, counts_host, slot_row, bad_ids_dev,
+                           options_of(*c).moe_gather_variant, (hipStream_t)stream);
+}
+
+int vccl_moe_pack(const void *const *x, const int32_t *const *expert_ids, int P, int tokens, int topk,
+                  uint64_t row_bytes, int num_experts, void *const *packed, uint64_t *counts_dev,
+                  uint64_t *counts_host, uint32_t *bad_ids_dev, void *stream) {
+    return moe_pack_common(x, expert_ids, P, tokens, topk, row_bytes, num_experts, 0, packed, counts_dev,
+                           counts_host, nullptr, bad_ids_dev, stream);
+}
+
+int vccl_moe_pack_per_rank(const void *const *x, const int32_t *const *expert_ids, int P, int tokens, int topk,
+                           uint64_t row_bytes, int num_experts, int experts_per_rank, void *const *packed,
+                           uint64_t *counts_dev, uint64_t *counts_host, uint32_t *const *slot_row,
+                           uint32_t *bad_ids_dev, void *stream) {
+    if (experts_per_rank < 1 || num_experts < 1 || num_experts % experts_per_rank)
+        return fail(VCCL_ERR_ARG, "experts_per_rank = %d does not divide num_experts = %d", experts_per_rank,
+                    num_experts);
+    return moe_pack_common(x, expert_ids, P, tokens, topk, row_bytes, num_experts, experts_per_rank, packed,
+                           counts_dev, counts_host, slot_row, bad_ids_dev, stream);
 }
 
 int vccl_moe_unpack(const void *const *packed, const int32_t *const *expert_ids, int P, int tokens,

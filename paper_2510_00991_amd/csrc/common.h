@@ -148,10 +148,13 @@ struct MoeScratch {
     std::mutex mu;
     void destroy();
 };
+// experts_per_rank == 0: one row per (token, slot), sorted by expert id.  experts_per_rank > 0:
+// one row per (token, destination rank), counts per rank, optional slot-to-row maps.
 int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P,
-                    int tokens, int topk, uint64_t row_bytes, int num_experts,
+                    int tokens, int topk, uint64_t row_bytes, int num_experts, int experts_per_rank,
                     void *const *packed, uint64_t *counts_dev, uint64_t *counts_host,
-                    uint32_t *bad_ids_dev, int gather_variant, hipStream_t stream);
+                    uint32_t *const *slot_row, uint32_t *bad_ids_dev, int gather_variant,
+                    hipStream_t stream);
 
 int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *const *ids, int P,
                       int tokens, int topk, uint64_t row_bytes, int num_experts, void *const *out,

@@ -16,6 +16,10 @@
 //                 its own slot k (16 bytes per lane per access)
 // The combine direction (vccl_moe_unpack) reuses launches 1-3 and replaces the
 // gather by its inverse: row dest(t,k) of the packed buffer goes to row t*K+k.
+// The per-rank form (vccl_moe_pack_per_rank: one row per token and destination
+// rank) puts a key launch in front - rank of the expert for the first slot of a
+// token that routes there, negative for repeats and bad ids - and a slot-to-row
+// launch behind the same four.
 #include "common.h"
 #include "device_util.h"
 
@@ -28,9 +32,14 @@ constexpr int kMaxExperts = 1024;
 
 struct MoePtrs {       // device arrays of P pointers each, in one allocation
     const uint8_t *const *x;
-    const int32_t *const *ids;
+    const int32_t *const *ids;      // sort keys: expert ids, or (per-rank form) rank keys in the scratch
     uint8_t *const *packed;
+    const int32_t *const *ids_in;   // per-rank form: the caller's expert ids
+    uint32_t *const *slot_row;      // per-rank form: the caller's slot-to-row maps (entries may be null)
 };
+constexpr int kPtrArrays = 5;
+constexpr int32_t kDuplicate = -1;   // rank key of a slot whose rank an earlier slot of the token already has
+constexpr int32_t kBadId = -2;       // rank key of a slot whose expert id is out of range
 
 __global__ __launch_bounds__(kMoeThreads) void moe_hist_kernel(MoePtrs ptrs, uint32_t npairs, int E,
                                                                uint32_t nblk, uint32_t *hist,
@@ -52,6 +61,66 @@ __global__ __launch_bounds__(kMoeThreads) void moe_hist_kernel(MoePtrs ptrs, uin
     __syncthreads();
     uint32_t *out = hist + ((size_t)rank * nblk + b) * (size_t)E;
     for (int e = threadIdx.x; e < E; e += kMoeThreads) out[e] = h[e];
+}
+
+// Per-rank form of the dispatch (one row per token and destination rank): the sort
+// key of slot k is the destination rank of its expert if no earlier slot of the
+// token routes to that rank, else kDuplicate; out-of-range ids give kBadId.  The
+// index launches then see R "experts" and drop the negative keys.
+__global__ __launch_bounds__(kMoeThreads) void moe_rank_keys_kernel(MoePtrs ptrs, uint32_t tokens, int K, int E,
+                                                                    int experts_per_rank, int32_t *keys,
+                                                                    uint32_t *bad_ids) {
+    const uint32_t rank = blockIdx.y;
+    const uint32_t t = blockIdx.x * kMoeThreads + threadIdx.x;
+    if (t >= tokens) return;
+    const int32_t *ids = ptrs.ids_in[rank] + (size_t)t * K;
+    int32_t *out = keys + ((size_t)rank * tokens + t) * K;
+    uint32_t bad = 0;
+    for (int k = 0; k < K; ++k) {
+        const int32_t e = ids[k];
+        int32_t key;
+        if (e < 0 || e >= E) {
+            key = kBadId;
+            ++bad;
+        } else {
+            key = e / experts_per_rank;
+            for (int q = 0; q < k; ++q) {
+                const int32_t eq = ids[q];
+                if (eq >= 0 && eq < E && eq / experts_per_rank == key) {
+                    key = kDuplicate;
+                    break;
+                }
+            }
+        }
+        out[k] = key;
+    }
+    if (bad && bad_ids) atomicAdd(bad_ids, bad);
+}
+
+// slot_row[t*K + k] = packed row that serves slot k: its own if the slot carries the
+// rank key, else the row of the earlier slot that carries the key of the same rank;
+// kDropped for out-of-range ids.
+__global__ __launch_bounds__(kMoeThreads) void moe_slot_row_kernel(MoePtrs ptrs, uint32_t tokens, int K,
+                                                                   int experts_per_rank, const uint32_t *dest,
+                                                                   uint32_t npairs) {
+    const uint32_t rank = blockIdx.y;
+    uint32_t *out = ptrs.slot_row[rank];
+    const uint32_t t = blockIdx.x * kMoeThreads + threadIdx.x;
+    if (!out || t >= tokens) return;
+    const int32_t *keys = ptrs.ids[rank] + (size_t)t * K;
+    const int32_t *ids = ptrs.ids_in[rank] + (size_t)t * K;
+    const uint32_t *d = dest + (size_t)rank * npairs + (size_t)t * K;
+    for (int k = 0; k < K; ++k) {
+        uint32_t row = kDropped;
+        if (keys[k] >= 0) {
+            row = d[k];
+        } else if (keys[k] == kDuplicate) {
+            const int32_t r = ids[k] / experts_per_rank;
+            for (int q = 0; q < k; ++q)
+                if (keys[q] == r) row = d[q];
+        }
+        out[(size_t)t * K + k] = row;
+    }
 }
 
 // Inclusive scan across the 64 lanes of a wavefront.
@@ -291,15 +360,21 @@ void MoeScratch::destroy() {
 
 // Launches 1-3: per-pair destination rows in the scratch.  `a` / `b` are the two
 // row buffers of every rank in the roles (read side, written side) of launch 4.
+// experts_per_rank > 0 selects the per-rank form: the sort keys are computed into
+// the scratch from the caller's ids and `num_experts` counts ranks from there on.
 static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *const *ids, int P,
-                           int tokens, int topk, int num_experts, void *const *b, uint64_t *counts_dev,
+                           int tokens, int topk, int num_experts, int experts_per_rank,
+                           uint32_t *const *slot_row, void *const *b, uint64_t *counts_dev,
                            uint32_t *bad_ids_dev, hipStream_t stream, MoePtrs *ptrs_out,
                            uint32_t **dest_out) {
+    const bool per_rank = experts_per_rank > 0;
+    const int nkeys = per_rank ? num_experts / experts_per_rank : num_experts;   // sort-key range
     const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
     const uint32_t nblk = npairs ? (npairs + kPairsPerBlock - 1) / kPairsPerBlock : 1;
-    const size_t hist_n = (size_t)P * nblk * (size_t)num_experts;
-    const size_t counts_words = 2 * (size_t)P * num_experts;            // private uint64 counts
-    const size_t need = hist_n + (size_t)P * npairs + counts_words + 2;  // histograms, rows, counts
+    const size_t hist_n = (size_t)P * nblk * (size_t)nkeys;
+    const size_t counts_words = 2 * (size_t)P * nkeys;                  // private uint64 counts
+    const size_t keys_words = per_rank ? (size_t)P * npairs : 0;
+    const size_t need = hist_n + (size_t)P * npairs + keys_words + counts_words + 2;
     if (!sc.done) VCCL_HIP(hipEventCreateWithFlags(&sc.done, hipEventDisableTiming));
     // The scratch is shared: a new call starts after the previous one has finished
     // with it on the device, and the pinned pointer staging is free again.
@@ -311,43 +386,57 @@ static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *
         VCCL_HIP(hipMalloc((void **)&sc.hist, need * sizeof(uint32_t)));
         sc.hist_n = need;
     }
-    if ((size_t)3 * P > sc.ptrs_n) {
+    if ((size_t)kPtrArrays * P > sc.ptrs_n) {
         if (sc.ptrs) VCCL_HIP(hipFree(sc.ptrs));
         if (sc.ptrs_host) VCCL_HIP(hipHostFree(sc.ptrs_host));
         sc.ptrs = nullptr;
         sc.ptrs_host = nullptr;
         sc.ptrs_n = 0;
-        VCCL_HIP(hipMalloc((void **)&sc.ptrs, (size_t)3 * P * sizeof(void *)));
-        VCCL_HIP(hipHostMalloc((void **)&sc.ptrs_host, (size_t)3 * P * sizeof(void *), hipHostMallocDefault));
-        sc.ptrs_n = (size_t)3 * P;
+        VCCL_HIP(hipMalloc((void **)&sc.ptrs, (size_t)kPtrArrays * P * sizeof(void *)));
+        VCCL_HIP(hipHostMalloc((void **)&sc.ptrs_host, (size_t)kPtrArrays * P * sizeof(void *), hipHostMallocDefault));
+        sc.ptrs_n = (size_t)kPtrArrays * P;
     }
+    uint32_t *hist = sc.hist;
+    uint32_t *dest = sc.hist + hist_n;
+    int32_t *keys = reinterpret_cast<int32_t *>(dest + (size_t)P * npairs);
     for (int s = 0; s < P; ++s) {
         sc.ptrs_host[s] = const_cast<void *>(a[s]);
-        sc.ptrs_host[P + s] = const_cast<int32_t *>(ids[s]);
+        sc.ptrs_host[P + s] = per_rank ? static_cast<void *>(keys + (size_t)s * npairs)
+                                       : static_cast<void *>(const_cast<int32_t *>(ids[s]));
         sc.ptrs_host[2 * P + s] = b[s];
+        sc.ptrs_host[3 * P + s] = const_cast<int32_t *>(ids[s]);
+        sc.ptrs_host[4 * P + s] = slot_row ? slot_row[s] : nullptr;
     }
-    VCCL_HIP(hipMemcpyAsync(sc.ptrs, sc.ptrs_host, (size_t)3 * P * sizeof(void *),
+    VCCL_HIP(hipMemcpyAsync(sc.ptrs, sc.ptrs_host, (size_t)kPtrArrays * P * sizeof(void *),
                             hipMemcpyHostToDevice, stream));
     MoePtrs ptrs;
     ptrs.x = reinterpret_cast<const uint8_t *const *>(sc.ptrs);
     ptrs.ids = reinterpret_cast<const int32_t *const *>(sc.ptrs + P);
     ptrs.packed = reinterpret_cast<uint8_t *const *>(sc.ptrs + 2 * P);
-    uint32_t *hist = sc.hist;
-    uint32_t *dest = sc.hist + hist_n;
+    ptrs.ids_in = reinterpret_cast<const int32_t *const *>(sc.ptrs + 3 * P);
+    ptrs.slot_row = reinterpret_cast<uint32_t *const *>(sc.ptrs + 4 * P);
     if (!counts_dev) {   // the caller does not want the counts: keep them in the scratch (8-byte aligned)
-        uintptr_t p = reinterpret_cast<uintptr_t>(dest + (size_t)P * npairs);
+        uintptr_t p = reinterpret_cast<uintptr_t>(keys + keys_words);
         counts_dev = reinterpret_cast<uint64_t *>((p + 7u) & ~(uintptr_t)7u);
     }
     int ebits = 0;
-    while ((1 << ebits) < num_experts) ++ebits;
-    moe_hist_kernel<<<dim3(nblk, P), dim3(kMoeThreads), 0, stream>>>(ptrs, npairs, num_experts, nblk,
-                                                                    hist, bad_ids_dev);
+    while ((1 << ebits) < nkeys) ++ebits;
+    if (per_rank && tokens) {
+        // out-of-range ids are counted here; the histogram then sees them as negative keys
+        moe_rank_keys_kernel<<<dim3(((uint32_t)tokens + kMoeThreads - 1) / kMoeThreads, P), dim3(kMoeThreads), 0,
+                               stream>>>(ptrs, (uint32_t)tokens, topk, num_experts, experts_per_rank, keys,
+                                         bad_ids_dev);
+        VCCL_HIP(hipGetLastError());
+        bad_ids_dev = nullptr;
+    }
+    moe_hist_kernel<<<dim3(nblk, P), dim3(kMoeThreads), 0, stream>>>(ptrs, npairs, nkeys, nblk, hist,
+                                                                    bad_ids_dev);
     VCCL_HIP(hipGetLastError());
-    moe_scan_kernel<<<dim3(P), dim3(kMoeThreads), 0, stream>>>(num_experts, nblk, hist, counts_dev);
+    moe_scan_kernel<<<dim3(P), dim3(kMoeThreads), 0, stream>>>(nkeys, nblk, hist, counts_dev);
     VCCL_HIP(hipGetLastError());
     if (npairs) {
-        moe_rank_kernel<<<dim3(nblk, P), dim3(kMoeThreads), 0, stream>>>(ptrs, npairs, num_experts,
-                                                                        ebits, nblk, hist, dest);
+        moe_rank_kernel<<<dim3(nblk, P), dim3(kMoeThreads), 0, stream>>>(ptrs, npairs, nkeys, ebits, nblk,
+                                                                        hist, dest);
         VCCL_HIP(hipGetLastError());
     }
     *ptrs_out = ptrs;
@@ -356,15 +445,16 @@ static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *
 }
 
 int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P, int tokens,
-                    int topk, uint64_t row_bytes, int num_experts, void *const *packed,
-                    uint64_t *counts_dev, uint64_t *counts_host, uint32_t *bad_ids_dev,
-                    int gather_variant, hipStream_t stream) {
+                    int topk, uint64_t row_bytes, int num_experts, int experts_per_rank,
+                    void *const *packed, uint64_t *counts_dev, uint64_t *counts_host,
+                    uint32_t *const *slot_row, uint32_t *bad_ids_dev, int gather_variant,
+                    hipStream_t stream) {
     const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
     std::lock_guard<std::mutex> lk(sc.mu);
     MoePtrs ptrs;
     uint32_t *dest = nullptr;
-    int rc = moe_index_phase(sc, x, ids, P, tokens, topk, num_experts, packed, counts_dev, bad_ids_dev,
-                             stream, &ptrs, &dest);
+    int rc = moe_index_phase(sc, x, ids, P, tokens, topk, num_experts, experts_per_rank, slot_row, packed,
+                             counts_dev, bad_ids_dev, stream, &ptrs, &dest);
     if (rc) return rc;
     if (npairs) {
         const uint32_t tok_blocks = ((uint32_t)tokens + kMoeThreads / 64 - 1) / (kMoeThreads / 64);
@@ -385,9 +475,15 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
             default: moe_gather_kernel<8, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
         }
         VCCL_HIP(hipGetLastError());
+        if (experts_per_rank > 0 && slot_row) {
+            moe_slot_row_kernel<<<dim3(((uint32_t)tokens + kMoeThreads - 1) / kMoeThreads, P), dim3(kMoeThreads),
+                                  0, stream>>>(ptrs, (uint32_t)tokens, topk, experts_per_rank, dest, npairs);
+            VCCL_HIP(hipGetLastError());
+        }
     }
+    const int ncounts = experts_per_rank > 0 ? num_experts / experts_per_rank : num_experts;
     if (counts_host)
-        VCCL_HIP(hipMemcpyAsync(counts_host, counts_dev, (size_t)P * num_experts * sizeof(uint64_t),
+        VCCL_HIP(hipMemcpyAsync(counts_host, counts_dev, (size_t)P * ncounts * sizeof(uint64_t),
                                 hipMemcpyDeviceToHost, stream));
     VCCL_HIP(hipEventRecord(sc.done, stream));
     return VCCL_OK;
@@ -400,8 +496,8 @@ int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *
     std::lock_guard<std::mutex> lk(sc.mu);
     MoePtrs ptrs;
     uint32_t *dest = nullptr;
-    int rc = moe_index_phase(sc, packed, ids, P, tokens, topk, num_experts, out, nullptr, nullptr, stream,
-                             &ptrs, &dest);
+    int rc = moe_index_phase(sc, packed, ids, P, tokens, topk, num_experts, 0, nullptr, out, nullptr, nullptr,
+                             stream, &ptrs, &dest);
     if (rc) return rc;
     if (npairs) {
         const uint32_t rv = (uint32_t)(row_bytes >> 4);

@@ -196,6 +196,111 @@ def test_kernel_variants_roundtrip(vccl, gather, unpack, shape):
         vccl.vccl_set_option("moe_unpack_variant", saved[1])
 
 
+def _dispatch_per_rank(torch, v, P, T, K, E, row, seed, mode, ids_np=None):
+    """Pack with one row per (token, destination rank), then the exchange the counts
+    describe; packed rows, counts, slot maps and received bytes against the oracle."""
+    epr = E // P
+    x_np = [wl.payload_bytes(seed, s, T * row) for s in range(P)]
+    if ids_np is None:
+        ids_np = [wl.zipf_topk_expert_ids(seed, s, T, K, E) for s in range(P)]
+    x = [to_dev(torch, a) for a in x_np]
+    ids = [torch.from_numpy(a.reshape(-1).copy()).cuda() for a in ids_np]
+    cap = T * min(K, P)
+    packed = [torch.full((max(1, cap * row),), SENTINEL, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    slot_row = [torch.full((max(1, T * K),), 0x5A5A5A5A, dtype=torch.int32, device="cuda") for _ in range(P)]
+    counts_dev = torch.zeros((P, P), dtype=torch.int64, device="cuda")
+    counts_host = torch.zeros((P, P), dtype=torch.int64).pin_memory()
+    bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    st = stream_handle(torch)
+    v.vccl_moe_pack_per_rank(x, ids, P, T, K, row, E, epr, packed, counts_dev, counts_host, slot_row, bad, st)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0
+    cnt_got = counts_host.numpy().astype(np.uint64)
+    assert np.array_equal(cnt_got, counts_dev.cpu().numpy().astype(np.uint64))
+    want_packed, cnts = [], []
+    for s in range(P):
+        pk, row_token, cnt, srow = oracle.moe_pack_dedup(x_np[s], ids_np[s], row, E, epr)
+        assert np.array_equal(cnt_got[s], cnt), f"counts of rank {s}"
+        got = to_host(packed[s])
+        assert_same(got[:pk.size], pk, f"packed[{s}]")
+        assert (got[pk.size:] == SENTINEL).all(), "rows beyond the packed ones must stay untouched"
+        assert np.array_equal(to_host(slot_row[s])[:T * K].view(np.uint32).astype(np.int64), srow), f"slot_row[{s}]"
+        want_packed.append(pk)
+        cnts.append(cnt)
+    lay = v.vccl_moe_exchange_layout(cnt_got, P, P, 1, row)
+    want_lay = oracle.moe_exchange_layout(np.stack(cnts), 1, row)
+    for k in want_lay:
+        assert np.array_equal(lay[k], want_lay[k]), k
+    rsz = [int(lay["recvcounts"][r].sum()) for r in range(P)]
+    recv = [torch.full((rsz[r] + 16,), SENTINEL, dtype=torch.uint8, device="cuda") for r in range(P)]
+    v.vccl_alltoallv(packed, lay["sendcounts"], lay["sdispls"], recv, lay["recvcounts"], lay["rdispls"],
+                     P, mode, st)
+    torch.cuda.synchronize()
+    recv_np = [np.full(rsz[r] + 16, SENTINEL, dtype=np.uint8) for r in range(P)]
+    oracle.alltoallv(want_packed, want_lay["sendcounts"], want_lay["sdispls"], recv_np,
+                     want_lay["recvcounts"], want_lay["rdispls"], threads=8)
+    for r in range(P):
+        assert_same(to_host(recv[r]), recv_np[r], f"recv[{r}]")
+    return [int(c.sum()) for c in cnts]
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1, 16), (2, 5, 2, 4, 32), (2, 300, 8, 256, 48),
+                                   (4, 1000, 4, 64, 14336), (8, 2049, 8, 256, 272), (3, 700, 3, 999, 16),
+                                   (2, 333, 11, 22, 2064)])
+def test_pack_per_rank_and_exchange(vccl, shape):
+    torch = require_gpu()
+    P, T, K, E, row = shape
+    E = max(P, (E // P) * P)
+    rows = _dispatch_per_rank(torch, vccl, P, T, K, E, row, 500 + P + T, vccl.MODE_CU)
+    assert all(n <= T * min(K, P) for n in rows)
+
+
+def test_pack_per_rank_degenerate(vccl):
+    torch = require_gpu()
+    _dispatch_per_rank(torch, vccl, 2, 0, 2, 4, 16, 1, vccl.MODE_CU)          # no tokens
+    # every slot of every token on rank 1: each token crosses once, in token order
+    P, T, K, E, row = 2, 600, 4, 8, 64
+    ids = [np.tile(np.array([4, 5, 6, 7], np.int32), (T, 1)) for _ in range(P)]
+    rows = _dispatch_per_rank(torch, vccl, P, T, K, E, row, 2, vccl.MODE_CU, ids_np=ids)
+    assert rows == [T, T]
+    # copy-engine exchange behind the same pack
+    _dispatch_per_rank(torch, vccl, 4, 512, 8, 64, 1024, 77, vccl.MODE_CE)
+
+
+def test_pack_per_rank_bad_ids_and_arguments(vccl):
+    torch = require_gpu()
+    T, K, E, epr, row = 64, 3, 8, 2, 32
+    ids_np = wl.zipf_topk_expert_ids(5, 0, T, K, E).copy()
+    ids_np[3, 1] = 9
+    ids_np[10, 0] = -2
+    x_np = wl.payload_bytes(6, 0, T * row)
+    x = to_dev(torch, x_np)
+    ids = torch.from_numpy(ids_np.reshape(-1).copy()).cuda()
+    packed = torch.full((T * K * row,), SENTINEL, dtype=torch.uint8, device="cuda")
+    slot_row = torch.zeros(T * K, dtype=torch.int32, device="cuda")
+    counts = torch.zeros((1, E // epr), dtype=torch.int64, device="cuda")
+    bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    vccl.vccl_moe_pack_per_rank([x], [ids], 1, T, K, row, E, epr, [packed], counts, None, [slot_row], bad,
+                                stream_handle(torch))
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 2
+    # what remains is what the oracle packs when the two bad slots repeat a valid slot of their token
+    fixed = ids_np.copy()
+    fixed[3, 1] = fixed[3, 0]
+    fixed[10, 0] = fixed[10, 1]
+    pk, _, cnt, srow = oracle.moe_pack_dedup(x_np, fixed, row, E, epr)
+    assert_same(to_host(packed)[:pk.size], pk, "packed with dropped slots")
+    assert np.array_equal(counts.cpu().numpy().reshape(-1).astype(np.uint64), cnt)
+    got = to_host(slot_row).view(np.uint32).astype(np.int64)
+    srow = srow.copy()
+    srow[3 * K + 1] = 0xFFFFFFFF
+    srow[10 * K + 0] = 0xFFFFFFFF
+    assert np.array_equal(got, srow)
+    with pytest.raises(vccl.VcclError):
+        vccl.vccl_moe_pack_per_rank([x], [ids], 1, T, K, row, E, 3, [packed], counts, None, None, bad,
+                                    stream_handle(torch))
+
+
 def test_unpack_leaves_rows_of_dropped_pairs_untouched(vccl):
     torch = require_gpu()
     T, K, E, row = 40, 2, 4, 32
@@ -227,3 +332,14 @@ def test_config3_moe_dispatch_full_size(vccl):
     rsz = _dispatch(torch, vccl, P, T, K, E, row, seed, vccl.MODE_CU, x_np=x_np, ids_np=ids_np)
     assert sum(rsz) == P * T * K * row
     assert rsz[0] == max(rsz), "rank 0 hosts the hot experts"
+
+
+def test_config3_moe_dispatch_per_rank_full_size(vccl):
+    """The config-3 shapes with one row per (token, destination rank): with top-8 of 256
+    Zipf(1.2) ids over 8 ranks most tokens reach fewer than 8 ranks, rank 0 stays the hot one."""
+    torch = require_gpu()
+    P, T, K, E, H = 8, 8192, 8, 256, 7168
+    seed = wl.config_seed(3)
+    ids_np = [wl.zipf_topk_expert_ids(seed, s, T, K, E) for s in range(P)]
+    rows = _dispatch_per_rank(torch, vccl, P, T, K, E, H * 2, seed, vccl.MODE_CU, ids_np=ids_np)
+    assert all(T <= n < T * K for n in rows)
