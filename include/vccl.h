@@ -144,7 +144,10 @@ int vccl_p2p_reginfo(int receiver_rank, uint64_t *receiver_ready, uint64_t *copy
 
 /* AlltoAll with equal blocks (MoE token routing, Section 2.1): block r
  * (bytes_per_peer bytes at offset r*bytes_per_peer) of sendbuf[s] becomes block s
- * of recvbuf[r].  Every buffer holds at least P*bytes_per_peer bytes. */
+ * of recvbuf[r].  Every buffer holds at least P*bytes_per_peer bytes.
+ * In VCCL_MODE_CU with 16-byte aligned buffers and block size (or at most 64
+ * segments otherwise) the call is one kernel launch with no allocation, copy or
+ * wait around it, so it may be recorded into a HIP graph on a capturing stream. */
 int vccl_alltoall(void *const *sendbuf, void *const *recvbuf, uint64_t bytes_per_peer,
                   int P, vccl_mode mode, void *stream);
 
