@@ -9,7 +9,7 @@ binding's functions raises.
 from .binding import (  # noqa: F401
     MODE_CU, MODE_CE, MODE_CU_STAGED,
     VcclError,
-    lib_path, load,
+    lib_path, load, pointer_array,
     vccl_init, vccl_finalize, vccl_last_error, vccl_set_option, vccl_get_option,
     vccl_sendrecv, vccl_sendrecv_staged_status, vccl_p2p_reginfo,
     vccl_alltoall, vccl_alltoallv, vccl_plan_alltoallv,

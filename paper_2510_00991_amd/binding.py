@@ -111,10 +111,19 @@ def _addr(b) -> int:
 
 
 def _ptrs(bufs: Sequence):
+    if isinstance(bufs, ctypes.Array):   # already marshalled by pointer_array()
+        return bufs
     arr = (ctypes.c_void_p * len(bufs))()
     for i, b in enumerate(bufs):
         arr[i] = _addr(b)
     return arr
+
+
+def pointer_array(bufs: Sequence):
+    """The host array of device pointers a call takes, built once: pass it in place of
+    the list of tensors when the same buffers are used call after call (marshalling
+    P tensors costs more than a small exchange)."""
+    return _ptrs(bufs)
 
 
 def _u64(a, shape=None) -> np.ndarray:

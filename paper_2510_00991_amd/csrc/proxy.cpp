@@ -24,9 +24,14 @@
 // serialised, which is the deadlock the paper describes.
 //
 // For SendRecv each connection also walks the receiver-owned handshake record of
-// Section 3.2 (receiverRegAddr / receiverReady -> copyStarted -> copyDone).  The
-// paper's 1-bit flags are kept here as monotonically increasing sequence numbers,
-// which need no reset between operations.
+// Section 3.2 (receiverRegAddr / receiverReady -> copyStarted -> copyDone), with
+// the two roles on two threads as in the paper: a receiver proxy publishes the
+// application buffer and raises ready once the previous transfer on the connection
+// has started; the sender proxy (the thread that drives the copy engines) issues
+// the copies of a transfer only when its connection shows ready, reads the
+// destination from the record, and marks started / done.  The paper's 1-bit flags
+// are kept here as monotonically increasing sequence numbers, which need no reset
+// between operations; the calling thread only draws the numbers and never waits.
 #include <hsa/hsa.h>
 #include <hsa/hsa_ext_amd.h>
 
@@ -51,6 +56,13 @@ struct RegInfo {  // one per receiving rank
     std::atomic<uint64_t> receiverReady{0};
     std::atomic<uint64_t> copyStarted{0};
     std::atomic<uint64_t> copyDone{0};
+    uint64_t drawn = 0;   // last sequence number handed to a transfer (guarded by handshake_mu)
+};
+
+struct RecvPost {   // what the receiver proxy publishes for one transfer on one connection
+    int rank;
+    uint64_t seq;
+    void *addr;
 };
 
 struct Op {
@@ -83,10 +95,12 @@ public:
     int device = 0;
     int max_streams = kMaxStreams;
     hipStream_t streams[kMaxStreams] = {};
-    std::thread th;
-    std::mutex mu, handshake_mu;
-    std::condition_variable cv_work, cv_issued, cv_idle;
+    std::thread th, receiver_th;
+    std::mutex mu, handshake_mu, recv_mu;
+    std::condition_variable cv_work, cv_issued, cv_idle, cv_recv;
     std::deque<Op *> queue;
+    std::deque<RecvPost> recv_queue;   // in the order the numbers were drawn (guarded by recv_mu)
+    bool recv_stop = false;
     std::vector<Op *> waiting;   // sdma ops whose ready word has not arrived (proxy thread only)
     std::vector<Op *> pending;   // issued, completion not yet observed   (proxy thread only)
     std::vector<Op *> free_ops;
@@ -112,6 +126,8 @@ public:
     }
 
     void run();
+    void run_receiver();
+    bool receivers_ready(const Op *op) const;
     void issue_events(Op *op);
     bool issue_sdma(Op *op);
     void poll();
@@ -269,6 +285,13 @@ std::vector<CeCopy> Proxy::expand(const Op *op, size_t lanes) {
 
 // ------------------------------------------------------- event back end ------
 void Proxy::issue_events(Op *op) {
+    // Operations are issued in the order they were queued, so every earlier transfer
+    // on these connections has started and the receiver proxy is free to publish.
+    // (An earlier SDMA operation may still wait for its stream: keep it moving.)
+    while (!receivers_ready(op)) {
+        poll();
+        std::this_thread::yield();
+    }
     const auto t0 = std::chrono::steady_clock::now();
     int ns = op->want_streams < 1 ? 1 : (op->want_streams > max_streams ? max_streams : op->want_streams);
     std::vector<CeCopy> work = expand(op, (size_t)ns);
@@ -322,6 +345,9 @@ bool Proxy::issue_sdma(Op *op) {
     } else if (__atomic_load_n(op->ready_word, __ATOMIC_ACQUIRE) < op->seq) {
         return false;
     }
+    // A connection carries its transfers in the order their numbers were drawn: this
+    // one goes when the receiver proxy has published its buffer.
+    if (!receivers_ready(op)) return false;
     const auto t0 = std::chrono::steady_clock::now();
     const int ne = op->max_engines > 0 && op->max_engines < nengines ? op->max_engines : nengines;
     std::vector<CeCopy> work = expand(op, (size_t)ne);
@@ -348,6 +374,32 @@ bool Proxy::issue_sdma(Op *op) {
     (void)vccl_monitor_post(monitor[op->primitive], op->monitor_id, bytes, now_ns());
     pending.push_back(op);
     return true;
+}
+
+bool Proxy::receivers_ready(const Op *op) const {
+    for (auto &c : op->conns)
+        if (reg[c.first].receiverReady.load(std::memory_order_acquire) != c.second) return false;
+    return true;
+}
+
+// Receiver proxy: for each posted transfer, in order, wait until the previous
+// transfer on the connection has started (the sender has taken its address out of
+// the record), then publish the application buffer and raise ready.
+void Proxy::run_receiver() {
+    for (;;) {
+        RecvPost post;
+        {
+            std::unique_lock<std::mutex> lk(recv_mu);
+            cv_recv.wait(lk, [&] { return recv_stop || !recv_queue.empty(); });
+            if (recv_queue.empty()) return;   // stop, and nothing left to publish
+            post = recv_queue.front();
+            recv_queue.pop_front();
+        }
+        RegInfo &ri = reg[post.rank];
+        while (ri.copyStarted.load(std::memory_order_acquire) != post.seq - 1) std::this_thread::yield();
+        ri.receiverRegAddr.store(post.addr, std::memory_order_relaxed);
+        ri.receiverReady.store(post.seq, std::memory_order_release);
+    }
 }
 
 void Proxy::finish(Op *op) {
@@ -446,6 +498,7 @@ Proxy *proxy_create(int device, int max_streams) {
     p->monitor[0] = vccl_monitor_create(8, 10000000ull);   // window 8, 10 ms: the paper's values
     p->monitor[1] = vccl_monitor_create(8, 10000000ull);
     p->th = std::thread([p] { p->run(); });
+    p->receiver_th = std::thread([p] { p->run_receiver(); });
     return p;
 }
 
@@ -471,6 +524,12 @@ void proxy_destroy(Proxy *p) {
     }
     p->cv_work.notify_all();
     if (p->th.joinable()) p->th.join();
+    {
+        std::lock_guard<std::mutex> lk(p->recv_mu);
+        p->recv_stop = true;
+    }
+    p->cv_recv.notify_all();
+    if (p->receiver_th.joinable()) p->receiver_th.join();
     for (int i = 0; i < p->max_streams; ++i) {
         (void)hipStreamSynchronize(p->streams[i]);
         (void)hipStreamDestroy(p->streams[i]);
@@ -557,21 +616,20 @@ int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hip
     return rv;
 }
 
-// Receiver side of the handshake: once the previous transfer on the connection has
-// started, publish the application buffer and raise ready.  Called with
-// handshake_mu held, which stays held until the op is queued so that records and
-// queue agree.
+// Calling thread's part of the handshake: draw the next sequence number of every
+// connection of the operation and hand the buffers to the receiver proxy.  Called
+// with handshake_mu held, which stays held until the op is queued, so that the
+// numbers, the receiver proxy's queue and the sender proxy's queue agree in order.
 static void publish_receivers(Proxy *p, Op *op, const std::vector<std::pair<int, void *>> &receivers) {
-    for (auto &rc : receivers) {
-        RegInfo &ri = p->reg[rc.first];
-        while (ri.copyStarted.load(std::memory_order_acquire) !=
-               ri.receiverReady.load(std::memory_order_relaxed))
-            std::this_thread::yield();
-        ri.receiverRegAddr.store(rc.second, std::memory_order_relaxed);
-        const uint64_t s = ri.receiverReady.load(std::memory_order_relaxed) + 1;
-        ri.receiverReady.store(s, std::memory_order_release);
-        op->conns.emplace_back(rc.first, s);
+    {
+        std::lock_guard<std::mutex> lk(p->recv_mu);
+        for (auto &rc : receivers) {
+            const uint64_t s = ++p->reg[rc.first].drawn;
+            op->conns.emplace_back(rc.first, s);
+            p->recv_queue.push_back(RecvPost{rc.first, s, rc.second});
+        }
     }
+    p->cv_recv.notify_one();
 }
 
 // SDMA back end without stream memory operations: the calling thread itself waits

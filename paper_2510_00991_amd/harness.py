@@ -182,10 +182,11 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
         for s in range(P):     # seeded payload, first 1 MiB of each buffer (timing does not depend on values)
             n = min(P * c, 1 << 20)
             send[s][:n].copy_(torch.from_numpy(wl.payload_bytes(wl.config_seed(5), s, n)))
+        send_p, recv_p = v.pointer_array(send), v.pointer_array(recv)   # marshalled once, not per call
         moved = 2.0 * P * P * c
         row = {"bytes_per_peer": c, "total_sent_MiB": P * P * c / (1 << 20)}
         for name, mode in (("cu", v.MODE_CU), ("ce", v.MODE_CE)):
-            fn = lambda s=st, m=mode: v.vccl_alltoall(send, recv, c, P, m, s)
+            fn = lambda s=st, m=mode: v.vccl_alltoall(send_p, recv_p, c, P, m, s)
             k = 10 if name == "cu" else 3
             # keep the device busy for ~50 ms first: the memory clocks of an idle
             # device ramp up slowly under copy-engine traffic alone
@@ -197,7 +198,7 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
             t = wall / k
             row[name] = {"us": t * 1e6, "GBps": moved / t / 1e9}
             if co is not None:
-                row[name].update(co.beside(lambda s, m=mode: v.vccl_alltoall(send, recv, c, P, m, s),
+                row[name].update(co.beside(lambda s, m=mode: v.vccl_alltoall(send_p, recv_p, c, P, m, s),
                                            moved, t, reps=6))
         rows.append(row)
         del send, recv

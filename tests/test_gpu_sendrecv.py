@@ -137,6 +137,58 @@ def test_ce_handshake_record_advances(vccl):
     assert st["ops"] >= 3 and st["bytes"] >= 3 * P * n
 
 
+@pytest.mark.parametrize("kind,sync", [("sdma", "memops"), ("hip_default", "memops")])
+def test_ce_connection_keeps_order_with_many_transfers_outstanding(vccl, kind, sync):
+    """Several copy-engine SendRecv calls on the same connections are handed over
+    without any wait in between (the calling thread only draws sequence numbers), the
+    first of them on a stream that is held back by a long kernel and the rest on a
+    second, idle stream.  Every transfer arrives whole in its own receive buffers, a
+    connection hands its transfers to the copy engines in the order they were posted
+    (a transfer whose stream is ready early waits for its turn), and each record
+    has advanced by the number of transfers."""
+    torch = require_gpu()
+    import time
+    P, n, calls = 4, 1 << 20, 6
+    to, frm = wl.ring_peers(P)
+    sends = [[to_dev(torch, wl.payload_bytes(300 + i, s, n)) for s in range(P)] for i in range(calls)]
+    recvs = [[to_dev(torch, np.full(n, SENTINEL, np.uint8)) for _ in range(P)] for _ in range(calls)]
+    before = [vccl.vccl_p2p_reginfo(r) for r in range(P)]
+    held, idle = torch.cuda.Stream(), torch.cuda.Stream()
+    sink = torch.zeros(256 * 256, dtype=torch.float32, device="cuda")
+    saved = (vccl.vccl_get_option("ce_kind"), vccl.vccl_get_option("ce_sync"))
+    vccl.vccl_set_option("ce_kind", kind)
+    vccl.vccl_set_option("ce_sync", sync)
+    try:
+        torch.cuda.synchronize()
+        vccl.vccl_fma_probe(sink, 256, 256, 20000, int(held.cuda_stream))       # a few ms of compute
+        t0 = time.perf_counter()
+        vccl.vccl_sendrecv(sends[0], [n] * P, to, recvs[0], [n] * P, frm, P, vccl.MODE_CE, int(held.cuda_stream))
+        for i in range(1, calls):
+            vccl.vccl_sendrecv(sends[i], [n] * P, to, recvs[i], [n] * P, frm, P, vccl.MODE_CE,
+                               int(idle.cuda_stream))
+        issue_s = time.perf_counter() - t0
+        torch.cuda.synchronize()
+    finally:
+        vccl.vccl_set_option("ce_kind", saved[0])
+        vccl.vccl_set_option("ce_sync", saved[1])
+    for i in range(calls):
+        want = [np.zeros(n, np.uint8) for _ in range(P)]
+        oracle.sendrecv([to_host(t) for t in sends[i]], [n] * P, to, want, [n] * P, frm)
+        for r in range(P):
+            assert_same(to_host(recvs[i][r]), want[r], f"transfer {i}, recv[{r}]")
+    deadline = time.time() + 5
+    while time.time() < deadline:
+        now = [vccl.vccl_p2p_reginfo(r) for r in range(P)]
+        if all(now[r][2] == before[r][2] + calls for r in range(P)):
+            break
+        time.sleep(0.001)
+    for r in range(P):
+        assert now[r][0] == now[r][1] == now[r][2] == before[r][0] + calls
+    if kind == "sdma":
+        # nothing in the sdma hand-over waits for the device: all calls return while the kernel still runs
+        assert issue_s < 2e-3, f"handing over {calls} transfers took {issue_s * 1e3:.2f} ms"
+
+
 def test_proxy_window_monitor_sees_copy_engine_operations(vccl):
     """The proxy feeds one window monitor per primitive with the operations it
     issues: message counts advance and the window estimate is a sane copy rate."""
