@@ -261,6 +261,16 @@ def main():
                 "exchange_GBps": 2.0 * float(lay_r["sendcounts"].sum()) / (wxr / 5) / 1e9,
                 "exchange_ms": wxr / 5 * 1e3,
                 "recv_bytes_per_rank": [int(lay_r["recvcounts"][r].sum()) for r in range(P)]}
+            # pack and exchange fused: rows written once, straight into the receive buffers
+            cap = np.array([int(lay["recvcounts"][r].sum()) // row for r in range(P)], dtype=np.uint64)
+            layout_d = torch.zeros((4, P, P), dtype=torch.int64, device="cuda")
+            status_d = torch.zeros(2, dtype=torch.int32, device="cuda")
+            ff = lambda: v.vccl_moe_dispatch_fused(x, ids, P, T, K, row, E, E // P, rcv, cap, counts, layout_d,
+                                                   None, status_d, st)
+            wf, _ = time_calls(torch, ff, 5, 2)
+            assert status_d.cpu().tolist() == [0, 0]
+            out["moe_dispatch_fused"] = {"GBps": pack_bytes / (wf / 5) / 1e9, "ms": wf / 5 * 1e3,
+                                         "two_step_ms": (w + wx) / 5 * 1e3}
             del x, ids, packed, rcv
             torch.cuda.empty_cache()
     finally:

@@ -220,6 +220,29 @@ int vccl_moe_pack_per_rank(const void *const *x, const int32_t *const *expert_id
                            void *const *packed, uint64_t *counts_dev, uint64_t *counts_host,
                            uint32_t *const *slot_row, uint32_t *bad_ids_dev, void *stream);
 
+/* Fused MoE dispatch: the pack and the exchange in one pass - the zero-copy idea of
+ * Section 3.2 (item 1: move data between application buffers directly, no staging
+ * buffer) applied to the dispatch phase of Section 6.  Every row goes from x[s]
+ * straight to the place in recv[r] where vccl_moe_pack + vccl_moe_exchange_layout +
+ * vccl_alltoallv would have put it (segments in source-rank order, inside a segment
+ * by expert id, token, slot), so each row is written once and no packed buffer
+ * exists.  num_experts must equal P * experts_per_rank.  recv[r] (device, 16-byte
+ * aligned) has room for recv_capacity_rows[r] rows (host array); rows beyond a
+ * buffer's capacity are not written and status_dev[1] becomes non-zero.
+ * status_dev (device uint32 [2], may be NULL, zeroed by the caller): [0] counts
+ * out-of-range ids (their pairs are dropped), [1] flags an overflow.  counts_dev
+ * (device uint64 [P][num_experts], may be NULL) receives the pairs per expert.
+ * layout_dev (device uint64 [4][P][P], required) receives sendcounts, sdispls,
+ * recvcounts, rdispls in bytes, as the two-step form would use them - rdispls and
+ * recvcounts tell the receiver where each source's rows are; layout_host, if not
+ * NULL, is pinned host memory of the same shape that gets an asynchronous copy.
+ * One call, no host synchronisation inside.  Compute units only. */
+int vccl_moe_dispatch_fused(const void *const *x, const int32_t *const *expert_ids, int P, int tokens,
+                            int topk, uint64_t row_bytes, int num_experts, int experts_per_rank,
+                            void *const *recv, const uint64_t *recv_capacity_rows, uint64_t *counts_dev,
+                            uint64_t *layout_dev, uint64_t *layout_host, uint32_t *status_dev,
+                            void *stream);
+
 /* MoE combine, un-permute step (Section 6: the combine phase mirrors dispatch).  The
  * inverse of vccl_moe_pack for all P ranks: packed[s] holds tokens*topk rows in the
  * packed order defined by expert_ids[s] (for instance the rows that came back

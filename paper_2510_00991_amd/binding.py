@@ -51,6 +51,10 @@ EXPORTS = {
                                               ctypes.c_uint64, ctypes.c_int, ctypes.c_int, _vpp,
                                               ctypes.c_void_p, ctypes.c_void_p, _vpp, ctypes.c_void_p,
                                               ctypes.c_void_p]),
+    "vccl_moe_dispatch_fused": (ctypes.c_int, [_vpp, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_uint64, ctypes.c_int, ctypes.c_int, _vpp, _u64p,
+                                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                               ctypes.c_void_p, ctypes.c_void_p]),
     "vccl_moe_unpack": (ctypes.c_int, [_vpp, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                        ctypes.c_uint64, ctypes.c_int, _vpp, ctypes.c_void_p]),
     "vccl_moe_exchange_layout": (ctypes.c_int, [_u64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -250,6 +254,22 @@ def vccl_moe_pack_per_rank(x, expert_ids, P: int, tokens: int, topk: int, row_by
                                          ctypes.c_void_p(_addr(counts_dev)), ctypes.c_void_p(_addr(counts_host)),
                                          _ptrs(slot_row) if slot_row is not None else None,
                                          ctypes.c_void_p(_addr(bad_ids_dev)), _stream(stream)))
+
+
+def vccl_moe_dispatch_fused(x, expert_ids, P: int, tokens: int, topk: int, row_bytes: int, num_experts: int,
+                            experts_per_rank: int, recv, recv_capacity_rows, counts_dev, layout_dev,
+                            layout_host=None, status_dev=None, stream=None) -> None:
+    """Pack and exchange in one pass.  recv_capacity_rows: P row counts (host); layout_dev /
+    layout_host: uint64 [4, P, P] (int64 storage) device tensor / pinned host tensor;
+    status_dev: device uint32 [2] (int32 storage), zeroed by the caller."""
+    if len(x) != P or len(expert_ids) != P or len(recv) != P:
+        raise ValueError("per-rank arrays must have P entries")
+    cap = _u64(recv_capacity_rows, (P,))
+    _check(load().vccl_moe_dispatch_fused(_ptrs(x), _ptrs(expert_ids), P, tokens, topk, int(row_bytes),
+                                          num_experts, experts_per_rank, _ptrs(recv), _p64(cap),
+                                          ctypes.c_void_p(_addr(counts_dev)), ctypes.c_void_p(_addr(layout_dev)),
+                                          ctypes.c_void_p(_addr(layout_host)), ctypes.c_void_p(_addr(status_dev)),
+                                          _stream(stream)))
 
 
 def vccl_moe_unpack(packed, expert_ids, P: int, tokens: int, topk: int, row_bytes: int,

@@ -156,6 +156,14 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
                     uint32_t *const *slot_row, uint32_t *bad_ids_dev, int gather_variant,
                     hipStream_t stream);
 
+// Pack and exchange in one pass: rows go from x[s] straight into recv[r] where the
+// exchange after a pack would have put them.
+int launch_moe_dispatch_fused(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P,
+                              int tokens, int topk, uint64_t row_bytes, int num_experts,
+                              int experts_per_rank, void *const *recv, const uint64_t *capacity_rows,
+                              uint64_t *counts_dev, uint64_t *layout_dev, uint64_t *layout_host,
+                              uint32_t *status_dev, hipStream_t stream);
+
 int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *const *ids, int P,
                       int tokens, int topk, uint64_t row_bytes, int num_experts, void *const *out,
                       int unpack_variant, hipStream_t stream);

@@ -36,8 +36,9 @@ struct MoePtrs {       // device arrays of P pointers each, in one allocation
     uint8_t *const *packed;
     const int32_t *const *ids_in;   // per-rank form: the caller's expert ids
     uint32_t *const *slot_row;      // per-rank form: the caller's slot-to-row maps (entries may be null)
+    const uint64_t *capacity_rows;  // fused form: rows each destination rank's receive buffer holds
 };
-constexpr int kPtrArrays = 5;
+constexpr int kPtrArrays = 6;
 constexpr int32_t kDuplicate = -1;   // rank key of a slot whose rank an earlier slot of the token already has
 constexpr int32_t kBadId = -2;       // rank key of a slot whose expert id is out of range
 
@@ -290,6 +291,93 @@ __global__ __launch_bounds__(kSlotWaves * 64) void moe_gather_shared_kernel(MoeP
     }
 }
 
+// Fused dispatch, layout step: from the per-expert counts of every source rank
+// derive what the exchange after a pack would use - rows(s -> r), the four byte
+// matrices - and, for the gather, delta[s][r] = first row of segment (s -> r) in
+// recv[r] minus first row of rank r's block in s's packed order.  One workgroup;
+// P*P is small.  status[1] is raised when a destination's rows exceed its capacity.
+__global__ __launch_bounds__(kMoeThreads) void moe_fused_layout_kernel(const uint64_t *counts, int P, int E,
+                                                                       int experts_per_rank, uint64_t row_bytes,
+                                                                       const uint64_t *capacity_rows,
+                                                                       uint64_t *layout, int64_t *delta,
+                                                                       uint32_t *status) {
+    uint64_t *sendcounts = layout, *sdispls = layout + (size_t)P * P;
+    uint64_t *recvcounts = layout + 2 * (size_t)P * P, *rdispls = layout + 3 * (size_t)P * P;
+    const int PP = P * P;
+    for (int i = threadIdx.x; i < PP; i += kMoeThreads) {   // rows(s -> r), kept in sendcounts for now
+        const int s = i / P, r = i - s * P;
+        uint64_t rows = 0;
+        for (int e = r * experts_per_rank; e < (r + 1) * experts_per_rank; ++e) rows += counts[(size_t)s * E + e];
+        sendcounts[i] = rows;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < P; i += kMoeThreads) {    // prefix sums: over r for a sender, over s for a receiver
+        uint64_t acc = 0;
+        for (int r = 0; r < P; ++r) {
+            sdispls[i * P + r] = acc;
+            acc += sendcounts[i * P + r];
+        }
+        acc = 0;
+        for (int s = 0; s < P; ++s) {
+            rdispls[i * P + s] = acc;
+            acc += sendcounts[s * P + i];
+        }
+        if (acc > capacity_rows[i] && status) atomicOr(status + 1, 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < PP; i += kMoeThreads) {
+        const int s = i / P, r = i - s * P;
+        delta[i] = (int64_t)rdispls[r * P + s] - (int64_t)sdispls[i];
+        recvcounts[r * P + s] = sendcounts[i] * row_bytes;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < PP; i += kMoeThreads) {   // rows -> bytes
+        sendcounts[i] *= row_bytes;
+        sdispls[i] *= row_bytes;
+        rdispls[i] *= row_bytes;
+    }
+}
+
+// Fused dispatch, gather step: the shared-piece gather, except that the row of
+// pair (t, k) goes straight into the receive buffer of the rank that hosts its
+// expert, at the place the exchange would have put it.  ptrs.packed holds the
+// receive buffers here.  Rows beyond a buffer's capacity are not written.
+template <bool NT>
+__global__ __launch_bounds__(kSlotWaves * 64) void moe_gather_fused_kernel(MoePtrs ptrs, uint32_t tokens, int K,
+                                                                           uint32_t row_vecs, uint32_t pieces,
+                                                                           uint32_t kgroups, const uint32_t *dest,
+                                                                           uint32_t npairs, int experts_per_rank,
+                                                                           const int64_t *delta, int P) {
+    const uint32_t rank = blockIdx.y;
+    const uint32_t per_token = pieces * kgroups;
+    const uint32_t t = blockIdx.x / per_token;
+    const uint32_t rem = blockIdx.x - t * per_token;
+    const uint32_t piece = rem / kgroups;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t k = (rem - piece * kgroups) * kSlotWaves + wave;
+    if (t >= tokens || k >= (uint32_t)K) return;
+    const uint32_t v0 = piece * kPieceVecs + (threadIdx.x & 63u), v1 = v0 + 64u;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(ptrs.x[rank]) + (size_t)t * row_vecs;
+    u32x4 r0 = {0, 0, 0, 0}, r1 = {0, 0, 0, 0};
+    if (v0 < row_vecs) r0 = row[v0];
+    if (v1 < row_vecs) r1 = row[v1];
+    const size_t p = (size_t)t * K + k;
+    const uint32_t j = dest[(size_t)rank * npairs + p];
+    if (j == kDropped) return;
+    const uint32_t to = (uint32_t)(ptrs.ids[rank][p] / experts_per_rank);   // valid: the pair was not dropped
+    const int64_t at = (int64_t)j + delta[(size_t)rank * P + to];          // row inside recv[to]
+    if ((uint64_t)at >= ptrs.capacity_rows[to]) return;
+    u32x4 *o = reinterpret_cast<u32x4 *>(ptrs.packed[to]) + (size_t)at * row_vecs;
+    if (v0 < row_vecs) {
+        if (NT) __builtin_nontemporal_store(r0, o + v0);
+        else o[v0] = r0;
+    }
+    if (v1 < row_vecs) {
+        if (NT) __builtin_nontemporal_store(r1, o + v1);
+        else o[v1] = r1;
+    }
+}
+
 // Inverse of the gather (combine direction): one workgroup per pair p = t*K + k
 // copies the packed row that pair was sent to back to row p of `out`.  Writes sweep
 // `out` front to back (the tight address window HBM likes), reads hop between
@@ -364,9 +452,10 @@ void MoeScratch::destroy() {
 // the scratch from the caller's ids and `num_experts` counts ranks from there on.
 static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *const *ids, int P,
                            int tokens, int topk, int num_experts, int experts_per_rank,
-                           uint32_t *const *slot_row, void *const *b, uint64_t *counts_dev,
-                           uint32_t *bad_ids_dev, hipStream_t stream, MoePtrs *ptrs_out,
-                           uint32_t **dest_out) {
+                           uint32_t *const *slot_row, void *const *b, const uint64_t *capacity_rows,
+                           size_t extra_words, uint64_t *counts_dev, uint32_t *bad_ids_dev,
+                           hipStream_t stream, MoePtrs *ptrs_out, uint32_t **dest_out,
+                           uint64_t **counts_out = nullptr, uint64_t **extra_out = nullptr) {
     const bool per_rank = experts_per_rank > 0;
     const int nkeys = per_rank ? num_experts / experts_per_rank : num_experts;   // sort-key range
     const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
@@ -374,7 +463,8 @@ static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *
     const size_t hist_n = (size_t)P * nblk * (size_t)nkeys;
     const size_t counts_words = 2 * (size_t)P * nkeys;                  // private uint64 counts
     const size_t keys_words = per_rank ? (size_t)P * npairs : 0;
-    const size_t need = hist_n + (size_t)P * npairs + keys_words + counts_words + 2;
+    // histograms, destination rows, rank keys, counts (8-byte aligned), caller's extra (8-byte aligned)
+    const size_t need = hist_n + (size_t)P * npairs + keys_words + counts_words + 2 + extra_words + 2;
     if (!sc.done) VCCL_HIP(hipEventCreateWithFlags(&sc.done, hipEventDisableTiming));
     // The scratch is shared: a new call starts after the previous one has finished
     // with it on the device, and the pinned pointer staging is free again.
@@ -406,6 +496,7 @@ static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *
         sc.ptrs_host[2 * P + s] = b[s];
         sc.ptrs_host[3 * P + s] = const_cast<int32_t *>(ids[s]);
         sc.ptrs_host[4 * P + s] = slot_row ? slot_row[s] : nullptr;
+        sc.ptrs_host[5 * P + s] = reinterpret_cast<void *>((uintptr_t)(capacity_rows ? capacity_rows[s] : 0));
     }
     VCCL_HIP(hipMemcpyAsync(sc.ptrs, sc.ptrs_host, (size_t)kPtrArrays * P * sizeof(void *),
                             hipMemcpyHostToDevice, stream));
@@ -415,10 +506,13 @@ static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *
     ptrs.packed = reinterpret_cast<uint8_t *const *>(sc.ptrs + 2 * P);
     ptrs.ids_in = reinterpret_cast<const int32_t *const *>(sc.ptrs + 3 * P);
     ptrs.slot_row = reinterpret_cast<uint32_t *const *>(sc.ptrs + 4 * P);
-    if (!counts_dev) {   // the caller does not want the counts: keep them in the scratch (8-byte aligned)
-        uintptr_t p = reinterpret_cast<uintptr_t>(keys + keys_words);
-        counts_dev = reinterpret_cast<uint64_t *>((p + 7u) & ~(uintptr_t)7u);
-    }
+    ptrs.capacity_rows = reinterpret_cast<const uint64_t *>(sc.ptrs + 5 * P);
+    static_assert(sizeof(void *) == sizeof(uint64_t), "capacities travel in pointer-sized slots");
+    uint64_t *counts_scratch =
+        reinterpret_cast<uint64_t *>((reinterpret_cast<uintptr_t>(keys + keys_words) + 7u) & ~(uintptr_t)7u);
+    if (!counts_dev) counts_dev = counts_scratch;   // the caller does not want the counts
+    if (counts_out) *counts_out = counts_dev;
+    if (extra_out) *extra_out = counts_scratch + (size_t)P * nkeys;
     int ebits = 0;
     while ((1 << ebits) < nkeys) ++ebits;
     if (per_rank && tokens) {
@@ -454,7 +548,7 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
     MoePtrs ptrs;
     uint32_t *dest = nullptr;
     int rc = moe_index_phase(sc, x, ids, P, tokens, topk, num_experts, experts_per_rank, slot_row, packed,
-                             counts_dev, bad_ids_dev, stream, &ptrs, &dest);
+                             nullptr, 0, counts_dev, bad_ids_dev, stream, &ptrs, &dest);
     if (rc) return rc;
     if (npairs) {
         const uint32_t tok_blocks = ((uint32_t)tokens + kMoeThreads / 64 - 1) / (kMoeThreads / 64);
@@ -489,6 +583,43 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
     return VCCL_OK;
 }
 
+int launch_moe_dispatch_fused(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P, int tokens,
+                              int topk, uint64_t row_bytes, int num_experts, int experts_per_rank,
+                              void *const *recv, const uint64_t *capacity_rows, uint64_t *counts_dev,
+                              uint64_t *layout_dev, uint64_t *layout_host, uint32_t *status_dev,
+                              hipStream_t stream) {
+    const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
+    const uint32_t rv = (uint32_t)(row_bytes >> 4);
+    const uint32_t pieces = (rv + kPieceVecs - 1) / kPieceVecs;
+    const uint32_t kgroups = ((uint32_t)topk + kSlotWaves - 1) / kSlotWaves;
+    const uint64_t grid = (uint64_t)tokens * pieces * kgroups;
+    if (grid > 0x7fffffffull)
+        return fail(VCCL_ERR_UNSUPPORTED, "tokens x row pieces x slot groups = %llu exceeds the launch grid",
+                    (unsigned long long)grid);
+    std::lock_guard<std::mutex> lk(sc.mu);
+    MoePtrs ptrs;
+    uint32_t *dest = nullptr;
+    uint64_t *counts = nullptr, *extra = nullptr;
+    int rc = moe_index_phase(sc, x, ids, P, tokens, topk, num_experts, 0, nullptr, recv, capacity_rows,
+                             2 * (size_t)P * P, counts_dev, status_dev, stream, &ptrs, &dest, &counts, &extra);
+    if (rc) return rc;
+    int64_t *delta = reinterpret_cast<int64_t *>(extra);
+    moe_fused_layout_kernel<<<dim3(1), dim3(kMoeThreads), 0, stream>>>(counts, P, num_experts, experts_per_rank,
+                                                                      row_bytes, ptrs.capacity_rows, layout_dev,
+                                                                      delta, status_dev);
+    VCCL_HIP(hipGetLastError());
+    if (npairs) {
+        moe_gather_fused_kernel<true><<<dim3((uint32_t)grid, P), dim3(kSlotWaves * 64), 0, stream>>>(
+            ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, dest, npairs, experts_per_rank, delta, P);
+        VCCL_HIP(hipGetLastError());
+    }
+    if (layout_host)
+        VCCL_HIP(hipMemcpyAsync(layout_host, layout_dev, 4 * (size_t)P * P * sizeof(uint64_t),
+                                hipMemcpyDeviceToHost, stream));
+    VCCL_HIP(hipEventRecord(sc.done, stream));
+    return VCCL_OK;
+}
+
 int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *const *ids, int P,
                       int tokens, int topk, uint64_t row_bytes, int num_experts, void *const *out,
                       int unpack_variant, hipStream_t stream) {
@@ -496,8 +627,8 @@ int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *
     std::lock_guard<std::mutex> lk(sc.mu);
     MoePtrs ptrs;
     uint32_t *dest = nullptr;
-    int rc = moe_index_phase(sc, packed, ids, P, tokens, topk, num_experts, 0, nullptr, out, nullptr, nullptr,
-                             stream, &ptrs, &dest);
+    int rc = moe_index_phase(sc, packed, ids, P, tokens, topk, num_experts, 0, nullptr, out, nullptr, 0,
+                             nullptr, nullptr, stream, &ptrs, &dest);
     if (rc) return rc;
     if (npairs) {
         const uint32_t rv = (uint32_t)(row_bytes >> 4);

@@ -301,6 +301,121 @@ def test_pack_per_rank_bad_ids_and_arguments(vccl):
                                     stream_handle(torch))
 
 
+def _oracle_dispatch(P, T, K, E, row, x_np, ids_np):
+    """What pack + layout + AlltoAllv deliver, from the oracle chain."""
+    opk = [oracle.moe_pack(x_np[s], ids_np[s], row, E) for s in range(P)]
+    lay = oracle.moe_exchange_layout(np.stack([o[2] for o in opk]), E // P, row)
+    rsz = [int(lay["recvcounts"][r].sum()) for r in range(P)]
+    recv = [np.zeros(rsz[r], np.uint8) for r in range(P)]
+    oracle.alltoallv([o[0] for o in opk], lay["sendcounts"], lay["sdispls"], recv, lay["recvcounts"],
+                     lay["rdispls"], threads=8)
+    return recv, lay, np.stack([o[2] for o in opk])
+
+
+def _fused(torch, v, P, T, K, E, row, seed, slack_rows=3, x_np=None, ids_np=None):
+    if x_np is None:
+        x_np = [wl.payload_bytes(seed, s, T * row) for s in range(P)]
+    if ids_np is None:
+        ids_np = [wl.zipf_topk_expert_ids(seed, s, T, K, E) for s in range(P)]
+    want, lay, cnts = _oracle_dispatch(P, T, K, E, row, x_np, ids_np)
+    rows = [w.size // row for w in want]
+    cap = np.array([n + slack_rows for n in rows], dtype=np.uint64)
+    x = [to_dev(torch, a) for a in x_np]
+    ids = [torch.from_numpy(a.reshape(-1).copy()).cuda() for a in ids_np]
+    recv = [torch.full((max(16, int(cap[r]) * row),), SENTINEL, dtype=torch.uint8, device="cuda") for r in range(P)]
+    counts = torch.zeros((P, E), dtype=torch.int64, device="cuda")
+    layout = torch.zeros((4, P, P), dtype=torch.int64, device="cuda")
+    layout_h = torch.zeros((4, P, P), dtype=torch.int64).pin_memory()
+    status = torch.zeros(2, dtype=torch.int32, device="cuda")
+    v.vccl_moe_dispatch_fused(x, ids, P, T, K, row, E, E // P, recv, cap, counts, layout, layout_h, status,
+                              stream_handle(torch))
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0]
+    assert np.array_equal(counts.cpu().numpy().astype(np.uint64), cnts)
+    got_lay = layout_h.numpy().astype(np.uint64)
+    assert np.array_equal(got_lay, layout.cpu().numpy().astype(np.uint64))
+    for i, k in enumerate(("sendcounts", "sdispls", "recvcounts", "rdispls")):
+        assert np.array_equal(got_lay[i], lay[k]), k
+    for r in range(P):
+        got = to_host(recv[r])
+        assert_same(got[:want[r].size], want[r], f"recv[{r}]")
+        assert (got[want[r].size:] == SENTINEL).all(), "bytes past the received rows must stay untouched"
+    return rows
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1, 16), (2, 5, 2, 4, 32), (2, 300, 8, 256, 48),
+                                   (4, 1000, 4, 64, 14336), (8, 2049, 8, 256, 272), (3, 700, 3, 999, 16),
+                                   (2, 333, 11, 22, 2064)])
+def test_fused_dispatch_equals_pack_then_exchange(vccl, shape):
+    torch = require_gpu()
+    P, T, K, E, row = shape
+    E = max(P, (E // P) * P)
+    _fused(torch, vccl, P, T, K, E, row, 700 + P + T)
+
+
+def test_fused_dispatch_degenerate_and_exact_capacity(vccl):
+    torch = require_gpu()
+    _fused(torch, vccl, 2, 0, 2, 4, 16, 1)                                   # no tokens
+    _fused(torch, vccl, 4, 500, 4, 16, 64, 2, slack_rows=0)                  # capacity = exactly what arrives
+    P, T, K, E, row = 2, 600, 2, 8, 64                                       # everything to rank 1
+    ids = [np.tile(np.array([5, 6], np.int32), (T, 1)) for _ in range(P)]
+    rows = _fused(torch, vccl, P, T, K, E, row, 3, ids_np=ids)
+    assert rows == [0, P * T * K]
+
+
+def test_fused_dispatch_overflow_and_bad_ids(vccl):
+    """A receive buffer that is too small: the flag is raised, the rows that fit are the
+    right ones and nothing is written past the capacity.  Out-of-range ids are counted."""
+    torch = require_gpu()
+    P, T, K, E, row = 4, 400, 4, 16, 48
+    seed = 11
+    x_np = [wl.payload_bytes(seed, s, T * row) for s in range(P)]
+    ids_np = [wl.zipf_topk_expert_ids(seed, s, T, K, E) for s in range(P)]
+    want, lay, _ = _oracle_dispatch(P, T, K, E, row, x_np, ids_np)
+    rows = [w.size // row for w in want]
+    cap = np.array(rows, dtype=np.uint64)
+    cap[0] = rows[0] // 2                                                   # rank 0 (the hot one) is short
+    x = [to_dev(torch, a) for a in x_np]
+    ids = [torch.from_numpy(a.reshape(-1).copy()).cuda() for a in ids_np]
+    recv = [torch.full((rows[r] * row + 64,), SENTINEL, dtype=torch.uint8, device="cuda") for r in range(P)]
+    layout = torch.zeros((4, P, P), dtype=torch.int64, device="cuda")
+    status = torch.zeros(2, dtype=torch.int32, device="cuda")
+    vccl.vccl_moe_dispatch_fused(x, ids, P, T, K, row, E, E // P, recv, cap, None, layout, None, status,
+                                 stream_handle(torch))
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 1]
+    for r in range(P):
+        got = to_host(recv[r])
+        kept = int(cap[r]) * row
+        assert_same(got[:kept], want[r][:kept], f"recv[{r}] within its capacity")
+        assert (got[kept:] == SENTINEL).all(), f"recv[{r}] beyond its capacity"
+    # out-of-range ids: counted, their pairs dropped; the rest as if those pairs did not exist
+    bad_ids = [a.copy() for a in ids_np]
+    bad_ids[1][7, 2] = E
+    bad_ids[2][0, 0] = -1
+    ids = [torch.from_numpy(a.reshape(-1).copy()).cuda() for a in bad_ids]
+    recv = [torch.full((rows[r] * row + 64,), SENTINEL, dtype=torch.uint8, device="cuda") for r in range(P)]
+    status.zero_()
+    vccl.vccl_moe_dispatch_fused(x, ids, P, T, K, row, E, E // P, recv, np.array(rows, np.uint64), None, layout,
+                                 None, status, stream_handle(torch))
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [2, 0]
+    # reference: drop the two pairs by hand (NumPy), then lay the segments out in source-rank order
+    for r in range(P):
+        parts = []
+        for s in range(P):
+            keys = bad_ids[s].reshape(-1)
+            ok = (keys >= 0) & (keys < E)
+            order = np.argsort(np.where(ok, keys, E), kind="stable")[:ok.sum()]
+            mine = order[(keys[order] // (E // P)) == r]
+            parts.append(x_np[s].reshape(T, row)[mine // K].reshape(-1))
+        ref = np.concatenate(parts) if parts else np.zeros(0, np.uint8)
+        assert_same(to_host(recv[r])[:ref.size], ref, f"recv[{r}] with two pairs dropped")
+    with pytest.raises(vccl.VcclError):
+        vccl.vccl_moe_dispatch_fused(x, ids, P, T, K, row, E + 4, E // P, recv, np.array(rows, np.uint64), None,
+                                     layout, None, status, stream_handle(torch))
+
+
 def test_unpack_leaves_rows_of_dropped_pairs_untouched(vccl):
     torch = require_gpu()
     T, K, E, row = 40, 2, 4, 32
@@ -343,3 +458,15 @@ def test_config3_moe_dispatch_per_rank_full_size(vccl):
     ids_np = [wl.zipf_topk_expert_ids(seed, s, T, K, E) for s in range(P)]
     rows = _dispatch_per_rank(torch, vccl, P, T, K, E, H * 2, seed, vccl.MODE_CU, ids_np=ids_np)
     assert all(T <= n < T * K for n in rows)
+
+
+def test_config3_fused_dispatch_full_size(vccl):
+    """Config-3 shapes through the fused dispatch: received bytes equal the oracle's
+    pack + exchange, rank 0 receives the most."""
+    torch = require_gpu()
+    P, T, K, E, H = 8, 8192, 8, 256, 7168
+    seed = wl.config_seed(3)
+    x_np = [wl.normal_bf16_bits(seed, s, T * H).view(np.uint8) for s in range(P)]
+    ids_np = [wl.zipf_topk_expert_ids(seed, s, T, K, E) for s in range(P)]
+    rows = _fused(torch, vccl, P, T, K, E, H * 2, seed, slack_rows=0, x_np=x_np, ids_np=ids_np)
+    assert sum(rows) == P * T * K and rows[0] == max(rows)
