@@ -271,6 +271,13 @@ def main():
             assert status_d.cpu().tolist() == [0, 0]
             out["moe_dispatch_fused"] = {"GBps": pack_bytes / (wf / 5) / 1e9, "ms": wf / 5 * 1e3,
                                          "two_step_ms": (w + wx) / 5 * 1e3}
+            # the way back fused: inverse exchange + un-permute in one pass
+            outp = [torch.empty(T * K * row, dtype=torch.uint8, device="cuda") for _ in range(P)]
+            fc = lambda: v.vccl_moe_combine_fused(rcv, cap, ids, P, T, K, row, E, E // P, outp, st)
+            wc, _ = time_calls(torch, fc, 5, 2)
+            out["moe_combine_fused"] = {"GBps": 2.0 * P * T * K * row / (wc / 5) / 1e9, "ms": wc / 5 * 1e3,
+                                        "two_step_ms": (wx + wu) / 5 * 1e3}
+            del outp
             del x, ids, packed, rcv
             torch.cuda.empty_cache()
     finally:

@@ -243,6 +243,21 @@ int vccl_moe_dispatch_fused(const void *const *x, const int32_t *const *expert_i
                             uint64_t *layout_dev, uint64_t *layout_host, uint32_t *status_dev,
                             void *stream);
 
+/* Fused MoE combine: the way back in one pass (Section 6: the combine phase mirrors
+ * dispatch; Section 3.2 item 1: no staging buffer).  back[r] holds, for rank r, the
+ * rows it received in the dispatch (in the order vccl_moe_dispatch_fused or pack +
+ * exchange delivered them, typically after the experts changed their contents),
+ * back_capacity_rows[r] rows of room (host array; a pair whose row would lie beyond
+ * it is skipped).  Row t*topk + k of out[s] (tokens*topk rows, 16-byte aligned)
+ * receives the row of pair (t, k) of source rank s - what the inverse vccl_alltoallv
+ * followed by vccl_moe_unpack would produce.  Rows of pairs with out-of-range ids are
+ * left untouched.  The weighted sum over a token's rows is a reduction and not part
+ * of this library. */
+int vccl_moe_combine_fused(const void *const *back, const uint64_t *back_capacity_rows,
+                           const int32_t *const *expert_ids, int P, int tokens, int topk,
+                           uint64_t row_bytes, int num_experts, int experts_per_rank, void *const *out,
+                           void *stream);
+
 /* MoE combine, un-permute step (Section 6: the combine phase mirrors dispatch).  The
  * inverse of vccl_moe_pack for all P ranks: packed[s] holds tokens*topk rows in the
  * packed order defined by expert_ids[s] (for instance the rows that came back

@@ -55,6 +55,9 @@ EXPORTS = {
                                                ctypes.c_uint64, ctypes.c_int, ctypes.c_int, _vpp, _u64p,
                                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                                ctypes.c_void_p, ctypes.c_void_p]),
+    "vccl_moe_combine_fused": (ctypes.c_int, [_vpp, _u64p, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_uint64, ctypes.c_int, ctypes.c_int, _vpp,
+                                              ctypes.c_void_p]),
     "vccl_moe_unpack": (ctypes.c_int, [_vpp, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                        ctypes.c_uint64, ctypes.c_int, _vpp, ctypes.c_void_p]),
     "vccl_moe_exchange_layout": (ctypes.c_int, [_u64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -270,6 +273,17 @@ def vccl_moe_dispatch_fused(x, expert_ids, P: int, tokens: int, topk: int, row_b
                                           ctypes.c_void_p(_addr(counts_dev)), ctypes.c_void_p(_addr(layout_dev)),
                                           ctypes.c_void_p(_addr(layout_host)), ctypes.c_void_p(_addr(status_dev)),
                                           _stream(stream)))
+
+
+def vccl_moe_combine_fused(back, back_capacity_rows, expert_ids, P: int, tokens: int, topk: int,
+                           row_bytes: int, num_experts: int, experts_per_rank: int, out, stream=None) -> None:
+    """Inverse exchange and un-permute in one pass: out[s] row t*topk+k from back[rank of the expert]."""
+    if len(back) != P or len(expert_ids) != P or len(out) != P:
+        raise ValueError("per-rank arrays must have P entries")
+    cap = _u64(back_capacity_rows, (P,))
+    _check(load().vccl_moe_combine_fused(_ptrs(back), _p64(cap), _ptrs(expert_ids), P, tokens, topk,
+                                         int(row_bytes), num_experts, experts_per_rank, _ptrs(out),
+                                         _stream(stream)))
 
 
 def vccl_moe_unpack(packed, expert_ids, P: int, tokens: int, topk: int, row_bytes: int,

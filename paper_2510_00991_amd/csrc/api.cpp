@@ -565,6 +565,35 @@ int vccl_moe_dispatch_fused(const void *const *x, const int32_t *const *expert_i
                                      layout_host, status_dev, (hipStream_t)stream);
 }
 
+int vccl_moe_combine_fused(const void *const *back, const uint64_t *back_capacity_rows,
+                           const int32_t *const *expert_ids, int P, int tokens, int topk, uint64_t row_bytes,
+                           int num_experts, int experts_per_rank, void *const *out, void *stream) {
+    auto c = ctx_get();
+    int rv = check_common(c, P, back, out);
+    if (rv) return rv;
+    if (!expert_ids || !back_capacity_rows) return fail(VCCL_ERR_ARG, "expert_ids or back_capacity_rows is NULL");
+    if (tokens < 0 || topk < 1 || topk > 64)
+        return fail(VCCL_ERR_ARG, "tokens = %d, topk = %d (topk must be 1..64)", tokens, topk);
+    if (num_experts < 1 || num_experts > 1024 || experts_per_rank < 1 || num_experts != P * experts_per_rank)
+        return fail(VCCL_ERR_ARG, "num_experts = %d must be P * experts_per_rank = %d * %d (at most 1024)",
+                    num_experts, P, experts_per_rank);
+    if (row_bytes == 0 || (row_bytes & 15u))
+        return fail(VCCL_ERR_ARG, "row_bytes = %llu must be a positive multiple of 16",
+                    (unsigned long long)row_bytes);
+    if ((uint64_t)tokens * (uint64_t)topk > 0x7fffffffull)
+        return fail(VCCL_ERR_UNSUPPORTED, "more than 2^31 (token, slot) pairs per rank");
+    for (int s = 0; s < P; ++s) {
+        if (tokens && (!expert_ids[s] || !out[s])) return fail(VCCL_ERR_ARG, "NULL buffer for rank %d", s);
+        if (back_capacity_rows[s] && !back[s])
+            return fail(VCCL_ERR_ARG, "NULL buffer with a capacity of %llu rows for rank %d",
+                        (unsigned long long)back_capacity_rows[s], s);
+        if ((reinterpret_cast<uintptr_t>(back[s]) | reinterpret_cast<uintptr_t>(out[s])) & 15u)
+            return fail(VCCL_ERR_ARG, "back / out of rank %d are not 16-byte aligned", s);
+    }
+    return launch_moe_combine_fused(c->moe, back, back_capacity_rows, expert_ids, P, tokens, topk, row_bytes,
+                                    num_experts, experts_per_rank, out, (hipStream_t)stream);
+}
+
 int vccl_moe_unpack(const void *const *packed, const int32_t *const *expert_ids, int P, int tokens,
                     int topk, uint64_t row_bytes, int num_experts, void *const *out, void *stream) {
     auto c = ctx_get();

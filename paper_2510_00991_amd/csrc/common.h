@@ -164,6 +164,11 @@ int launch_moe_dispatch_fused(MoeScratch &sc, const void *const *x, const int32_
                               uint64_t *counts_dev, uint64_t *layout_dev, uint64_t *layout_host,
                               uint32_t *status_dev, hipStream_t stream);
 
+// The way back in one pass: row t*K+k of out[s] is read straight from back[r].
+int launch_moe_combine_fused(MoeScratch &sc, const void *const *back, const uint64_t *capacity_rows,
+                             const int32_t *const *ids, int P, int tokens, int topk, uint64_t row_bytes,
+                             int num_experts, int experts_per_rank, void *const *out, hipStream_t stream);
+
 int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *const *ids, int P,
                       int tokens, int topk, uint64_t row_bytes, int num_experts, void *const *out,
                       int unpack_variant, hipStream_t stream);

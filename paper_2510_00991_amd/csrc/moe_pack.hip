@@ -431,6 +431,30 @@ __global__ __launch_bounds__(64) void moe_scatter_back_tiles_kernel(MoePtrs ptrs
         if (v0 + u * 64u + threadIdx.x < row_vecs) o.store(u * 64u + threadIdx.x, r[u]);
 }
 
+// Fused combine: the inverse exchange and the un-permute in one pass.  Row p = t*K + k
+// of out[s] comes straight from the place in back[r] (r = rank of the pair's expert)
+// where the fused dispatch - or pack + exchange - had put the pair's row.  ptrs.x
+// holds the P buffers `back`, ptrs.packed the P outputs; same tile shape as the
+// un-permute kernel above.
+template <int POL>
+__global__ __launch_bounds__(64) void moe_combine_fused_kernel(MoePtrs ptrs, uint32_t row_vecs,
+                                                               uint32_t tiles_per_row, const uint32_t *dest,
+                                                               uint32_t npairs, int experts_per_rank,
+                                                               const int64_t *delta, int P) {
+    const uint32_t rank = blockIdx.y;
+    const uint32_t p = blockIdx.x / tiles_per_row;
+    const uint32_t v0 = (blockIdx.x - p * tiles_per_row) * 64u;
+    if (p >= npairs) return;
+    const uint32_t j = dest[(size_t)rank * npairs + p];
+    if (j == kDropped) return;
+    const uint32_t from = (uint32_t)(ptrs.ids[rank][p] / experts_per_rank);
+    const int64_t at = (int64_t)j + delta[(size_t)rank * P + from];
+    if ((uint64_t)at >= ptrs.capacity_rows[from]) return;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(ptrs.x[from]) + (size_t)at * row_vecs + v0;
+    const TileDst<POL> o(reinterpret_cast<u32x4 *>(ptrs.packed[rank]) + (size_t)p * row_vecs + v0);
+    if (v0 + threadIdx.x < row_vecs) o.store(threadIdx.x, ld16<POL>(row + threadIdx.x));
+}
+
 void MoeScratch::destroy() {
     if (done) {
         (void)hipEventSynchronize(done);
@@ -616,6 +640,38 @@ int launch_moe_dispatch_fused(MoeScratch &sc, const void *const *x, const int32_
     if (layout_host)
         VCCL_HIP(hipMemcpyAsync(layout_host, layout_dev, 4 * (size_t)P * P * sizeof(uint64_t),
                                 hipMemcpyDeviceToHost, stream));
+    VCCL_HIP(hipEventRecord(sc.done, stream));
+    return VCCL_OK;
+}
+
+int launch_moe_combine_fused(MoeScratch &sc, const void *const *back, const uint64_t *capacity_rows,
+                             const int32_t *const *ids, int P, int tokens, int topk, uint64_t row_bytes,
+                             int num_experts, int experts_per_rank, void *const *out, hipStream_t stream) {
+    const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
+    const uint32_t rv = (uint32_t)(row_bytes >> 4);
+    const uint32_t tiles_per_row = (rv + 63u) / 64u;
+    const uint64_t grid = (uint64_t)npairs * tiles_per_row;
+    if (grid > 0x7fffffffull)
+        return fail(VCCL_ERR_UNSUPPORTED, "pairs x row tiles = %llu exceeds the launch grid", (unsigned long long)grid);
+    std::lock_guard<std::mutex> lk(sc.mu);
+    MoePtrs ptrs;
+    uint32_t *dest = nullptr;
+    uint64_t *counts = nullptr, *extra = nullptr;
+    // room after the counts: delta [P][P] (int64), then the four layout matrices, which nobody reads here
+    int rc = moe_index_phase(sc, back, ids, P, tokens, topk, num_experts, 0, nullptr, out, capacity_rows,
+                             2 * (size_t)P * P * 5, nullptr, nullptr, stream, &ptrs, &dest, &counts, &extra);
+    if (rc) return rc;
+    int64_t *delta = reinterpret_cast<int64_t *>(extra);
+    uint64_t *layout = extra + (size_t)P * P;
+    moe_fused_layout_kernel<<<dim3(1), dim3(kMoeThreads), 0, stream>>>(counts, P, num_experts, experts_per_rank,
+                                                                      row_bytes, ptrs.capacity_rows, layout, delta,
+                                                                      nullptr);
+    VCCL_HIP(hipGetLastError());
+    if (npairs && rv) {
+        moe_combine_fused_kernel<2><<<dim3((uint32_t)grid, P), dim3(64), 0, stream>>>(
+            ptrs, rv, tiles_per_row, dest, npairs, experts_per_rank, delta, P);
+        VCCL_HIP(hipGetLastError());
+    }
     VCCL_HIP(hipEventRecord(sc.done, stream));
     return VCCL_OK;
 }

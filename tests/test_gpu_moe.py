@@ -416,6 +416,77 @@ def test_fused_dispatch_overflow_and_bad_ids(vccl):
                                      layout, None, status, stream_handle(torch))
 
 
+def _fused_roundtrip(torch, v, P, T, K, E, row, seed):
+    """Fused dispatch, a change on the receiving side, fused combine; against the oracle's
+    pack -> AlltoAllv -> change -> inverse AlltoAllv -> un-permute."""
+    x_np = [wl.payload_bytes(seed, s, T * row) for s in range(P)]
+    ids_np = [wl.zipf_topk_expert_ids(seed, s, T, K, E) for s in range(P)]
+    want_recv, lay, _ = _oracle_dispatch(P, T, K, E, row, x_np, ids_np)
+    rows = np.array([w.size // row for w in want_recv], dtype=np.uint64)
+    x = [to_dev(torch, a) for a in x_np]
+    ids = [torch.from_numpy(a.reshape(-1).copy()).cuda() for a in ids_np]
+    recv = [torch.zeros(max(16, int(rows[r]) * row), dtype=torch.uint8, device="cuda") for r in range(P)]
+    layout = torch.zeros((4, P, P), dtype=torch.int64, device="cuda")
+    st = stream_handle(torch)
+    v.vccl_moe_dispatch_fused(x, ids, P, T, K, row, E, E // P, recv, rows, None, layout, None, None, st)
+    for r in range(P):
+        recv[r].bitwise_not_()                       # the experts' work
+    out = [torch.full((T * K * row + 16,), SENTINEL, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    v.vccl_moe_combine_fused(recv, rows, ids, P, T, K, row, E, E // P, out, st)
+    torch.cuda.synchronize()
+    # oracle: the way back through the inverse exchange and the un-permute
+    changed = [np.bitwise_not(w) for w in want_recv]
+    back = [np.zeros(T * K * row, np.uint8) for _ in range(P)]
+    oracle.alltoallv(changed, lay["recvcounts"], lay["rdispls"], back, lay["sendcounts"], lay["sdispls"])
+    for s in range(P):
+        want = oracle.moe_unpack(back[s], ids_np[s], row, E)
+        got = to_host(out[s])
+        assert_same(got[:T * K * row], want, f"combined rows of rank {s}")
+        assert (got[T * K * row:] == SENTINEL).all()
+        assert np.array_equal(want.reshape(T * K, row),
+                              np.repeat(np.bitwise_not(x_np[s]).reshape(T, row), K, axis=0))
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1, 16), (2, 77, 2, 6, 48), (4, 1000, 4, 64, 14336),
+                                   (8, 2049, 8, 256, 272), (2, 333, 11, 22, 2064)])
+def test_fused_dispatch_and_combine_roundtrip(vccl, shape):
+    torch = require_gpu()
+    P, T, K, E, row = shape
+    E = max(P, (E // P) * P)
+    _fused_roundtrip(torch, vccl, P, T, K, E, row, 1300 + T)
+
+
+def test_fused_combine_skips_dropped_pairs(vccl):
+    torch = require_gpu()
+    P, T, K, E, row = 2, 40, 2, 4, 32
+    ids_np = [wl.zipf_topk_expert_ids(5, s, T, K, E).copy() for s in range(P)]
+    ids_np[0][7, 0] = 99
+    back_np = [wl.payload_bytes(8, r, P * T * K * row) for r in range(P)]
+    back = [to_dev(torch, a) for a in back_np]
+    ids = [torch.from_numpy(a.reshape(-1).copy()).cuda() for a in ids_np]
+    out = [torch.full((T * K * row,), SENTINEL, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    cap = np.full(P, P * T * K, dtype=np.uint64)
+    vccl.vccl_moe_combine_fused(back, cap, ids, P, T, K, row, E, E // P, out, stream_handle(torch))
+    torch.cuda.synchronize()
+    # reference in NumPy: where each kept pair's row sits in back[r] (segments in source order,
+    # inside a segment by expert id, token, slot)
+    epr = E // P
+    orders, ranks = [], []
+    for s in range(P):
+        keys = ids_np[s].reshape(-1)
+        ok = (keys >= 0) & (keys < E)
+        order = np.argsort(np.where(ok, keys, E), kind="stable")[:ok.sum()]
+        orders.append(order)
+        ranks.append(keys[order] // epr)
+    for s in range(P):
+        want = np.full((T * K, row), SENTINEL, np.uint8)
+        for r in range(P):
+            first = sum(int((ranks[q] == r).sum()) for q in range(s))      # rows of earlier sources in back[r]
+            mine = orders[s][ranks[s] == r]
+            want[mine] = back_np[r].reshape(-1, row)[first:first + mine.size]
+        assert_same(to_host(out[s]), want.reshape(-1), f"out[{s}] with a dropped pair")
+
+
 def test_unpack_leaves_rows_of_dropped_pairs_untouched(vccl):
     torch = require_gpu()
     T, K, E, row = 40, 2, 4, 32
