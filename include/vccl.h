@@ -103,7 +103,9 @@ const char *vccl_last_error(void);
  *       "check" (0/1 overlap validation),
  *       "moe_gather_variant" (row gather of vccl_moe_pack: 208 / 308 = one workgroup of 8
  *       wavefronts per 2 KiB piece of a token's row, one wavefront per slot, non-temporal /
- *       plain stores; 4, 8, 16 = one wavefront per token holding that many vectors per lane,
+ *       plain stores (the per-rank pack uses 408 / 508 in their place); 408 / 508 = one
+ *       wavefront per 2 KiB piece looping over the slots, non-temporal / plain stores;
+ *       4, 8, 16 = one wavefront per token holding that many vectors per lane,
  *       non-temporal stores; 108, 116 = the same with plain stores),
  *       "moe_unpack_variant" (row un-permute of vccl_moe_unpack: 0 = one workgroup per row,
  *       1 / 2 = one wavefront per 1 KiB tile with non-temporal / device-scope stores,

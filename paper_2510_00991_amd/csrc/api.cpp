@@ -339,8 +339,8 @@ int vccl_set_option(const char *key, const char *value) {
         if (!in(1, 8)) return fail(VCCL_ERR_ARG, "ce_streams must be 1..8");
         o.ce_streams = (int)x;
     } else if (k == "moe_gather_variant") {
-        if (!(x == 4 || x == 8 || x == 16 || x == 108 || x == 116 || x == 208 || x == 308))
-            return fail(VCCL_ERR_ARG, "moe_gather_variant must be 4, 8, 16, 108, 116, 208 or 308");
+        if (!(x == 4 || x == 8 || x == 16 || x == 108 || x == 116 || x == 208 || x == 308 || x == 408 || x == 508))
+            return fail(VCCL_ERR_ARG, "moe_gather_variant must be 4, 8, 16, 108, 116, 208, 308, 408 or 508");
         o.moe_gather_variant = (int)x;
     } else if (k == "moe_unpack_variant") {
         if (!in(0, 3)) return fail(VCCL_ERR_ARG, "moe_unpack_variant must be 0..3");

@@ -291,6 +291,41 @@ __global__ __launch_bounds__(kSlotWaves * 64) void moe_gather_shared_kernel(MoeP
     }
 }
 
+// Gather, piece-loop form: one single-wavefront workgroup per 2 KiB piece of a
+// token's row loads the piece once and stores it for every slot that is not
+// dropped.  This is the better shape when most slots are dropped, as in the
+// per-rank form of the dispatch (a token reaches about 3 of 8 ranks on the
+// measured routing): no wavefront is launched only to find its slot empty.
+template <bool NT>
+__global__ __launch_bounds__(64) void moe_gather_piece_loop_kernel(MoePtrs ptrs, uint32_t tokens, int K,
+                                                                   uint32_t row_vecs, uint32_t pieces,
+                                                                   const uint32_t *dest, uint32_t npairs) {
+    const uint32_t rank = blockIdx.y;
+    const uint32_t t = blockIdx.x / pieces;
+    const uint32_t piece = blockIdx.x - t * pieces;
+    if (t >= tokens) return;
+    const uint32_t v0 = piece * kPieceVecs + threadIdx.x, v1 = v0 + 64u;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(ptrs.x[rank]) + (size_t)t * row_vecs;
+    u32x4 *out = reinterpret_cast<u32x4 *>(ptrs.packed[rank]);
+    u32x4 r0 = {0, 0, 0, 0}, r1 = {0, 0, 0, 0};
+    if (v0 < row_vecs) r0 = __builtin_nontemporal_load(row + v0);   // read once
+    if (v1 < row_vecs) r1 = __builtin_nontemporal_load(row + v1);
+    const uint32_t *d = dest + (size_t)rank * npairs + (size_t)t * K;
+    for (int k = 0; k < K; ++k) {
+        const uint32_t j = d[k];
+        if (j == kDropped) continue;
+        u32x4 *o = out + (size_t)j * row_vecs;
+        if (v0 < row_vecs) {
+            if (NT) __builtin_nontemporal_store(r0, o + v0);
+            else o[v0] = r0;
+        }
+        if (v1 < row_vecs) {
+            if (NT) __builtin_nontemporal_store(r1, o + v1);
+            else o[v1] = r1;
+        }
+    }
+}
+
 // Fused dispatch, layout step: from the per-expert counts of every source rank
 // derive what the exchange after a pack would use - rows(s -> r), the four byte
 // matrices - and, for the gather, delta[s][r] = first row of segment (s -> r) in
@@ -582,8 +617,15 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
         const uint32_t kgroups = ((uint32_t)topk + kSlotWaves - 1) / kSlotWaves;
         const uint64_t shared_grid = (uint64_t)tokens * pieces * kgroups;
         if ((gather_variant == 208 || gather_variant == 308) && shared_grid > 0x7fffffffull) gather_variant = 116;
+        // per-rank form: most slots are dropped, the piece-loop kernel wastes no wavefront on them
+        if (experts_per_rank > 0 && (gather_variant == 208 || gather_variant == 308)) gather_variant += 200;
+        const uint64_t loop_grid = (uint64_t)tokens * pieces;
+        if ((gather_variant == 408 || gather_variant == 508) && loop_grid > 0x7fffffffull) gather_variant = 116;
+        const dim3 gl((uint32_t)loop_grid, P), bl(64);
         const dim3 gs((uint32_t)shared_grid, P), bs(kSlotWaves * 64);
         switch (gather_variant) {
+            case 408: moe_gather_piece_loop_kernel<true><<<gl, bl, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, dest, npairs); break;
+            case 508: moe_gather_piece_loop_kernel<false><<<gl, bl, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, dest, npairs); break;
             case 208: moe_gather_shared_kernel<true><<<gs, bs, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, dest, npairs); break;
             case 308: moe_gather_shared_kernel<false><<<gs, bs, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, dest, npairs); break;
             case 4: moe_gather_kernel<4, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;

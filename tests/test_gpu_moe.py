@@ -177,7 +177,7 @@ def test_combine_roundtrip_copy_engine(vccl):
     _combine(torch, vccl, 4, 600, 8, 64, 2048, 901, vccl.MODE_CE)
 
 
-@pytest.mark.parametrize("gather,unpack", [(116, 0), (208, 1), (308, 2), (8, 3)])
+@pytest.mark.parametrize("gather,unpack", [(116, 0), (208, 1), (308, 2), (8, 3), (408, 2), (508, 2)])
 @pytest.mark.parametrize("shape", [(2, 333, 11, 22, 2064), (3, 257, 8, 9, 4096 + 16), (2, 100, 17, 18, 16)])
 def test_kernel_variants_roundtrip(vccl, gather, unpack, shape):
     """Every gather / un-permute kernel form on shapes with more than 8 slots per token
