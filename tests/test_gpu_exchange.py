@@ -170,6 +170,48 @@ def test_config5_p64_1mib_sampled_destinations(vccl):
         torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("k", range(11))
+def test_config5_p64_every_sweep_size(vccl, k):
+    """P = 64 at every size of the sweep, 4 KiB ... 4 MiB per peer (up to 16 GiB sent), both
+    data paths.  The payload is produced on the device (seeded), too large to build on the
+    host at the upper sizes; the whole result is checked on the device against the exchange
+    law block by block (recv[r] block s == send[s] block r, nothing else touched), and one
+    destination rank per size is brought to the host and checked against the oracle."""
+    torch = require_gpu()
+    P, c = 64, 4096 << k
+    g = torch.Generator(device="cuda")
+    g.manual_seed(wl.config_seed(5) + k)
+    send = [torch.randint(0, 256, (P * c,), dtype=torch.uint8, device="cuda", generator=g) for _ in range(P)]
+    r_chk = (7 * k + 3) % P
+    send_blocks = [to_host(send[s][r_chk * c:(r_chk + 1) * c]) for s in range(P)]   # everything bound for r_chk
+    want = np.full(P * c + 16, SENTINEL, dtype=np.uint8)
+    cnt = np.zeros((P, P), dtype=np.uint64)
+    cnt[:, r_chk] = c
+    z = np.zeros((P, P), dtype=np.uint64)
+    rd = np.zeros((P, P), dtype=np.uint64)
+    rd[r_chk, :] = np.arange(P, dtype=np.uint64) * np.uint64(c)
+    dummy = [np.zeros(16, np.uint8) for _ in range(P)]
+    dummy[r_chk] = want
+    oracle.alltoallv(send_blocks, cnt, z, dummy, cnt.T.copy(), rd, threads=4)
+    for mode in ("cu", "ce"):
+        recv = [torch.full((P * c + 16,), SENTINEL, dtype=torch.uint8, device="cuda") for _ in range(P)]
+        vccl.vccl_alltoall(send, recv, c, P, _mode(vccl, mode), stream_handle(torch))
+        torch.cuda.synchronize()
+        for r in range(P):
+            got = recv[r][:P * c].view(P, c)
+            ref = torch.stack([send[s][r * c:(r + 1) * c] for s in range(P)]) if c <= (1 << 16) else None
+            if ref is not None:
+                assert torch.equal(got, ref), f"{mode} recv[{r}]"
+            else:
+                for s in range(P):
+                    assert torch.equal(got[s], send[s][r * c:(r + 1) * c]), f"{mode} recv[{r}] block {s}"
+            assert bool((recv[r][P * c:] == SENTINEL).all()), f"{mode} recv[{r}] tail"
+        assert_same(to_host(recv[r_chk]), want, f"{mode} recv[{r_chk}] against the oracle")
+        del recv
+    del send
+    torch.cuda.empty_cache()
+
+
 def _with_options(v, opts, fn):
     saved = {k: v.vccl_get_option(k) for k in opts}
     for k, val in opts.items():
