@@ -73,6 +73,8 @@ def headline(torch, v, a2a_cu, args, algo_bytes, P, c, send, recv):
                                "bf16 payload as random 16-bit patterns, compute-unit copy path",
                    "P": P, "bytes_per_peer": c, "mode": "cu",
                    "cu_unroll": int(v.vccl_get_option("cu_unroll")),
+                   "cu_threads": int(v.vccl_get_option("cu_threads")),
+                   "cu_nontemporal": int(v.vccl_get_option("cu_nontemporal")),
                    "cu_wg_per_cu": int(v.vccl_get_option("cu_wg_per_cu"))},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(),
