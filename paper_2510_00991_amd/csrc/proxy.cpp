@@ -223,6 +223,20 @@ void Proxy::setup_sdma() {
     sdma_ok = true;
 }
 
+// Signal words (device memory the caller's stream waits on) are never given back to
+// the allocator: memory of that kind that a stream operation has read is kept until
+// the process ends, and a context created later takes the words over together with
+// the last sequence number each one holds.
+namespace {
+struct SignalWord {
+    uint64_t *word;
+    uint64_t seq;
+    int device;
+};
+std::mutex g_signal_mu;
+std::vector<SignalWord> g_signal_pool;
+}  // namespace
+
 Op *Proxy::get_op() {  // mu held
     if (!free_ops.empty()) {
         Op *op = free_ops.back();
@@ -236,8 +250,21 @@ Op *Proxy::get_op() {  // mu held
     if (ok && sdma_ok) {
         ok = hipHostMalloc((void **)&op->ready_word, 64, hipHostMallocDefault) == hipSuccess;
         if (ok) *op->ready_word = 0;
-        ok = ok && hipExtMallocWithFlags((void **)&op->done_word, 8, hipMallocSignalMemory) == hipSuccess;
-        if (ok) __atomic_store_n(op->done_word, (uint64_t)0, __ATOMIC_RELEASE);
+        if (ok) {
+            std::lock_guard<std::mutex> lk(g_signal_mu);
+            for (size_t i = 0; i < g_signal_pool.size(); ++i) {
+                if (g_signal_pool[i].device != device) continue;
+                op->done_word = g_signal_pool[i].word;
+                op->seq = g_signal_pool[i].seq;   // the word holds this value: later numbers are fresh
+                g_signal_pool[i] = g_signal_pool.back();
+                g_signal_pool.pop_back();
+                break;
+            }
+        }
+        if (ok && !op->done_word) {
+            ok = hipExtMallocWithFlags((void **)&op->done_word, 8, hipMallocSignalMemory) == hipSuccess;
+            if (ok) __atomic_store_n(op->done_word, (uint64_t)0, __ATOMIC_RELEASE);
+        }
         ok = ok && hsa_signal_create(0, 0, nullptr, &op->left) == HSA_STATUS_SUCCESS;
     }
     if (!ok) {   // events and words of a half-built op are few and leak only on this error path
@@ -539,7 +566,10 @@ void proxy_destroy(Proxy *p) {
         (void)hipEventDestroy(op->ready);
         for (int i = 0; i < kMaxStreams; ++i) (void)hipEventDestroy(op->done[i]);
         if (op->ready_word) (void)hipHostFree((void *)op->ready_word);
-        if (op->done_word) (void)hipFree(op->done_word);
+        if (op->done_word) {
+            std::lock_guard<std::mutex> lk(g_signal_mu);
+            g_signal_pool.push_back(SignalWord{op->done_word, op->seq, p->device});
+        }
         if (op->left.handle) hsa_signal_destroy(op->left);
         delete op;
     }
