@@ -193,6 +193,12 @@ def main():
             wcap, _ = time_calls(torch, a2a_cu, 5, 2)
             cor_cap = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes, wcap / 5)
             cor_cap["GBps_alone"] = algo_bytes / (wcap / 5) / 1e9
+            # and to a quarter of that: 64 workgroups
+            v.vccl_set_option("cu_max_wg", 64)
+            wcap64, _ = time_calls(torch, a2a_cu, 3, 1)
+            cor_cap64 = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes,
+                                  wcap64 / 3)
+            cor_cap64["GBps_alone"] = algo_bytes / (wcap64 / 3) / 1e9
             v.vccl_set_option("cu_max_wg", 0)
             v.vccl_set_option("cu_unroll", 1)
             v.vccl_set_option("cu_threads", 64)
@@ -201,7 +207,7 @@ def main():
             out["corun"] = {"probe": f"FMA kernel, {co.cu} workgroups x {co.threads} threads, "
                                      f"{co.iters} rounds of 64 FMAs per lane",
                             "cu_path": cor_cu, "cu_path_capped_1wg_per_cu": cor_cap,
-                            "copy_engine_path": cor_ce}
+                            "cu_path_capped_64wg": cor_cap64, "copy_engine_path": cor_ce}
         if "sendrecv" in legs:
             # SendRecv ring, 8 stages x 64 MiB
             n = 64 << 20
