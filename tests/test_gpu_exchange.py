@@ -536,3 +536,42 @@ def test_cu_path_replays_from_a_hip_graph(vccl, P, c):
         oracle.alltoall(send_np, want, c, threads=4)
         for r in range(P):
             assert_same(to_host(recv[r]), want[r], f"replay {rep} recv[{r}]")
+
+
+@pytest.mark.parametrize("kind,sync", [("sdma", "memops"), ("sdma", "host"), ("hip_nocu", "memops")])
+def test_kernels_after_a_copy_engine_exchange_read_fresh_data(vccl, kind, sync):
+    """Cache coherence of the copy-engine path: the receive buffers are small enough to
+    stay in the L2 caches, a kernel writes and another reads them right before the
+    exchange (so their old contents are cached), the copy engines then write them
+    behind the caches' back, and a compute kernel on the same stream reads them right
+    after.  It must see the new bytes, iteration after iteration."""
+    torch = require_gpu()
+    P, c = 4, 1 << 16
+    st = torch.cuda.current_stream()
+    send = [torch.zeros(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    recv = [torch.zeros(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    saved = (vccl.vccl_get_option("ce_kind"), vccl.vccl_get_option("ce_sync"))
+    vccl.vccl_set_option("ce_kind", kind)
+    vccl.vccl_set_option("ce_sync", sync)
+    try:
+        for it in range(25):
+            send_np = [wl.payload_bytes(5000 + it, s, P * c) for s in range(P)]
+            for s in range(P):
+                send[s].copy_(torch.from_numpy(send_np[s]), non_blocking=False)
+            touched = []
+            for r in range(P):
+                recv[r].fill_(it & 0xFF)                       # a kernel writes the old contents
+                touched.append(recv[r].to(torch.int32).sum())    # and a kernel reads them
+            vccl.vccl_alltoall(send, recv, c, P, vccl.MODE_CE, int(st.cuda_stream))
+            seen = [recv[r] ^ 0 for r in range(P)]               # compute kernels read right behind the exchange
+            sums = [recv[r].to(torch.int64).sum() for r in range(P)]
+            torch.cuda.synchronize()
+            want = [np.zeros(P * c, dtype=np.uint8) for _ in range(P)]
+            oracle.alltoall(send_np, want, c)
+            for r in range(P):
+                assert int(touched[r].item()) == (it & 0xFF) * P * c
+                assert_same(to_host(seen[r]), want[r], f"iteration {it} recv[{r}] as a kernel saw it")
+                assert int(sums[r].item()) == int(want[r].astype(np.int64).sum())
+    finally:
+        vccl.vccl_set_option("ce_kind", saved[0])
+        vccl.vccl_set_option("ce_sync", saved[1])
