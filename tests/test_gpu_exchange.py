@@ -544,7 +544,9 @@ def test_kernels_after_a_copy_engine_exchange_read_fresh_data(vccl, kind, sync):
     stay in the L2 caches, a kernel writes and another reads them right before the
     exchange (so their old contents are cached), the copy engines then write them
     behind the caches' back, and a compute kernel on the same stream reads them right
-    after.  It must see the new bytes, iteration after iteration."""
+    after.  It must see the new bytes, iteration after iteration.  The bytes to send
+    are themselves produced by a kernel right before the exchange: the engines must
+    read what that kernel wrote, not what memory held before."""
     torch = require_gpu()
     P, c = 4, 1 << 16
     st = torch.cuda.current_stream()
@@ -557,7 +559,9 @@ def test_kernels_after_a_copy_engine_exchange_read_fresh_data(vccl, kind, sync):
         for it in range(25):
             send_np = [wl.payload_bytes(5000 + it, s, P * c) for s in range(P)]
             for s in range(P):
-                send[s].copy_(torch.from_numpy(send_np[s]), non_blocking=False)
+                send[s].copy_(torch.from_numpy(np.bitwise_not(send_np[s])), non_blocking=False)
+            for s in range(P):
+                send[s].bitwise_not_()          # a kernel produces the bytes to send right before the exchange
             touched = []
             for r in range(P):
                 recv[r].fill_(it & 0xFF)                       # a kernel writes the old contents
