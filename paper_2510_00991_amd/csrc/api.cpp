@@ -54,15 +54,31 @@ void DescRing::destroy() {
 int DescRing::acquire(DescSlot **out) {
     DescSlot *s;
     {
-        std::lock_guard<std::mutex> lk(mu);
+        std::unique_lock<std::mutex> lk(mu);
+        cv.wait(lk, [&] { return !slot[next].busy; });
         s = &slot[next];
+        s->busy = true;
         next = (next + 1) % kSlots;
     }
     // A slot is recycled only after the launch that last read it has finished.
-    if (s->used) VCCL_HIP(hipEventSynchronize(s->done));
+    if (s->used) {
+        hipError_t e = hipEventSynchronize(s->done);
+        if (e != hipSuccess) {
+            release(s);
+            return fail(VCCL_ERR_HIP, "hipEventSynchronize(descriptor slot) failed: %s", hipGetErrorString(e));
+        }
+    }
     s->used = true;
     *out = s;
     return VCCL_OK;
+}
+
+void DescRing::release(DescSlot *s) {
+    {
+        std::lock_guard<std::mutex> lk(mu);
+        s->busy = false;
+    }
+    cv.notify_all();
 }
 
 // ------------------------------------------------------------------ context ---
@@ -99,10 +115,6 @@ struct Piece {
     int receiver;
 };
 
-static bool ranges_overlap(const uint8_t *a, uint64_t an, const uint8_t *b, uint64_t bn) {
-    return an && bn && a < b + bn && b < a + an;
-}
-
 // O(n log n) check that no receive piece overlaps another receive piece or any
 // send piece (undefined behaviour for an exchange; rejected when "check" is on).
 static int check_overlap(const std::vector<Piece> &pieces) {
@@ -134,7 +146,6 @@ static int check_overlap(const std::vector<Piece> &pieces) {
             if (!src_end || r.p + r.n > src_end) src_end = r.p + r.n;
         }
     }
-    (void)ranges_overlap;
     return VCCL_OK;
 }
 

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <condition_variable>
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
@@ -74,6 +75,7 @@ struct DescSlot {
     Seg *dev = nullptr;
     hipEvent_t done = nullptr;
     bool used = false;
+    bool busy = false;   // handed to a caller that has not yet recorded `done` (guarded by DescRing::mu)
 };
 
 struct DescRing {
@@ -82,10 +84,14 @@ struct DescRing {
     size_t capacity = 0;   // descriptors per slot
     int next = 0;
     std::mutex mu;
+    std::condition_variable cv;
     int init(size_t cap);
     void destroy();
-    // Blocks until the slot's previous launch has finished on the device.
+    // Hands out the slots in turn.  Blocks while the next slot is still held by another
+    // caller, and until the slot's previous launch has finished on the device.
     int acquire(DescSlot **out);
+    // The caller has recorded `done` behind its launch (or has given up): the slot may go round again.
+    void release(DescSlot *s);
 };
 
 // ---- CU copy path

@@ -133,7 +133,7 @@ __global__ __launch_bounds__(T) void copy_segments_kernel(CopyArgs by_value) {
 
 // Fast path for the common case in which every descriptor starts at 16-byte aligned
 // addresses on both sides and is a whole number of vectors long (all five
-// workload configurations): no head, tail, realignment, LDS or loop - one scalar
+// workload configurations): no head, tail, realignment or loop - one scalar
 // descriptor load, U vector loads, U vector stores.  Needs the full grid.
 template <int U, int NT, bool INLINE, int T>
 __global__ __launch_bounds__(T) void copy_aligned_kernel(CopyArgs by_value) {
@@ -382,6 +382,13 @@ int launch_copy(const CopyPlan &plan, const Options &opt, int cu_count, DescRing
     args.nseg = (uint32_t)plan.segs.size();
     args.pad = 0;
     DescSlot *slot = nullptr;
+    struct SlotGuard {   // gives the staging slot back on every way out
+        DescRing &ring;
+        DescSlot *&slot;
+        ~SlotGuard() {
+            if (slot) ring.release(slot);
+        }
+    } guard{ring, slot};
     const bool inl = plan.segs.size() <= (size_t)kInlineSegs;
     if (inl) {
         for (size_t i = 0; i < plan.segs.size(); ++i) args.inl[i] = plan.segs[i];
