@@ -17,7 +17,9 @@ EXE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "native", "gpu_na
 def test_native_c_program(sync):
     require_gpu()
     if not os.path.exists(EXE):
-        pytest.fail("tests/native/gpu_native is not built: run __graft_entry__.build() first")
+        # normally built by build(); one gcc call on a C file if the tree arrived without it
+        from paper_2510_00991_amd import build as b
+        b.build_native_check(verbose=False)
     rv = subprocess.run([EXE, sync], capture_output=True, text=True, timeout=120)
     assert rv.returncode == 0, rv.stdout[-2000:] + rv.stderr[-2000:]
     assert "native ok" in rv.stdout and f"ordering: {sync}" in rv.stdout
