@@ -110,6 +110,43 @@ def test_staged_equals_oracle_fifo_model(vccl):
             vccl.vccl_set_option("fifo_wg_per_conn", 8)
 
 
+def test_staged_wait_gives_up_when_its_poll_budget_runs_out(vccl):
+    """Failure path of the staged FIFO, forced from the host: with a poll budget of one
+    and a single slow sender workgroup per connection, the receiver's bounded wait runs
+    out long before the first chunk is there.  The kernel still ends by itself, the
+    status call reports the time-out, and the next staged transfer with the normal
+    budget is complete and right."""
+    torch = require_gpu()
+    P, n = 2, 8 << 20
+    to, frm = wl.ring_peers(P)
+    send_np = [wl.payload_bytes(77, s, n) for s in range(P)]
+    send = [to_dev(torch, a) for a in send_np]
+    recv = [to_dev(torch, np.full(n, SENTINEL, np.uint8)) for _ in range(P)]
+    keys = ("fifo_spin_limit", "fifo_chunk_bytes", "fifo_slots", "fifo_wg_per_conn")
+    saved = {k: vccl.vccl_get_option(k) for k in keys}
+    try:
+        for k, val in (("fifo_spin_limit", 1), ("fifo_chunk_bytes", 64 << 20), ("fifo_slots", 1),
+                       ("fifo_wg_per_conn", 1)):
+            vccl.vccl_set_option(k, val)
+        vccl.vccl_sendrecv(send, [n] * P, to, recv, [n] * P, frm, P, vccl.MODE_CU_STAGED, stream_handle(torch))
+        with pytest.raises(vccl.VcclError) as e:
+            vccl.vccl_sendrecv_staged_status()
+        assert e.value.code == -7
+        torch.cuda.synchronize()            # the grid has drained by itself
+    finally:
+        for k, val in saved.items():
+            vccl.vccl_set_option(k, val)
+    for r in range(P):
+        recv[r].fill_(SENTINEL)
+    vccl.vccl_sendrecv(send, [n] * P, to, recv, [n] * P, frm, P, vccl.MODE_CU_STAGED, stream_handle(torch))
+    vccl.vccl_sendrecv_staged_status()
+    torch.cuda.synchronize()
+    want = [np.zeros(n, np.uint8) for _ in range(P)]
+    oracle.sendrecv(send_np, [n] * P, to, want, [n] * P, frm)
+    for r in range(P):
+        assert_same(to_host(recv[r]), want[r], f"recv[{r}] after the time-out")
+
+
 def test_ce_handshake_record_advances(vccl):
     """Copy-engine SendRecv walks receiverReady -> copyStarted -> copyDone on the
     receiver's record and publishes the receive buffer's address in it."""
