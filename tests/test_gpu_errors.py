@@ -91,3 +91,45 @@ def test_overlap_check(vccl):
     finally:
         vccl.vccl_set_option("check", 0)
     torch.cuda.synchronize()
+
+
+def test_finalize_with_operations_in_flight_drains_them_and_init_works_again(vccl):
+    """vccl_finalize while copy-engine and compute-unit operations are still queued behind
+    a long kernel: it waits for them (nothing is dropped, nothing hangs), the bytes are
+    right, and a new context can be created afterwards.  (The module's context is
+    re-created at the end for the tests that follow.)"""
+    import oracle
+    import workloads as wl
+    from gpu_util import assert_same
+    torch = require_gpu()
+    P, c = 4, 1 << 18
+    send_np = [wl.payload_bytes(31, s, P * c) for s in range(P)]
+    send = [to_dev(torch, a) for a in send_np]
+    recv_ce = [to_dev(torch, np.full(P * c, SENTINEL, np.uint8)) for _ in range(P)]
+    recv_cu = [to_dev(torch, np.full(P * c, SENTINEL, np.uint8)) for _ in range(P)]
+    sink = torch.zeros(256 * 256, dtype=torch.float32, device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    vccl.vccl_fma_probe(sink, 256, 256, 30000, int(s1.cuda_stream))          # a few ms of compute first
+    vccl.vccl_alltoall(send, recv_ce, c, P, vccl.MODE_CE, int(s1.cuda_stream))
+    vccl.vccl_fma_probe(sink, 256, 256, 30000, int(s2.cuda_stream))
+    vccl.vccl_alltoall(send, recv_cu, c, P, vccl.MODE_CU, int(s2.cuda_stream))
+    try:
+        vccl.vccl_finalize()
+        torch.cuda.synchronize()
+        want = [np.zeros(P * c, np.uint8) for _ in range(P)]
+        oracle.alltoall(send_np, want, c)
+        for r in range(P):
+            assert_same(to_host(recv_ce[r]), want[r], f"copy-engine recv[{r}]")
+            assert_same(to_host(recv_cu[r]), want[r], f"compute-unit recv[{r}]")
+        with pytest.raises(vccl.VcclError) as e:
+            vccl.vccl_alltoall(send, recv_cu, c, P, vccl.MODE_CU, stream_handle(torch))
+        assert e.value.code == -5
+    finally:
+        vccl.vccl_init(0, 8)
+    for r in range(P):
+        recv_cu[r].fill_(SENTINEL)
+    vccl.vccl_alltoall(send, recv_cu, c, P, vccl.MODE_CE, stream_handle(torch))
+    torch.cuda.synchronize()
+    for r in range(P):
+        assert_same(to_host(recv_cu[r]), want[r], f"recv[{r}] on the new context")
