@@ -241,9 +241,29 @@ def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000,
     dst_b = [[torch.zeros(act_bytes, dtype=torch.uint8, device="cuda") for _ in range(2)] for _ in range(stages)]
     null = torch.zeros(16, dtype=torch.uint8, device="cuda")
 
-    def transfer(mode, src, dst, stream):
-        v.vccl_sendrecv([src, null], [act_bytes, 0], [1, 0], [null, dst], [0, act_bytes], [1, 0], 2, mode,
-                        int(stream.cuda_stream))
+    # Every link is a connection of its own (its own pair of virtual ranks), as between real
+    # pipeline stages: forward links use ranks 0..S-1 (i -> i+1), backward links S..2S-1
+    # (S+i -> S+i-1).  Sharing one pair of ranks would queue all links behind each other,
+    # because a connection carries its transfers in the order they were posted.
+    S = stages
+    PR = 2 * S
+    ring_up = [(r + 1) % S if r < S else S + (r - S + 1) % S for r in range(PR)]
+    ring_up_inv = [(r - 1) % S if r < S else S + (r - S - 1) % S for r in range(PR)]
+    ring_down = [(r - 1) % S if r < S else S + (r - S - 1) % S for r in range(PR)]
+    ring_down_inv = ring_up
+
+    def transfer(mode, src, dst, stream, stage, forward):
+        sendbuf, recvbuf = [null] * PR, [null] * PR
+        sb, rb = [0] * PR, [0] * PR
+        if forward:
+            s_rank, r_rank = stage, stage + 1
+            to, frm = ring_up, ring_up_inv
+        else:
+            s_rank, r_rank = S + stage, S + stage - 1
+            to, frm = ring_down, ring_down_inv
+        sendbuf[s_rank], sb[s_rank] = src, act_bytes
+        recvbuf[r_rank], rb[r_rank] = dst, act_bytes
+        v.vccl_sendrecv(sendbuf, sb, to, recvbuf, rb, frm, PR, mode, int(stream.cuda_stream))
 
     def iteration(mode):
         """Enqueue one whole iteration; returns the wall time from the first launch to
@@ -281,13 +301,13 @@ def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000,
                     if mode is not None:
                         if kind == "F" and i < stages - 1:
                             link_f[i].wait_event(e)
-                            transfer(mode, src_f[i][m % 2], dst_f[i][m % 2], link_f[i])
+                            transfer(mode, src_f[i][m % 2], dst_f[i][m % 2], link_f[i], i, True)
                             a = torch.cuda.Event()
                             a.record(link_f[i])
                             arrived[("F", i + 1, m)] = a
                         if kind == "B" and i > 0:
                             link_b[i].wait_event(e)
-                            transfer(mode, src_b[i][m % 2], dst_b[i][m % 2], link_b[i])
+                            transfer(mode, src_b[i][m % 2], dst_b[i][m % 2], link_b[i], i, False)
                             a = torch.cuda.Event()
                             a.record(link_b[i])
                             arrived[("B", i - 1, m)] = a
@@ -335,6 +355,7 @@ def main(argv=None):
             # 4 stages need 12 streams, which share this box's 4 hardware queues; the
             # 2-stage runs (4 streams) show the schedule without that false sharing
             out["pipeline"] = [pipeline_1f1b(torch, stages=4, fwd_iters=4000),
+                               pipeline_1f1b(torch, stages=4, fwd_iters=40000, reps=3),
                                pipeline_1f1b(torch, stages=2, fwd_iters=4000),
                                pipeline_1f1b(torch, stages=2, fwd_iters=40000)]
             print(json.dumps(out["pipeline"]), flush=True)
