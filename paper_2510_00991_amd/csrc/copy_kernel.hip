@@ -140,26 +140,38 @@ __global__ __launch_bounds__(T) void copy_aligned_kernel(CopyArgs by_value) {
     (void)by_value;
     const CopyArgs *a =
         reinterpret_cast<const CopyArgs *>((const void *)__builtin_amdgcn_kernarg_segment_ptr());
-    const Seg *sg = (INLINE ? a->inl : a->table) + blockIdx.y;
+    // the whole 32-byte descriptor in one scalar load, before any branch
+    const Seg *sp = (INLINE ? a->inl : a->table) + blockIdx.y;
+    const uint8_t *seg_src = sp->src;
+    uint8_t *seg_dst = sp->dst;
+    const uint64_t seg_bytes = sp->bytes;
+    const uint32_t lead = sp->lead;
+    // (an empty statement that needs both pointers in registers here: without it the
+    // compiler moves their load behind the first branch and the wavefront waits twice)
+    asm volatile("" ::"s"(seg_src), "s"(seg_dst));
     constexpr uint32_t kTileVecs = (uint32_t)U * T;
-    const uint64_t nv = sg->bytes >> 4;
+    // 32-bit vector counts (the planner gives this kernel no segment of 64 GiB or more):
+    // the bounds tests stay on the scalar unit
+    const uint32_t nv = (uint32_t)(seg_bytes >> 4);
     // tile 0 holds the `lead` vectors' worth of room before the segment, so that
     // every later tile starts on a destination address that is a multiple of the tile
-    const uint32_t lead = sg->lead;
-    const uint64_t end = ((uint64_t)blockIdx.x + 1) * kTileVecs - lead;
-    const uint64_t v0 = blockIdx.x ? (uint64_t)blockIdx.x * kTileVecs - lead : 0;
+    // (no 32-bit overflow: the grid has at most ceil((nv + lead) / tile) columns and
+    // nv <= 0xffff0000, tiles are at most 4096 vectors)
+    const uint32_t start = blockIdx.x * kTileVecs;
+    const uint32_t v0 = blockIdx.x ? start - lead : 0;
     if (v0 >= nv) return;
-    const u32x4 *s = reinterpret_cast<const u32x4 *>(sg->src) + v0;
-    const TileDst<NT> d(reinterpret_cast<u32x4 *>(sg->dst) + v0);
+    const uint32_t end = min(start + kTileVecs - lead, nv);
+    const u32x4 *s = reinterpret_cast<const u32x4 *>(seg_src) + v0;
+    const TileDst<NT> d(reinterpret_cast<u32x4 *>(seg_dst) + v0);
     const uint32_t tid = threadIdx.x;
-    if (end - v0 == kTileVecs && end <= nv) {
+    if (end - v0 == kTileVecs) {
         u32x4 r[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) r[u] = ld16<NT>(s + u * T + tid);
 #pragma unroll
         for (int u = 0; u < U; ++u) d.store(u * T + tid, r[u]);
     } else {
-        const uint32_t cnt = (uint32_t)(min(end, nv) - v0);
+        const uint32_t cnt = end - v0;
         for (uint32_t i = tid; i < cnt; i += T) d.store(i, ld16<NT>(s + i));
     }
 }
@@ -283,6 +295,8 @@ int plan_tiles(CopyPlan &plan, int unroll, int threads, bool allow_fast) {
     // Cutting (below) adds at most 8192 pieces; the all-aligned kernel needs one
     // grid row per descriptor, and a grid has at most 65535 rows.
     plan.fast = plan.all_aligned && allow_fast && plan.segs.size() <= 65535u - 8192u;
+    for (const Seg &s : plan.segs)   // the all-aligned kernel counts vectors in 32 bits
+        if ((s.bytes >> 4) > 0xffff0000ull) plan.fast = false;
     plan.threads = threads;
     const uint64_t tile_vecs = (uint64_t)unroll * plan.threads;
     const uint64_t tile_bytes = tile_vecs << 4;
