@@ -468,26 +468,42 @@ __global__ __launch_bounds__(64) void moe_scatter_back_tiles_kernel(MoePtrs ptrs
 
 // Fused combine: the inverse exchange and the un-permute in one pass.  Row p = t*K + k
 // of out[s] comes straight from the place in back[r] (r = rank of the pair's expert)
-// where the fused dispatch - or pack + exchange - had put the pair's row.  ptrs.x
-// holds the P buffers `back`, ptrs.packed the P outputs; same tile shape as the
-// un-permute kernel above.
+// where the fused dispatch - or pack + exchange - had put the pair's row.  A first
+// launch resolves, per pair, where that row is (destination row -> expert's rank ->
+// segment offset -> capacity: four dependent look-ups) into one pointer, null for a
+// pair that is dropped or beyond the buffer's capacity; the tile kernel then has
+// the same short chain as the un-permute kernel above: one look-up, load, store.
+__global__ __launch_bounds__(kMoeThreads) void moe_pair_source_kernel(MoePtrs ptrs, uint32_t row_vecs,
+                                                                      const uint32_t *dest, uint32_t npairs,
+                                                                      int experts_per_rank, const int64_t *delta,
+                                                                      int P, const u32x4 **source) {
+    const uint32_t rank = blockIdx.y;
+    const uint32_t p = blockIdx.x * kMoeThreads + threadIdx.x;
+    if (p >= npairs) return;
+    const u32x4 *row = nullptr;
+    const uint32_t j = dest[(size_t)rank * npairs + p];
+    if (j != kDropped) {
+        const uint32_t from = (uint32_t)(ptrs.ids[rank][p] / experts_per_rank);
+        const int64_t at = (int64_t)j + delta[(size_t)rank * P + from];
+        if ((uint64_t)at < ptrs.capacity_rows[from])
+            row = reinterpret_cast<const u32x4 *>(ptrs.x[from]) + (size_t)at * row_vecs;
+    }
+    source[(size_t)rank * npairs + p] = row;
+}
+
+// ptrs.packed holds the P outputs; 1 KiB single-wavefront tiles in output order.
 template <int POL>
 __global__ __launch_bounds__(64) void moe_combine_fused_kernel(MoePtrs ptrs, uint32_t row_vecs,
-                                                               uint32_t tiles_per_row, const uint32_t *dest,
-                                                               uint32_t npairs, int experts_per_rank,
-                                                               const int64_t *delta, int P) {
+                                                               uint32_t tiles_per_row, uint32_t npairs,
+                                                               const u32x4 *const *source) {
     const uint32_t rank = blockIdx.y;
     const uint32_t p = blockIdx.x / tiles_per_row;
     const uint32_t v0 = (blockIdx.x - p * tiles_per_row) * 64u;
     if (p >= npairs) return;
-    const uint32_t j = dest[(size_t)rank * npairs + p];
-    if (j == kDropped) return;
-    const uint32_t from = (uint32_t)(ptrs.ids[rank][p] / experts_per_rank);
-    const int64_t at = (int64_t)j + delta[(size_t)rank * P + from];
-    if ((uint64_t)at >= ptrs.capacity_rows[from]) return;
-    const u32x4 *row = reinterpret_cast<const u32x4 *>(ptrs.x[from]) + (size_t)at * row_vecs + v0;
+    const u32x4 *row = source[(size_t)rank * npairs + p];
+    if (!row) return;
     const TileDst<POL> o(reinterpret_cast<u32x4 *>(ptrs.packed[rank]) + (size_t)p * row_vecs + v0);
-    if (v0 + threadIdx.x < row_vecs) o.store(threadIdx.x, ld16<POL>(row + threadIdx.x));
+    if (v0 + threadIdx.x < row_vecs) o.store(threadIdx.x, ld16<POL>(row + v0 + threadIdx.x));
 }
 
 void MoeScratch::destroy() {
@@ -699,19 +715,25 @@ int launch_moe_combine_fused(MoeScratch &sc, const void *const *back, const uint
     MoePtrs ptrs;
     uint32_t *dest = nullptr;
     uint64_t *counts = nullptr, *extra = nullptr;
-    // room after the counts: delta [P][P] (int64), then the four layout matrices, which nobody reads here
+    // room after the counts: delta [P][P] (int64), the four layout matrices (which nobody reads
+    // here), one source pointer per pair
     int rc = moe_index_phase(sc, back, ids, P, tokens, topk, num_experts, 0, nullptr, out, capacity_rows,
-                             2 * (size_t)P * P * 5, nullptr, nullptr, stream, &ptrs, &dest, &counts, &extra);
+                             2 * ((size_t)P * P * 5 + (size_t)P * npairs), nullptr, nullptr, stream, &ptrs, &dest,
+                             &counts, &extra);
     if (rc) return rc;
     int64_t *delta = reinterpret_cast<int64_t *>(extra);
     uint64_t *layout = extra + (size_t)P * P;
+    const u32x4 **source = reinterpret_cast<const u32x4 **>(extra + (size_t)P * P * 5);
     moe_fused_layout_kernel<<<dim3(1), dim3(kMoeThreads), 0, stream>>>(counts, P, num_experts, experts_per_rank,
                                                                       row_bytes, ptrs.capacity_rows, layout, delta,
                                                                       nullptr);
     VCCL_HIP(hipGetLastError());
     if (npairs && rv) {
-        moe_combine_fused_kernel<2><<<dim3((uint32_t)grid, P), dim3(64), 0, stream>>>(
-            ptrs, rv, tiles_per_row, dest, npairs, experts_per_rank, delta, P);
+        moe_pair_source_kernel<<<dim3((npairs + kMoeThreads - 1) / kMoeThreads, P), dim3(kMoeThreads), 0, stream>>>(
+            ptrs, rv, dest, npairs, experts_per_rank, delta, P, source);
+        VCCL_HIP(hipGetLastError());
+        moe_combine_fused_kernel<2><<<dim3((uint32_t)grid, P), dim3(64), 0, stream>>>(ptrs, rv, tiles_per_row,
+                                                                                      npairs, source);
         VCCL_HIP(hipGetLastError());
     }
     VCCL_HIP(hipEventRecord(sc.done, stream));
