@@ -373,16 +373,36 @@ __global__ __launch_bounds__(kMoeThreads) void moe_fused_layout_kernel(const uin
     }
 }
 
+// Fused dispatch, target step: where in which receive buffer the row of pair p goes
+// (packed row -> expert's rank -> segment offset -> capacity), resolved once per pair
+// into a pointer; null for a dropped pair or a row beyond the buffer's capacity.
+// ptrs.packed holds the receive buffers here.
+__global__ __launch_bounds__(kMoeThreads) void moe_pair_target_kernel(MoePtrs ptrs, uint32_t row_vecs,
+                                                                      const uint32_t *dest, uint32_t npairs,
+                                                                      int experts_per_rank, const int64_t *delta,
+                                                                      int P, u32x4 **target) {
+    const uint32_t rank = blockIdx.y;
+    const uint32_t p = blockIdx.x * kMoeThreads + threadIdx.x;
+    if (p >= npairs) return;
+    u32x4 *row = nullptr;
+    const uint32_t j = dest[(size_t)rank * npairs + p];
+    if (j != kDropped) {
+        const uint32_t to = (uint32_t)(ptrs.ids[rank][p] / experts_per_rank);
+        const int64_t at = (int64_t)j + delta[(size_t)rank * P + to];
+        if ((uint64_t)at < ptrs.capacity_rows[to])
+            row = reinterpret_cast<u32x4 *>(ptrs.packed[to]) + (size_t)at * row_vecs;
+    }
+    target[(size_t)rank * npairs + p] = row;
+}
+
 // Fused dispatch, gather step: the shared-piece gather, except that the row of
 // pair (t, k) goes straight into the receive buffer of the rank that hosts its
-// expert, at the place the exchange would have put it.  ptrs.packed holds the
-// receive buffers here.  Rows beyond a buffer's capacity are not written.
+// expert, at the place the exchange would have put it.
 template <bool NT>
 __global__ __launch_bounds__(kSlotWaves * 64) void moe_gather_fused_kernel(MoePtrs ptrs, uint32_t tokens, int K,
                                                                            uint32_t row_vecs, uint32_t pieces,
-                                                                           uint32_t kgroups, const uint32_t *dest,
-                                                                           uint32_t npairs, int experts_per_rank,
-                                                                           const int64_t *delta, int P) {
+                                                                           uint32_t kgroups, uint32_t npairs,
+                                                                           u32x4 *const *target) {
     const uint32_t rank = blockIdx.y;
     const uint32_t per_token = pieces * kgroups;
     const uint32_t t = blockIdx.x / per_token;
@@ -396,13 +416,8 @@ __global__ __launch_bounds__(kSlotWaves * 64) void moe_gather_fused_kernel(MoePt
     u32x4 r0 = {0, 0, 0, 0}, r1 = {0, 0, 0, 0};
     if (v0 < row_vecs) r0 = row[v0];
     if (v1 < row_vecs) r1 = row[v1];
-    const size_t p = (size_t)t * K + k;
-    const uint32_t j = dest[(size_t)rank * npairs + p];
-    if (j == kDropped) return;
-    const uint32_t to = (uint32_t)(ptrs.ids[rank][p] / experts_per_rank);   // valid: the pair was not dropped
-    const int64_t at = (int64_t)j + delta[(size_t)rank * P + to];          // row inside recv[to]
-    if ((uint64_t)at >= ptrs.capacity_rows[to]) return;
-    u32x4 *o = reinterpret_cast<u32x4 *>(ptrs.packed[to]) + (size_t)at * row_vecs;
+    u32x4 *o = target[(size_t)rank * npairs + (size_t)t * K + k];
+    if (!o) return;
     if (v0 < row_vecs) {
         if (NT) __builtin_nontemporal_store(r0, o + v0);
         else o[v0] = r0;
@@ -682,17 +697,23 @@ int launch_moe_dispatch_fused(MoeScratch &sc, const void *const *x, const int32_
     MoePtrs ptrs;
     uint32_t *dest = nullptr;
     uint64_t *counts = nullptr, *extra = nullptr;
+    // room after the counts: delta [P][P] (int64), one target pointer per pair
     int rc = moe_index_phase(sc, x, ids, P, tokens, topk, num_experts, 0, nullptr, recv, capacity_rows,
-                             2 * (size_t)P * P, counts_dev, status_dev, stream, &ptrs, &dest, &counts, &extra);
+                             2 * ((size_t)P * P + (size_t)P * npairs), counts_dev, status_dev, stream, &ptrs, &dest,
+                             &counts, &extra);
     if (rc) return rc;
     int64_t *delta = reinterpret_cast<int64_t *>(extra);
+    u32x4 **target = reinterpret_cast<u32x4 **>(extra + (size_t)P * P);
     moe_fused_layout_kernel<<<dim3(1), dim3(kMoeThreads), 0, stream>>>(counts, P, num_experts, experts_per_rank,
                                                                       row_bytes, ptrs.capacity_rows, layout_dev,
                                                                       delta, status_dev);
     VCCL_HIP(hipGetLastError());
     if (npairs) {
+        moe_pair_target_kernel<<<dim3((npairs + kMoeThreads - 1) / kMoeThreads, P), dim3(kMoeThreads), 0, stream>>>(
+            ptrs, rv, dest, npairs, experts_per_rank, delta, P, target);
+        VCCL_HIP(hipGetLastError());
         moe_gather_fused_kernel<true><<<dim3((uint32_t)grid, P), dim3(kSlotWaves * 64), 0, stream>>>(
-            ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, dest, npairs, experts_per_rank, delta, P);
+            ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, npairs, target);
         VCCL_HIP(hipGetLastError());
     }
     if (layout_host)
