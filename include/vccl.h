@@ -99,6 +99,9 @@ const char *vccl_last_error(void);
  *       of the two stream operations with a one-lane helper kernel; "host" = no stream
  *       operation at all, the calling thread blocks until the copies are done),
  *       "ce_engines" (read-only: SDMA engines found),
+ *       "ce_errors" (read-only: copy-engine operations of which an engine refused a copy
+ *       after the call had returned; the next copy-engine call then fails once with
+ *       VCCL_ERR_HIP, and vccl_finalize returns VCCL_ERR_HIP if any went unreported),
  *       "ce_max_engines" (0 = all; else use only that many engines),
  *       "check" (0/1 overlap validation),
  *       "moe_gather_variant" (row gather of vccl_moe_pack: 208 / 308 = one workgroup of 8

@@ -92,6 +92,7 @@ struct Context {
     FifoState fifo;
     MoeScratch moe;
     Proxy *proxy = nullptr;
+    std::atomic<uint64_t> ce_errors_reported{0};
 };
 
 static std::mutex g_mu;
@@ -173,6 +174,13 @@ static int run_pieces(Context &c, std::vector<Piece> &pieces, vccl_mode mode, hi
         for (const Piece &pc : pieces)
             if (pc.bytes) copies.push_back(CeCopy{pc.src, pc.dst, pc.bytes, pc.receiver});
         if (copies.empty()) return VCCL_OK;
+        // An engine that refused a copy of an earlier, already returned operation cannot
+        // fail that call any more: the first copy-engine call after it does, once.
+        const uint64_t errs = proxy_sdma_errors(c.proxy);
+        if (errs > c.ce_errors_reported.exchange(errs))
+            return fail(VCCL_ERR_HIP, "an earlier copy-engine operation could not submit all of its copies "
+                                      "(%llu such operations so far): its receive buffers are incomplete",
+                        (unsigned long long)errs);
         return proxy_submit(c.proxy, std::move(copies), opt, stream, receivers);
     }
     return fail(VCCL_ERR_ARG, "unknown mode %d", (int)mode);
@@ -275,12 +283,18 @@ int vccl_finalize(void) {
     }
     if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_finalize without vccl_init");
     (void)hipSetDevice(c->device);
+    (void)proxy_drain(c->proxy);
+    const uint64_t errs = proxy_sdma_errors(c->proxy);
+    const bool unreported = errs > c->ce_errors_reported.load();
     proxy_destroy(c->proxy);
     c->proxy = nullptr;
     (void)hipDeviceSynchronize();
     c->ring.destroy();
     c->fifo.destroy();
     c->moe.destroy();
+    if (unreported)
+        return fail(VCCL_ERR_HIP, "%llu copy-engine operations could not submit all of their copies",
+                    (unsigned long long)errs);
     return VCCL_OK;
 }
 
@@ -317,7 +331,7 @@ int vccl_set_option(const char *key, const char *value) {
         else return fail(VCCL_ERR_ARG, "ce_kind must be 'sdma', 'hip_nocu' or 'hip_default', got '%s'", value);
         return VCCL_OK;
     }
-    if (k == "ce_engines") return fail(VCCL_ERR_ARG, "ce_engines is read-only");
+    if (k == "ce_engines" || k == "ce_errors") return fail(VCCL_ERR_ARG, "%s is read-only", key);
     if (k == "ce_sync") {
         if (!strcmp(value, "memops")) o.ce_sync_host = 0;
         else if (!strcmp(value, "host")) o.ce_sync_host = 1;
@@ -396,6 +410,7 @@ int vccl_get_option(const char *key, char *out, int cap) {
         snprintf(out, (size_t)cap, "%s", o.ce_sync_host ? "host" : "memops");
         return VCCL_OK;
     } else if (k == "ce_engines") v = (unsigned long long)proxy_engine_count(c->proxy);
+    else if (k == "ce_errors") v = (unsigned long long)proxy_sdma_errors(c->proxy);
     else if (k == "cu_unroll") v = o.cu_unroll;
     else if (k == "cu_wg_per_cu") v = o.cu_wg_per_cu;
     else if (k == "cu_max_wg") v = o.cu_max_wg;

@@ -133,3 +133,14 @@ def test_finalize_with_operations_in_flight_drains_them_and_init_works_again(vcc
     torch.cuda.synchronize()
     for r in range(P):
         assert_same(to_host(recv_cu[r]), want[r], f"recv[{r}] on the new context")
+
+
+def test_copy_engine_error_counter_is_readable_and_read_only(vccl):
+    torch = require_gpu()
+    x = [to_dev(torch, np.arange(4096, dtype=np.uint8).repeat(1)) for _ in range(2)]
+    y = [to_dev(torch, np.zeros(4096, np.uint8)) for _ in range(2)]
+    vccl.vccl_alltoall(x, y, 2048, 2, vccl.MODE_CE, stream_handle(torch))
+    torch.cuda.synchronize()
+    assert int(vccl.vccl_get_option("ce_errors")) == 0
+    with pytest.raises(vccl.VcclError):
+        vccl.vccl_set_option("ce_errors", 0)
