@@ -283,6 +283,21 @@ int vccl_moe_exchange_layout(const uint64_t *counts, int P, int num_experts, int
                              uint64_t row_bytes, uint64_t *sendcounts, uint64_t *sdispls,
                              uint64_t *recvcounts, uint64_t *rdispls);
 
+/* HBM ceiling probe, a measurement aid: plain streaming kernels in the launch shapes of
+ * the copy paths, for finding what the device gives to read-only, write-only, copy
+ * and scattered-row-write traffic - the rooflines the copy kernel (Appendix A: the
+ * P2P copy that occupies compute units) and the MoE row movement (Section 6) are
+ * held against.  One workgroup of `threads` lanes handles vecs_per_lane consecutive
+ * 16-byte vectors per lane; accepted shapes: 64x1, 64x2, 64x4, 64x16, 256x1, 256x4,
+ * 448x2.  kind 0: read `bytes` from src (dst = any 64-byte device buffer, not
+ * written); 1: write `bytes` to dst; 2: copy `bytes` from src to dst; 3: write n_rows
+ * whole rows of row_bytes to dst, the i-th at row row_index[i] (device uint32 array,
+ * values below the number of rows dst holds; NULL = row i).  Buffers are device
+ * memory, 16-byte aligned; what is written is a fixed pattern.  Asynchronous on
+ * `stream`; timing is the caller's. */
+int vccl_hbm_probe(int kind, const void *src, void *dst, uint64_t bytes, int threads, int vecs_per_lane,
+                   const uint32_t *row_index, uint64_t n_rows, uint64_t row_bytes, void *stream);
+
 /* Co-run probe (Appendix E: a compute kernel forming one wave of workgroups over
  * all compute units, slowed by co-resident communication warps).  Launches a
  * register-only FP32 FMA kernel of `workgroups` x `threads` (threads a multiple of

@@ -62,6 +62,9 @@ EXPORTS = {
                                        ctypes.c_uint64, ctypes.c_int, _vpp, ctypes.c_void_p]),
     "vccl_moe_exchange_layout": (ctypes.c_int, [_u64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                 ctypes.c_uint64, _u64p, _u64p, _u64p, _u64p]),
+    "vccl_hbm_probe": (ctypes.c_int, [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64,
+                                      ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_uint64,
+                                      ctypes.c_uint64, ctypes.c_void_p]),
     "vccl_fma_probe": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32,
                                       ctypes.c_uint64, ctypes.c_void_p]),
     "vccl_monitor_create": (ctypes.c_void_p, [ctypes.c_int, ctypes.c_uint64]),
@@ -342,6 +345,14 @@ def vccl_proxy_monitor(primitive: int) -> dict:
     a, b, s = ctypes.c_uint64(), ctypes.c_uint64(), MonitorSample()
     _check(load().vccl_proxy_monitor(primitive, ctypes.byref(a), ctypes.byref(b), ctypes.byref(s)))
     return {"messages": a.value, "anomalies": b.value, "last": s.as_dict()}
+
+
+def vccl_hbm_probe(kind: int, src, dst, nbytes: int, threads: int, vecs_per_lane: int, row_index=None,
+                   n_rows: int = 0, row_bytes: int = 0, stream=None) -> None:
+    """kind 0 read, 1 write, 2 copy, 3 write n_rows rows of row_bytes at row_index[i] (device int32 tensor or None)."""
+    _check(load().vccl_hbm_probe(kind, ctypes.c_void_p(_addr(src)), ctypes.c_void_p(_addr(dst)), int(nbytes),
+                                 threads, vecs_per_lane, ctypes.c_void_p(_addr(row_index)), int(n_rows),
+                                 int(row_bytes), _stream(stream)))
 
 
 def vccl_fma_probe(out_dev, workgroups: int, threads: int, iters: int, stream=None) -> None:

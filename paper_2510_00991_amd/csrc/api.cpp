@@ -729,6 +729,25 @@ int vccl_fma_probe(float *out_dev, uint32_t workgroups, uint32_t threads, uint64
     return launch_fma_probe(out_dev, workgroups, threads, iters, (hipStream_t)stream);
 }
 
+int vccl_hbm_probe(int kind, const void *src, void *dst, uint64_t bytes, int threads, int vecs_per_lane,
+                   const uint32_t *row_index, uint64_t n_rows, uint64_t row_bytes, void *stream) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    if (kind < 0 || kind > 3) return fail(VCCL_ERR_ARG, "kind %d is not 0 (read), 1 (write), 2 (copy) or 3 (write rows)", kind);
+    if (!dst || ((kind == 0 || kind == 2) && !src)) return fail(VCCL_ERR_ARG, "NULL buffer");
+    if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u)
+        return fail(VCCL_ERR_ARG, "buffers are not 16-byte aligned");
+    if (kind == 3) {
+        if (!n_rows || !row_bytes || (row_bytes & 15u) || (row_bytes >> 4) > 0xffffffffull)
+            return fail(VCCL_ERR_ARG, "n_rows = %llu, row_bytes = %llu (a positive multiple of 16)",
+                        (unsigned long long)n_rows, (unsigned long long)row_bytes);
+    } else if (!bytes || (bytes & 15u)) {
+        return fail(VCCL_ERR_ARG, "bytes = %llu must be a positive multiple of 16", (unsigned long long)bytes);
+    }
+    return launch_hbm_probe(kind, src, dst, bytes, threads, vecs_per_lane, row_index, n_rows, row_bytes,
+                            (hipStream_t)stream);
+}
+
 int vccl_sendrecv_staged_status(void) {
     auto c = ctx_get();
     if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");

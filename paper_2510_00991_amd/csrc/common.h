@@ -183,6 +183,10 @@ int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *
 int launch_fma_probe(float *out, uint32_t workgroups, uint32_t threads, uint64_t iters,
                      hipStream_t stream);
 
+// kind: 0 read-only (dst = 64-byte sink), 1 write-only, 2 copy, 3 write rows of row_bytes at row_index[i]
+int launch_hbm_probe(int kind, const void *src, void *dst, uint64_t bytes, int threads, int vecs,
+                     const uint32_t *row_index, uint64_t n_rows, uint64_t row_bytes, hipStream_t stream);
+
 // ---- copy-engine proxy
 struct CeCopy {
     const void *src;

@@ -4,7 +4,7 @@ effect the paper describes in Appendix E), the pipeline SendRecv ring and the
 P = 64 message-size sweep.  PyTorch is used for device memory, streams and
 events only; every byte is moved by libvccl.
 
-CLI:  python -m paper_2510_00991_amd.harness ring|sweep|pipeline|all  [--json FILE]
+CLI:  python -m paper_2510_00991_amd.harness ring|sweep|pipeline|ceilings|all  [--json FILE]
 """
 from __future__ import annotations
 
@@ -206,6 +206,54 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
     return {"workload": f"AlltoAll sweep, P={P}, per-peer 4 KiB..4 MiB", "rows": rows}
 
 
+def hbm_ceilings(torch, gib=(1, 7), reps=10):
+    """What the device gives plain streaming kernels, for the rooflines of the copy
+    paths: read-only, write-only, copy, and whole 14 KiB rows written in order or to
+    permuted row positions (the MoE pack's write pattern), in several launch shapes.
+    GB/s = bytes read + bytes written."""
+    st = int(torch.cuda.current_stream().cuda_stream)
+    rows_out = []
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        ev = [(_ev(torch), _ev(torch)) for _ in range(reps)]
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        return statistics.median(a.elapsed_time(b) * 1e-3 for a, b in ev)
+
+    sink = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    for g in gib:
+        n = g << 30
+        a = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+        b = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(2)
+        for kind, name, moved in ((0, "read", n), (1, "write", n), (2, "copy", 2 * n)):
+            for threads, vecs in ((64, 1), (64, 2), (64, 4), (64, 16), (256, 1), (256, 4)):
+                dst = sink if kind == 0 else b
+                t = timed(lambda: v.vccl_hbm_probe(kind, a, dst, n, threads, vecs, None, 0, 0, st))
+                rows_out.append({"pattern": name, "GiB": g, "lanes": threads, "vectors_per_lane": vecs,
+                                 "us": t * 1e6, "GBps": moved / t / 1e9})
+        del a
+        # whole rows of 14 336 bytes (config 3), in order and to permuted positions
+        row = 14336
+        n_rows = n // row
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(12345)
+        perm = torch.randperm(n_rows, device="cuda", generator=gen).to(torch.int32)
+        for order, idx in (("rows in order", None), ("rows permuted", perm)):
+            for threads, vecs in ((64, 2), (256, 1), (448, 2), (64, 16)):
+                t = timed(lambda: v.vccl_hbm_probe(3, None, b, 0, threads, vecs, idx, n_rows, row, st))
+                rows_out.append({"pattern": "write " + order, "GiB": g, "lanes": threads, "vectors_per_lane": vecs,
+                                 "us": t * 1e6, "GBps": n_rows * row / t / 1e9})
+        del b, perm
+        torch.cuda.empty_cache()
+    return {"workload": "HBM ceiling probes (vccl_hbm_probe)", "rows": rows_out}
+
+
 def _schedule_1f1b(stages, micro):
     """Per stage, the 1F1B order of ("F", m) / ("B", m) steps (warm-up forwards,
     then one forward one backward, then the remaining backwards)."""
@@ -336,7 +384,8 @@ def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000,
 
 def main(argv=None):
     ap = argparse.ArgumentParser()
-    ap.add_argument("what", choices=["ring", "sweep", "pipeline", "all"])
+    ap.add_argument("what", choices=["ring", "sweep", "pipeline", "ceilings", "all"])
+    ap.add_argument("--ceiling-gib", default="1,7", help="buffer sizes of the ceiling probes, GiB, comma separated")
     ap.add_argument("--json", default=None)
     ap.add_argument("--no-corun", action="store_true")
     args = ap.parse_args(argv)
@@ -359,6 +408,8 @@ def main(argv=None):
                                pipeline_1f1b(torch, stages=2, fwd_iters=4000),
                                pipeline_1f1b(torch, stages=2, fwd_iters=40000)]
             print(json.dumps(out["pipeline"]), flush=True)
+        if args.what in ("ceilings", "all"):
+            out["ceilings"] = hbm_ceilings(torch, gib=tuple(int(x) for x in args.ceiling_gib.split(",")))
         if args.what in ("sweep", "all"):
             out["sweep"] = sweep_p64(torch, with_corun=not args.no_corun)
             print(json.dumps(out["sweep"]), flush=True)

@@ -90,3 +90,41 @@ def test_copy_engine_progresses_while_all_wave_slots_are_busy(vccl, kind):
         assert t_copy_done < 0.7 * t_compute, (t_copy_done, t_compute)
     for r, s in ((0, 5), (7, 7), (3, 0)):
         assert torch.equal(recv[r][s * c:(s + 1) * c], send[s][r * c:(r + 1) * c])
+
+
+def test_hbm_probe_kernels_touch_exactly_what_they_should(vccl):
+    """The ceiling probes are measurement aids, but they must move what they claim to: the
+    copy copies, the write fills exactly `bytes`, the row writer puts whole rows at the
+    indexed positions and nothing else, in every accepted launch shape."""
+    torch = require_gpu()
+    import numpy as np
+    st = int(torch.cuda.current_stream().cuda_stream)
+    n = (1 << 20) + 4096 + 16
+    for threads, vecs in ((64, 1), (64, 2), (64, 4), (64, 16), (256, 1), (256, 4), (448, 2)):
+        src = torch.randint(0, 256, (n + 64,), dtype=torch.uint8, device="cuda")
+        dst = torch.full((n + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        vccl.vccl_hbm_probe(2, src, dst, n, threads, vecs, None, 0, 0, st)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n], src[:n]) and bool((dst[n:] == 0xA5).all()), (threads, vecs)
+        dst.fill_(0xA5)
+        vccl.vccl_hbm_probe(1, None, dst, n, threads, vecs, None, 0, 0, st)
+        vccl.vccl_hbm_probe(0, src, dst[n:], n, threads, vecs, None, 0, 0, st)     # reads only: the sink stays
+        torch.cuda.synchronize()
+        assert bool((dst[n:] == 0xA5).all())
+        words = dst[:n].cpu().numpy().view(np.uint32).reshape(-1, 4)
+        assert (words[:, 2] == 0x5A5A5A5A).all() and (words[:, 3] == 0xA5A5A5A5).all(), (threads, vecs)
+        # rows: 7 rows of 1 040 bytes into a buffer of 16 rows, at chosen positions
+        row, total_rows = 1040, 16
+        idx = torch.tensor([3, 0, 15, 7, 9, 1, 12], dtype=torch.int32, device="cuda")
+        buf = torch.full((row * total_rows,), 0xA5, dtype=torch.uint8, device="cuda")
+        vccl.vccl_hbm_probe(3, None, buf, 0, threads, vecs, idx, idx.numel(), row, st)
+        torch.cuda.synchronize()
+        got = buf.cpu().numpy().reshape(total_rows, row)
+        for r in range(total_rows):
+            if r in idx.cpu().tolist():
+                w = got[r].view(np.uint32).reshape(-1, 4)
+                assert (w[:, 2] == 0x5A5A5A5A).all() and (w[:, 0] == idx.cpu().tolist().index(r)).all(), (threads, vecs, r)
+            else:
+                assert (got[r] == 0xA5).all(), (threads, vecs, r)
+    with pytest.raises(vccl.VcclError):
+        vccl.vccl_hbm_probe(2, src, dst, n, 128, 3, None, 0, 0, st)
