@@ -176,11 +176,17 @@ def main():
             del a, b
         if "ce" in legs:
             k_ce = max(3, min(args.steps, 10))
+            cpu0 = v.vccl_proxy_cpu_time()
             wall_ce, per_ce = time_calls(torch, a2a_ce, k_ce, 2)
+            cpu1 = v.vccl_proxy_cpu_time()
             out["copy_engine"] = {"GBps": algo_bytes / (wall_ce / k_ce) / 1e9,
                                   "ms_per_step": wall_ce / k_ce * 1e3, "steps": k_ce,
                                   "kind": v.vccl_get_option("ce_kind"), "sync": v.vccl_get_option("ce_sync"),
-                                  "engines": int(v.vccl_get_option("ce_engines"))}
+                                  "engines": int(v.vccl_get_option("ce_engines")),
+                                  # processor time of the proxy threads over warm-up + timed calls
+                                  "proxy_cpu_ms_per_step": (cpu1["sender_ns"] - cpu0["sender_ns"]
+                                                            + cpu1["receiver_ns"] - cpu0["receiver_ns"])
+                                  / (k_ce + 2) * 1e-6}
         if "corun" in legs:
             # co-run: FMA probe alone vs beside each path (protocol in harness.CoRun)
             co = CoRun(torch)

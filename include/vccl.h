@@ -338,6 +338,14 @@ int vccl_proxy_monitor(int primitive, uint64_t *messages, uint64_t *anomalies, v
  * bytes, and nanoseconds the proxy spent issuing.  Any pointer may be NULL. */
 int vccl_proxy_stats(uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t *issue_ns);
 
+/* Processor time, in nanoseconds, that the sender proxy thread (which drives the
+ * copy engines and polls for completion) and the receiver proxy thread (the
+ * receiving side of the SendRecv handshake) have used since vccl_init: the cost the
+ * paper's CPU-utilisation measurement (Section 4.1) charges to moving control from
+ * the GPU to host threads.  The threads sleep while nothing is in flight and poll
+ * while something is.  Either pointer may be NULL. */
+int vccl_proxy_cpu_time(uint64_t *sender_ns, uint64_t *receiver_ns);
+
 /* Number of compute units of the initialised device (for sizing probes). */
 int vccl_device_cu_count(void);
 

@@ -74,6 +74,7 @@ EXPORTS = {
     "vccl_monitor_totals": (ctypes.c_int, [ctypes.c_void_p, _u64p, _u64p, ctypes.c_void_p]),
     "vccl_proxy_monitor": (ctypes.c_int, [ctypes.c_int, _u64p, _u64p, ctypes.c_void_p]),
     "vccl_proxy_stats": (ctypes.c_int, [_u64p, _u64p, _u64p, _u64p]),
+    "vccl_proxy_cpu_time": (ctypes.c_int, [_u64p, _u64p]),
     "vccl_device_cu_count": (ctypes.c_int, []),
 }
 
@@ -364,3 +365,10 @@ def vccl_proxy_stats():
     v = [ctypes.c_uint64() for _ in range(4)]
     _check(load().vccl_proxy_stats(*[ctypes.byref(x) for x in v]))
     return {"ops": v[0].value, "copies": v[1].value, "bytes": v[2].value, "issue_ns": v[3].value}
+
+
+def vccl_proxy_cpu_time():
+    """Processor time (ns) used so far by the sender and the receiver proxy thread."""
+    a, b = ctypes.c_uint64(), ctypes.c_uint64()
+    _check(load().vccl_proxy_cpu_time(ctypes.byref(a), ctypes.byref(b)))
+    return {"sender_ns": a.value, "receiver_ns": b.value}

@@ -765,6 +765,12 @@ int vccl_proxy_stats(uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t 
     return VCCL_OK;
 }
 
+int vccl_proxy_cpu_time(uint64_t *sender_ns, uint64_t *receiver_ns) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    return proxy_cpu_time(c->proxy, sender_ns, receiver_ns);
+}
+
 int vccl_proxy_monitor(int primitive, uint64_t *messages, uint64_t *anomalies, vccl_monitor_sample *last) {
     auto c = ctx_get();
     if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");

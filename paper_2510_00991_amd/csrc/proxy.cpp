@@ -35,6 +35,9 @@
 #include <hsa/hsa.h>
 #include <hsa/hsa_ext_amd.h>
 
+#include <pthread.h>
+#include <time.h>
+
 #include <chrono>
 #include <condition_variable>
 #include <cstdlib>
@@ -738,6 +741,22 @@ void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uin
 }
 
 uint64_t proxy_sdma_errors(Proxy *p) { return p->sdma_errors.load(); }
+
+// Processor time the two proxy threads have used so far (what the paper's CPU
+// utilisation figure, Section 4.1, charges to the SM-free design).
+int proxy_cpu_time(Proxy *p, uint64_t *sender_ns, uint64_t *receiver_ns) {
+    std::thread *threads[2] = {&p->th, &p->receiver_th};
+    uint64_t *out[2] = {sender_ns, receiver_ns};
+    for (int i = 0; i < 2; ++i) {
+        if (!out[i]) continue;
+        clockid_t cid;
+        struct timespec ts;
+        if (pthread_getcpuclockid(threads[i]->native_handle(), &cid) != 0 || clock_gettime(cid, &ts) != 0)
+            return fail(VCCL_ERR_UNSUPPORTED, "the thread's processor-time clock cannot be read");
+        *out[i] = (uint64_t)ts.tv_sec * 1000000000ull + (uint64_t)ts.tv_nsec;
+    }
+    return VCCL_OK;
+}
 
 vccl_monitor *proxy_monitor(Proxy *p, int primitive) {
     return (primitive == 0 || primitive == 1) ? p->monitor[primitive] : nullptr;

@@ -172,6 +172,12 @@ def test_ce_handshake_record_advances(vccl):
             assert addr == recv[r].data_ptr()
     st = vccl.vccl_proxy_stats()
     assert st["ops"] >= 3 and st["bytes"] >= 3 * P * n
+    # both proxy threads have run, and neither can have used more processor time than
+    # has passed since the module's fixture initialised the library
+    cpu = vccl.vccl_proxy_cpu_time()
+    assert cpu["sender_ns"] > 0 and cpu["receiver_ns"] > 0
+    again = vccl.vccl_proxy_cpu_time()
+    assert again["sender_ns"] >= cpu["sender_ns"] and again["receiver_ns"] >= cpu["receiver_ns"]
 
 
 @pytest.mark.parametrize("kind,sync", [("sdma", "memops"), ("hip_default", "memops")])
