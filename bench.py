@@ -24,7 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-from paper_2510_00991_amd.harness import time_calls  # noqa: E402  (event timing helper)
+from paper_2510_00991_amd.harness import time_calls, time_region  # noqa: E402  (timing helpers)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
@@ -59,11 +59,17 @@ def cpu_baseline(P, c, budget_s=12.0):
 
 def headline(torch, v, a2a_cu, args, algo_bytes, P, c, send, recv):
     """The timed region of the benchmark: K AlltoAll calls on the compute-unit path."""
-    wall, per = time_calls(torch, a2a_cu, args.steps, args.warmup)
+    # One call is one launch of the copy kernel (64 descriptors travel as kernel
+    # arguments), so the device time of the train of K calls divided by K is the
+    # kernel's average duration in the timed region.
+    wall, dev = time_region(torch, a2a_cu, args.steps, args.warmup)
     ms_per_step = wall / args.steps * 1e3
     value = algo_bytes / (wall / args.steps) / 1e9
-    kern = statistics.mean(per)
+    kern = dev / args.steps
     achieved = algo_bytes / kern / 1e9
+    # the same kernel with an event pair around every single call (outside the timed
+    # region: the events themselves delay the next launch)
+    _, per = time_calls(torch, a2a_cu, min(args.steps, 20), 0)
     out = {
         "metric": "AlltoAll(v) achieved GB/s (R+W) vs HBM peak; co-run compute slowdown %",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -79,6 +85,7 @@ def headline(torch, v, a2a_cu, args, algo_bytes, P, c, send, recv):
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(),
                      "kernel": "copy_aligned_kernel", "kernel_us": kern * 1e6,
+                     "kernel_us_single_calls": statistics.mean(per) * 1e6,
                      "algorithmic_bytes": algo_bytes},
         "frac_of_hbm_peak": value / HBM_PEAK_GBS,
     }
@@ -171,13 +178,13 @@ def main():
         if "calib" in legs:
             a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
             b = torch.empty_like(a)
-            w, _ = time_calls(torch, lambda: b.copy_(a), 5, 2)
+            w, _ = time_region(torch, lambda: b.copy_(a), 5, 2)
             out["calib_copy_1GiB"] = {"GBps": 2.0 * (1 << 30) / (w / 5) / 1e9, "launches": 7}
             del a, b
         if "ce" in legs:
             k_ce = max(3, min(args.steps, 10))
             cpu0 = v.vccl_proxy_cpu_time()
-            wall_ce, per_ce = time_calls(torch, a2a_ce, k_ce, 2)
+            wall_ce, _ = time_region(torch, a2a_ce, k_ce, 2)
             cpu1 = v.vccl_proxy_cpu_time()
             out["copy_engine"] = {"GBps": algo_bytes / (wall_ce / k_ce) / 1e9,
                                   "ms_per_step": wall_ce / k_ce * 1e3, "steps": k_ce,
@@ -196,19 +203,19 @@ def main():
             v.vccl_set_option("cu_max_wg", co.cu)
             v.vccl_set_option("cu_unroll", 8)
             v.vccl_set_option("cu_threads", 256)
-            wcap, _ = time_calls(torch, a2a_cu, 5, 2)
+            wcap, _ = time_region(torch, a2a_cu, 5, 2)
             cor_cap = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes, wcap / 5)
             cor_cap["GBps_alone"] = algo_bytes / (wcap / 5) / 1e9
             # and to a quarter of that: 64 workgroups
             v.vccl_set_option("cu_max_wg", 64)
-            wcap64, _ = time_calls(torch, a2a_cu, 3, 1)
+            wcap64, _ = time_region(torch, a2a_cu, 3, 1)
             cor_cap64 = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes,
                                   wcap64 / 3)
             cor_cap64["GBps_alone"] = algo_bytes / (wcap64 / 3) / 1e9
             v.vccl_set_option("cu_max_wg", 0)
             v.vccl_set_option("cu_unroll", 1)
             v.vccl_set_option("cu_threads", 64)
-            wce, _ = time_calls(torch, a2a_ce, 3, 1)
+            wce, _ = time_region(torch, a2a_ce, 3, 1)
             cor_ce = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CE, sh), algo_bytes, wce / 3)
             out["corun"] = {"probe": f"FMA kernel, {co.cu} workgroups x {co.threads} threads, "
                                      f"{co.iters} rounds of 64 FMAs per lane",
@@ -222,7 +229,7 @@ def main():
             for name, mode in (("cu_direct", v.MODE_CU), ("cu_staged", v.MODE_CU_STAGED),
                                ("copy_engine", v.MODE_CE)):
                 fn = lambda m=mode: v.vccl_sendrecv(send, [n] * P, to, recv, [n] * P, frm, P, m, st)
-                w, _ = time_calls(torch, fn, 5, 2)
+                w, _ = time_region(torch, fn, 5, 2)
                 sr[name] = {"GBps": 2.0 * P * n / (w / 5) / 1e9, "ms": w / 5 * 1e3}
             v.vccl_sendrecv_staged_status()
             out["sendrecv_ring_8x64MiB"] = sr
@@ -240,17 +247,17 @@ def main():
             counts = torch.zeros((P, E), dtype=torch.int64, device="cuda")
             counts_h = torch.zeros((P, E), dtype=torch.int64).pin_memory()
             fn = lambda: v.vccl_moe_pack(x, ids, P, T, K, row, E, packed, counts, counts_h, None, st)
-            w, _ = time_calls(torch, fn, 5, 2)
+            w, _ = time_region(torch, fn, 5, 2)
             pack_bytes = P * (T * row + T * K * 4 + T * K * row)
             lay = v.vccl_moe_exchange_layout(counts_h.numpy().astype(np.uint64), P, E, E // P, row)
             rcv = [torch.empty(int(lay["recvcounts"][r].sum()), dtype=torch.uint8, device="cuda")
                    for r in range(P)]
             fx = lambda: v.vccl_alltoallv(packed, lay["sendcounts"], lay["sdispls"], rcv,
                                           lay["recvcounts"], lay["rdispls"], P, v.MODE_CU, st)
-            wx, _ = time_calls(torch, fx, 5, 2)
+            wx, _ = time_region(torch, fx, 5, 2)
             outp = [torch.empty(T * K * row, dtype=torch.uint8, device="cuda") for _ in range(P)]
             fu = lambda: v.vccl_moe_unpack(packed, ids, P, T, K, row, E, outp, st)
-            wu, _ = time_calls(torch, fu, 5, 2)
+            wu, _ = time_region(torch, fu, 5, 2)
             del outp
             out["moe_combine_unpack"] = {"GBps": 2.0 * P * T * K * row / (wu / 5) / 1e9, "ms": wu / 5 * 1e3}
             out["moe_dispatch"] = {
@@ -263,12 +270,12 @@ def main():
             counts_rh = torch.zeros((P, P), dtype=torch.int64).pin_memory()
             fr = lambda: v.vccl_moe_pack_per_rank(x, ids, P, T, K, row, E, E // P, packed, counts_r, counts_rh,
                                                   None, None, st)
-            wr, _ = time_calls(torch, fr, 5, 2)
+            wr, _ = time_region(torch, fr, 5, 2)
             rows_r = int(counts_rh.numpy().sum())
             lay_r = v.vccl_moe_exchange_layout(counts_rh.numpy().astype(np.uint64), P, P, 1, row)
             fxr = lambda: v.vccl_alltoallv(packed, lay_r["sendcounts"], lay_r["sdispls"], rcv,
                                            lay_r["recvcounts"], lay_r["rdispls"], P, v.MODE_CU, st)
-            wxr, _ = time_calls(torch, fxr, 5, 2)
+            wxr, _ = time_region(torch, fxr, 5, 2)
             out["moe_dispatch_per_rank"] = {
                 "rows": rows_r, "rows_per_slot_form": P * T * K,
                 "pack_GBps": (P * (T * row + T * K * 4) + rows_r * row) / (wr / 5) / 1e9, "pack_ms": wr / 5 * 1e3,
@@ -281,14 +288,14 @@ def main():
             status_d = torch.zeros(2, dtype=torch.int32, device="cuda")
             ff = lambda: v.vccl_moe_dispatch_fused(x, ids, P, T, K, row, E, E // P, rcv, cap, counts, layout_d,
                                                    None, status_d, st)
-            wf, _ = time_calls(torch, ff, 5, 2)
+            wf, _ = time_region(torch, ff, 5, 2)
             assert status_d.cpu().tolist() == [0, 0]
             out["moe_dispatch_fused"] = {"GBps": pack_bytes / (wf / 5) / 1e9, "ms": wf / 5 * 1e3,
                                          "two_step_ms": (w + wx) / 5 * 1e3}
             # the way back fused: inverse exchange + un-permute in one pass
             outp = [torch.empty(T * K * row, dtype=torch.uint8, device="cuda") for _ in range(P)]
             fc = lambda: v.vccl_moe_combine_fused(rcv, cap, ids, P, T, K, row, E, E // P, outp, st)
-            wc, _ = time_calls(torch, fc, 5, 2)
+            wc, _ = time_region(torch, fc, 5, 2)
             out["moe_combine_fused"] = {"GBps": 2.0 * P * T * K * row / (wc / 5) / 1e9, "ms": wc / 5 * 1e3,
                                         "two_step_ms": (wx + wu) / 5 * 1e3}
             del outp

@@ -38,6 +38,26 @@ def time_calls(torch, fn, steps, warmup):
     return wall, [a.elapsed_time(b) * 1e-3 for a, b in ev]
 
 
+def time_region(torch, fn, steps, warmup):
+    """(wall seconds, device seconds) for `steps` back-to-back calls: the host clock
+    between two device synchronisations, and one pair of events on the current stream
+    around the whole train of calls.  Nothing is recorded between the calls, so the
+    launches follow each other as they would in an application (an event between two
+    kernels costs about 5 us of dispatch each on this device)."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    a, b = _ev(torch), _ev(torch)
+    t0 = time.perf_counter()
+    a.record()
+    for _ in range(steps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, a.elapsed_time(b) * 1e-3
+
+
 class CoRun:
     """FMA probe on its own stream, timed alone and while `comm_fn` keeps another
     stream busy.  slowdown = (T_with - T_alone) / T_alone."""
