@@ -274,6 +274,56 @@ def hbm_ceilings(torch, gib=(1, 7), reps=10):
     return {"workload": "HBM ceiling probes (vccl_hbm_probe)", "rows": rows_out}
 
 
+def p2p_sweep(torch, sizes=None, reps=20):
+    """One pair of ranks exchanging one message each way (rank 0 -> 1 and 1 -> 0) over
+    message sizes 1 KiB .. 256 MiB in every SendRecv mode: the time from the call to the
+    completion of the caller's stream (median over single calls on an idle device) and
+    the rate of a train of calls.  The shape of the paper's point-to-point evaluation
+    (Section 4.1): bandwidth for large messages, latency for small ones."""
+    import workloads as wl
+
+    sizes = sizes or [1 << k for k in range(10, 29, 2)]
+    P = 2
+    to, frm = wl.ring_peers(P)
+    st = int(torch.cuda.current_stream().cuda_stream)
+    top = max(sizes)
+    send = [torch.from_numpy(wl.payload_bytes(wl.config_seed(4), s, min(top, 1 << 20))).cuda().repeat(
+        (top + (1 << 20) - 1) >> 20)[:top].contiguous() for s in range(P)]
+    recv = [torch.zeros(top, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    send_p, recv_p = v.pointer_array(send), v.pointer_array(recv)
+    modes = (("cu_direct", v.MODE_CU, {}),
+             ("cu_staged_fifo", v.MODE_CU_STAGED, {}),
+             ("copy_engine_memops", v.MODE_CE, {"ce_kind": "sdma", "ce_sync": "memops"}),
+             ("copy_engine_host_sync", v.MODE_CE, {"ce_kind": "sdma", "ce_sync": "host"}))
+    rows = []
+    for n in sizes:
+        row = {"bytes": n}
+        for name, mode, opts in modes:
+            saved = _set(opts)
+            try:
+                fn = lambda: v.vccl_sendrecv(send_p, [n] * P, to, recv_p, [n] * P, frm, P, mode, st)
+                fn()
+                torch.cuda.synchronize()
+                lat = []
+                for _ in range(reps):
+                    t0 = time.perf_counter()
+                    fn()
+                    torch.cuda.synchronize()
+                    lat.append(time.perf_counter() - t0)
+                k = 10 if n <= (16 << 20) else 4
+                wall = statistics.median(time_region(torch, fn, k, 1)[0] for _ in range(5))
+                if mode == v.MODE_CU_STAGED:
+                    v.vccl_sendrecv_staged_status()
+                row[name] = {"call_to_completion_us": statistics.median(lat) * 1e6,
+                             "train_us_per_call": wall / k * 1e6,
+                             "GBps": 2.0 * P * n / (wall / k) / 1e9}
+            finally:
+                _set(saved)
+        rows.append(row)
+    return {"workload": "SendRecv between one pair of ranks, one message each way, 1 KiB .. 256 MiB "
+                        "(GB/s = bytes read + bytes written)", "rows": rows}
+
+
 def _schedule_1f1b(stages, micro):
     """Per stage, the 1F1B order of ("F", m) / ("B", m) steps (warm-up forwards,
     then one forward one backward, then the remaining backwards)."""
@@ -404,7 +454,7 @@ def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000,
 
 def main(argv=None):
     ap = argparse.ArgumentParser()
-    ap.add_argument("what", choices=["ring", "sweep", "pipeline", "ceilings", "all"])
+    ap.add_argument("what", choices=["ring", "sweep", "pipeline", "ceilings", "p2p", "all"])
     ap.add_argument("--ceiling-gib", default="1,7", help="buffer sizes of the ceiling probes, GiB, comma separated")
     ap.add_argument("--json", default=None)
     ap.add_argument("--no-corun", action="store_true")
@@ -430,6 +480,9 @@ def main(argv=None):
             print(json.dumps(out["pipeline"]), flush=True)
         if args.what in ("ceilings", "all"):
             out["ceilings"] = hbm_ceilings(torch, gib=tuple(int(x) for x in args.ceiling_gib.split(",")))
+        if args.what in ("p2p", "all"):
+            out["p2p"] = p2p_sweep(torch)
+            print(json.dumps(out["p2p"]), flush=True)
         if args.what in ("sweep", "all"):
             out["sweep"] = sweep_p64(torch, with_corun=not args.no_corun)
             print(json.dumps(out["sweep"]), flush=True)

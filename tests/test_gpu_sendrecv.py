@@ -203,13 +203,16 @@ def test_ce_connection_keeps_order_with_many_transfers_outstanding(vccl, kind, s
     vccl.vccl_set_option("ce_sync", sync)
     try:
         torch.cuda.synchronize()
-        vccl.vccl_fma_probe(sink, 256, 256, 20000, int(held.cuda_stream))       # a few ms of compute
+        vccl.vccl_fma_probe(sink, 256, 256, 60000, int(held.cuda_stream))       # about 9 ms of compute
+        probe_done = torch.cuda.Event()
+        probe_done.record(held)
         t0 = time.perf_counter()
         vccl.vccl_sendrecv(sends[0], [n] * P, to, recvs[0], [n] * P, frm, P, vccl.MODE_CE, int(held.cuda_stream))
         for i in range(1, calls):
             vccl.vccl_sendrecv(sends[i], [n] * P, to, recvs[i], [n] * P, frm, P, vccl.MODE_CE,
                                int(idle.cuda_stream))
         issue_s = time.perf_counter() - t0
+        still_running = not probe_done.query()
         torch.cuda.synchronize()
     finally:
         vccl.vccl_set_option("ce_kind", saved[0])
@@ -229,7 +232,7 @@ def test_ce_connection_keeps_order_with_many_transfers_outstanding(vccl, kind, s
         assert now[r][0] == now[r][1] == now[r][2] == before[r][0] + calls
     if kind == "sdma":
         # nothing in the sdma hand-over waits for the device: all calls return while the kernel still runs
-        assert issue_s < 2e-3, f"handing over {calls} transfers took {issue_s * 1e3:.2f} ms"
+        assert still_running, f"handing over {calls} transfers took {issue_s * 1e3:.2f} ms: the held stream's kernel had ended"
 
 
 def test_proxy_window_monitor_sees_copy_engine_operations(vccl):
