@@ -163,7 +163,7 @@ def ring_corun(torch, P=8, nbytes=64 << 20, cu_grids=(8, 16, 32, 64, 256), steps
         saved = _set(opts or {})
         try:
             fn = lambda s=st: v.vccl_sendrecv(send, [nbytes] * P, to, recv, [nbytes] * P, frm, P, mode, s)
-            wall, _ = time_calls(torch, fn, steps, 2)
+            wall, _ = time_region(torch, fn, steps, 2)
             per = wall / steps
             moved = 2.0 * P * nbytes
             row = {"mode": name, "ms": per * 1e3, "GBps_effective": moved / per / 1e9,
@@ -214,8 +214,7 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
             while time.perf_counter() - t_warm < 0.05:
                 fn()
                 torch.cuda.synchronize()
-            wall, per = time_calls(torch, fn, k, 1)
-            t = wall / k
+            t = statistics.median(time_region(torch, fn, k, 1)[0] for _ in range(3)) / k
             row[name] = {"us": t * 1e6, "GBps": moved / t / 1e9}
             if co is not None:
                 row[name].update(co.beside(lambda s, m=mode: v.vccl_alltoall(send_p, recv_p, c, P, m, s),
