@@ -113,8 +113,14 @@ const char *vccl_last_error(void);
  *       "moe_unpack_variant" (row un-permute of vccl_moe_unpack: 0 = one workgroup per row,
  *       1 / 2 = one wavefront per 1 KiB tile with non-temporal / device-scope stores,
  *       3 = one wavefront per two tiles, device-scope stores),
- *       "fifo_chunk_bytes", "fifo_slots", "fifo_wg_per_conn",
- *       "fifo_spin_limit" (polls before a staged wait gives up).
+ *       "fifo_chunk_bytes", "fifo_slots", "fifo_wg_per_conn" (sender / receiver workgroup
+ *       pairs per connection, default 32; fewer when the
+ *       pairs of all connections would exceed two workgroups per compute unit),
+ *       "fifo_spin_limit" (polls before a staged wait gives up),
+ *       "fifo_scoped" (1, default: FIFO memory is read and written with device-scope
+ *       accesses and the chunk counters move relaxed; 0: plain accesses ordered by a
+ *       release on the sender's counter and an acquire on the receiver's poll, which
+ *       costs a cache write-back / invalidate per workgroup and chunk).
  * vccl_get_option writes the current value as text into out[0..cap). */
 int vccl_set_option(const char *key, const char *value);
 int vccl_get_option(const char *key, char *out, int cap);
@@ -134,9 +140,11 @@ int vccl_sendrecv(void *const *sendbuf, const uint64_t *sendbytes, const int *se
                   void *const *recvbuf, const uint64_t *recvbytes, const int *recv_from,
                   int P, vccl_mode mode, void *stream);
 
-/* Waits (on the host) for the most recent VCCL_MODE_CU_STAGED operation and returns
- * VCCL_ERR_TIMEOUT if one of its bounded device-side FIFO waits gave up (the data
- * is then incomplete), VCCL_OK otherwise. */
+/* Waits (on the host) for the VCCL_MODE_CU_STAGED operations issued so far and returns
+ * VCCL_ERR_TIMEOUT if, since the last time this was asked, one of them had a bounded
+ * device-side FIFO wait give up (its data is then incomplete), VCCL_OK otherwise.
+ * The staged call itself does not wait for the device: operations queue behind each
+ * other on the device (one at a time owns the FIFO), whatever streams they are on. */
 int vccl_sendrecv_staged_status(void);
 
 /* The receiver-owned handshake record of a SendRecv connection in copy-engine mode

@@ -386,6 +386,9 @@ int vccl_set_option(const char *key, const char *value) {
     } else if (k == "fifo_wg_per_conn") {
         if (!in(1, 64)) return fail(VCCL_ERR_ARG, "fifo_wg_per_conn must be 1..64");
         o.fifo_wg_per_conn = (int)x;
+    } else if (k == "fifo_scoped") {
+        if (!in(0, 1)) return fail(VCCL_ERR_ARG, "fifo_scoped must be 0 or 1");
+        o.fifo_scoped = (int)x;
     } else if (k == "fifo_spin_limit") {
         if (!in(1, 1ull << 40)) return fail(VCCL_ERR_ARG, "fifo_spin_limit must be 1..2^40");
         o.fifo_spin_limit = x;
@@ -426,6 +429,7 @@ int vccl_get_option(const char *key, char *out, int cap) {
     else if (k == "fifo_slots") v = o.fifo_slots;
     else if (k == "fifo_wg_per_conn") v = o.fifo_wg_per_conn;
     else if (k == "fifo_spin_limit") v = o.fifo_spin_limit;
+    else if (k == "fifo_scoped") v = o.fifo_scoped;
     else return fail(VCCL_ERR_ARG, "unknown option '%s'", key);
     snprintf(out, (size_t)cap, "%llu", v);
     return VCCL_OK;

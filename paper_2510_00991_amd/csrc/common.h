@@ -53,8 +53,9 @@ struct Options {
     int check = 0;
     uint64_t fifo_chunk_bytes = 512u << 10;
     int fifo_slots = 8;
-    int fifo_wg_per_conn = 8;
+    int fifo_wg_per_conn = 32;
     uint64_t fifo_spin_limit = 1ull << 24;
+    int fifo_scoped = 1;
 };
 
 // thread-local error message + status helper
@@ -122,10 +123,12 @@ int launch_uniform_alltoall(void *const *sendbuf, void *const *recvbuf, uint64_t
 struct FifoState {
     uint8_t *slots = nullptr;        // connections x fifo_slots x chunk bytes
     uint64_t *counters = nullptr;    // per (connection, lane-group): head, tail
-    uint32_t *status = nullptr;      // device word: non-zero when a bounded wait gave up
-    uint32_t *status_host = nullptr; // pinned mirror read after the stream is synchronised
-    struct FifoConn *conns_dev = nullptr;
-    struct FifoConn *conns_host = nullptr;
+    uint32_t *status = nullptr;      // device words: [0] non-zero while the running operation has given up,
+                                     // [1] number of operations that gave up since the allocation
+    uint32_t *errors_host = nullptr; // pinned word the status query copies [1] into
+    uint32_t errors_reported = 0;
+    struct FifoConn *conns_dev = nullptr;   // table for operations with more connections than fit
+    struct FifoConn *conns_host = nullptr;  // the kernel arguments (pinned staging)
     hipEvent_t done = nullptr;       // recorded behind the last staged operation
     size_t slots_bytes = 0;
     size_t counters_n = 0;

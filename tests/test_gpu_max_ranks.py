@@ -67,6 +67,29 @@ def test_alltoallv_256_ranks_random_layout(vccl):
         assert (host[int(roff[r]) + recv_np[r].size:int(roff[r + 1])] == SENTINEL).all()
 
 
+@pytest.mark.parametrize("P,mode", [(100, "staged"), (256, "staged"), (256, "cu"), (100, "ce")])
+def test_sendrecv_ring_many_ranks(vccl, P, mode):
+    """A ring over more connections than the staged kernel carries in its arguments
+    (the table path) and up to the rank limit; every rank a different message size."""
+    torch = require_gpu()
+    to, frm = wl.ring_peers(P)
+    sizes = [int(4096 + 1000 * (s % 7) + (s % 3)) for s in range(P)]
+    send_np = [wl.payload_bytes(4500 + P, s, sizes[s]) for s in range(P)]
+    rbytes = [sizes[frm[r]] for r in range(P)]
+    want = [np.full(rbytes[r] + 8, SENTINEL, dtype=np.uint8) for r in range(P)]
+    oracle.sendrecv(send_np, sizes, to, want, rbytes, frm)
+    send = [to_dev(torch, a) for a in send_np]
+    recv = [to_dev(torch, np.full(rbytes[r] + 8, SENTINEL, dtype=np.uint8)) for r in range(P)]
+    m = {"cu": vccl.MODE_CU, "ce": vccl.MODE_CE, "staged": vccl.MODE_CU_STAGED}[mode]
+    for _ in range(2):      # the second staged call reuses the table of the first
+        vccl.vccl_sendrecv(send, sizes, to, recv, rbytes, frm, P, m, stream_handle(torch))
+    if mode == "staged":
+        vccl.vccl_sendrecv_staged_status()
+    torch.cuda.synchronize()
+    for r in range(P):
+        assert_same(to_host(recv[r]), want[r], f"recv[{r}]")
+
+
 def test_rank_count_above_the_limit_is_rejected(vccl):
     torch = require_gpu()
     P = 257

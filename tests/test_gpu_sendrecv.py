@@ -1,4 +1,6 @@
 """GPU parity: SendRecv ring (direct on compute units, copy engines, staged FIFO)."""
+import contextlib
+
 import numpy as np
 import pytest
 
@@ -18,8 +20,23 @@ def vccl():
     v.vccl_finalize()
 
 
+MODES = ["cu", "ce", "staged", "staged_fenced"]
+
+
 def _modes(v):
-    return {"cu": v.MODE_CU, "ce": v.MODE_CE, "staged": v.MODE_CU_STAGED}
+    return {"cu": v.MODE_CU, "ce": v.MODE_CE, "staged": v.MODE_CU_STAGED, "staged_fenced": v.MODE_CU_STAGED}
+
+
+@contextlib.contextmanager
+def _protocol(v, mode):
+    """The staged mode has two synchronisation protocols: device-scope accesses to
+    the FIFO (default) and plain accesses ordered by release / acquire fences."""
+    saved = v.vccl_get_option("fifo_scoped")
+    v.vccl_set_option("fifo_scoped", 0 if mode == "staged_fenced" else 1)
+    try:
+        yield _modes(v)[mode]
+    finally:
+        v.vccl_set_option("fifo_scoped", saved)
 
 
 def _ring(torch, v, mode, sizes, misalign=0, stream=None):
@@ -39,22 +56,24 @@ def _ring(torch, v, mode, sizes, misalign=0, stream=None):
         assert_same(to_host(recv[r]), recv_np[r], f"recv[{r}]")
 
 
-@pytest.mark.parametrize("mode", ["cu", "ce", "staged"])
+@pytest.mark.parametrize("mode", MODES)
 def test_ring_small_and_ragged(vccl, mode):
     torch = require_gpu()
-    m = _modes(vccl)[mode]
-    _ring(torch, vccl, m, [100000, 0, 7, 65536, 1 << 20])
-    _ring(torch, vccl, m, [12345], misalign=0)
-    _ring(torch, vccl, m, [3 * 524288 + 17, 524288, 524287], misalign=0)
+    with _protocol(vccl, mode) as m:
+        _ring(torch, vccl, m, [100000, 0, 7, 65536, 1 << 20])
+        _ring(torch, vccl, m, [12345], misalign=0)
+        _ring(torch, vccl, m, [3 * 524288 + 17, 524288, 524287], misalign=0)
 
 
-@pytest.mark.parametrize("mode", ["cu", "ce", "staged"])
+@pytest.mark.parametrize("mode", MODES)
 def test_ring_unaligned_buffers(vccl, mode):
     torch = require_gpu()
-    _ring(torch, vccl, _modes(vccl)[mode], [700001, 33, 524288 + 1, 99999], misalign=5)
+    with _protocol(vccl, mode) as m:
+        _ring(torch, vccl, m, [700001, 33, 524288 + 1, 99999], misalign=5)
+        _ring(torch, vccl, m, [524288 * 2 + 3, 17, 524288 - 16, 4099], misalign=11)
 
 
-@pytest.mark.parametrize("mode", ["cu", "ce", "staged"])
+@pytest.mark.parametrize("mode", MODES)
 def test_config4_ring_p8_64m_full_size(vccl, mode):
     """8 stages, one 64 MiB activation (1 x 4096 x 8192 bf16, N(0,1)) per stage,
     512 KiB chunks through 8 FIFO slots in staged mode."""
@@ -66,11 +85,11 @@ def test_config4_ring_p8_64m_full_size(vccl, mode):
     send_np = [wl.normal_bf16_bits(wl.config_seed(4), s, n // 2).view(np.uint8) for s in range(P)]
     send = [to_dev(torch, a) for a in send_np]
     recv = [torch.full((n,), SENTINEL, dtype=torch.uint8, device="cuda") for _ in range(P)]
-    m = _modes(vccl)[mode]
-    vccl.vccl_sendrecv(send, [n] * P, to, recv, [n] * P, frm, P, m, stream_handle(torch))
-    if mode == "staged":
-        vccl.vccl_sendrecv_staged_status()
-    torch.cuda.synchronize()
+    with _protocol(vccl, mode) as m:
+        vccl.vccl_sendrecv(send, [n] * P, to, recv, [n] * P, frm, P, m, stream_handle(torch))
+        if m == vccl.MODE_CU_STAGED:
+            vccl.vccl_sendrecv_staged_status()
+        torch.cuda.synchronize()
     recv_np = [np.empty(n, dtype=np.uint8) for _ in range(P)]
     oracle.sendrecv(send_np, [n] * P, to, recv_np, [n] * P, frm)
     for r in range(P):
@@ -86,15 +105,20 @@ def test_ring_sdma_host_sync(vccl):
         vccl.vccl_set_option("ce_sync", "memops")
 
 
-def test_staged_equals_oracle_fifo_model(vccl):
-    """Different chunk / slot settings give the same bytes as the oracle's FIFO model."""
+@pytest.mark.parametrize("scoped", [1, 0])
+def test_staged_equals_oracle_fifo_model(vccl, scoped):
+    """Different chunk / slot settings give the same bytes as the oracle's FIFO model,
+    under either synchronisation protocol."""
     torch = require_gpu()
     n = 200000
     src_np = wl.payload_bytes(3, 0, n)
-    for chunk, slots, wg in ((4096, 1, 1), (8192, 3, 4), (65536, 8, 16)):
+    keys = ("fifo_chunk_bytes", "fifo_slots", "fifo_wg_per_conn", "fifo_scoped")
+    saved = {k: vccl.vccl_get_option(k) for k in keys}
+    for chunk, slots, wg in ((4096, 1, 1), (8192, 3, 4), (65536, 8, 16), (4096, 2, 64)):
         vccl.vccl_set_option("fifo_chunk_bytes", chunk)
         vccl.vccl_set_option("fifo_slots", slots)
         vccl.vccl_set_option("fifo_wg_per_conn", wg)
+        vccl.vccl_set_option("fifo_scoped", scoped)
         try:
             src = to_dev(torch, src_np)
             dst = to_dev(torch, np.full(n, SENTINEL, np.uint8))
@@ -105,9 +129,72 @@ def test_staged_equals_oracle_fifo_model(vccl):
             oracle.sendrecv_staged(src_np, want, n, chunk, slots)
             assert_same(to_host(dst), want, f"chunk {chunk} slots {slots}")
         finally:
-            vccl.vccl_set_option("fifo_chunk_bytes", 524288)
-            vccl.vccl_set_option("fifo_slots", 8)
-            vccl.vccl_set_option("fifo_wg_per_conn", 8)
+            for k, val in saved.items():
+                vccl.vccl_set_option(k, val)
+
+
+@pytest.mark.parametrize("scoped", [1, 0])
+def test_staged_transfers_in_a_row_never_read_a_stale_slot(vccl, scoped):
+    """The FIFO slots are reused by every chunk and every call.  Twelve rings in a row,
+    each with its own payload and each wrapping the 8 slots twice, all arrive whole: a
+    receiver that took a slot's bytes from a cache instead of from the sender's latest
+    write would deliver the previous chunk's or the previous call's data."""
+    torch = require_gpu()
+    P, n = 8, 8 << 20
+    to, frm = wl.ring_peers(P)
+    saved = vccl.vccl_get_option("fifo_scoped")
+    vccl.vccl_set_option("fifo_scoped", scoped)
+    try:
+        recv = [torch.full((n,), SENTINEL, dtype=torch.uint8, device="cuda") for _ in range(P)]
+        for it in range(12):
+            send = [to_dev(torch, wl.payload_bytes(4100 + it, s, n)) for s in range(P)]
+            vccl.vccl_sendrecv(send, [n] * P, to, recv, [n] * P, frm, P, vccl.MODE_CU_STAGED, stream_handle(torch))
+            vccl.vccl_sendrecv_staged_status()
+            torch.cuda.synchronize()
+            for r in range(P):
+                assert torch.equal(recv[r], send[frm[r]]), f"round {it}, recv[{r}]"
+            if it == 0:     # the device-side comparison itself, pinned to the oracle once
+                want = [np.zeros(n, np.uint8) for _ in range(P)]
+                oracle.sendrecv([to_host(t) for t in send], [n] * P, to, want, [n] * P, frm)
+                for r in range(P):
+                    assert_same(to_host(recv[r]), want[r], f"recv[{r}]")
+    finally:
+        vccl.vccl_set_option("fifo_scoped", saved)
+
+
+def test_staged_calls_do_not_wait_for_the_device(vccl):
+    """Staged calls on a stream that a long kernel holds back, and on a second stream,
+    all return while that kernel still runs; the operations then run one after the
+    other on the device (they share the FIFO) and every one arrives whole."""
+    torch = require_gpu()
+    P, n, calls = 4, 2 << 20, 4
+    to, frm = wl.ring_peers(P)
+    sends = [[to_dev(torch, wl.payload_bytes(4300 + i, s, n)) for s in range(P)] for i in range(calls)]
+    recvs = [[to_dev(torch, np.full(n, SENTINEL, np.uint8)) for _ in range(P)] for _ in range(calls)]
+    held, other = torch.cuda.Stream(), torch.cuda.Stream()
+    sink = torch.zeros(256 * 256, dtype=torch.float32, device="cuda")
+    # a first staged call so that the FIFO exists at the size the others need
+    vccl.vccl_sendrecv(sends[0], [n] * P, to, recvs[0], [n] * P, frm, P, vccl.MODE_CU_STAGED, stream_handle(torch))
+    vccl.vccl_sendrecv_staged_status()
+    for r in range(P):
+        recvs[0][r].fill_(SENTINEL)
+    torch.cuda.synchronize()
+    vccl.vccl_fma_probe(sink, 256, 256, 60000, int(held.cuda_stream))       # about 9 ms of compute
+    probe_done = torch.cuda.Event()
+    probe_done.record(held)
+    for i in range(calls):
+        st = held if i % 2 == 0 else other
+        vccl.vccl_sendrecv(sends[i], [n] * P, to, recvs[i], [n] * P, frm, P, vccl.MODE_CU_STAGED,
+                           int(st.cuda_stream))
+    still_running = not probe_done.query()
+    vccl.vccl_sendrecv_staged_status()
+    torch.cuda.synchronize()
+    assert still_running, "the staged calls waited for the kernel on the held stream"
+    for i in range(calls):
+        want = [np.zeros(n, np.uint8) for _ in range(P)]
+        oracle.sendrecv([to_host(t) for t in sends[i]], [n] * P, to, want, [n] * P, frm)
+        for r in range(P):
+            assert_same(to_host(recvs[i][r]), want[r], f"transfer {i}, recv[{r}]")
 
 
 def test_staged_wait_gives_up_when_its_poll_budget_runs_out(vccl):
