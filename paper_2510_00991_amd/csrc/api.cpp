@@ -89,7 +89,7 @@ struct Context {
     Options opt;
     std::mutex opt_mu;
     DescRing ring;
-    FifoState fifo;
+    FifoPool fifo;
     MoeScratch moe;
     Proxy *proxy = nullptr;
     std::atomic<uint64_t> ce_errors_reported{0};

@@ -130,9 +130,19 @@ struct FifoState {
     struct FifoConn *conns_dev = nullptr;   // table for operations with more connections than fit
     struct FifoConn *conns_host = nullptr;  // the kernel arguments (pinned staging)
     hipEvent_t done = nullptr;       // recorded behind the last staged operation
+    hipStream_t last_stream = nullptr;
     size_t slots_bytes = 0;
     size_t counters_n = 0;
     size_t conns_n = 0;
+    void destroy();
+};
+// Staged operations that are in flight together (different streams) each need FIFO
+// memory of their own, as every connection of a kernel-driven library has; a call takes
+// an idle state if there is one and otherwise queues behind the oldest.
+struct FifoPool {
+    static constexpr int kStates = 8;
+    FifoState st[kStates];
+    unsigned next = 0;
     std::mutex mu;
     void destroy();
 };
@@ -142,8 +152,8 @@ struct FifoConn {
     uint64_t bytes;
 };
 // Waits for the last staged operation and reports whether a bounded wait gave up.
-int fifo_last_status(FifoState &st, uint32_t *out);
-int launch_fifo(FifoState &st, const std::vector<FifoConn> &conns, const Options &opt,
+int fifo_last_status(FifoPool &pool, uint32_t *out);
+int launch_fifo(FifoPool &pool, const std::vector<FifoConn> &conns, const Options &opt,
                 int cu_count, hipStream_t stream);
 
 // ---- MoE pack

@@ -243,6 +243,12 @@ void FifoState::destroy() {
     conns_host = nullptr;
     slots_bytes = counters_n = conns_n = 0;
     errors_reported = 0;
+    last_stream = nullptr;
+}
+
+void FifoPool::destroy() {
+    std::lock_guard<std::mutex> lk(mu);
+    for (FifoState &s : st) s.destroy();
 }
 
 // Nothing here makes the calling thread wait for the device in the common case: a
@@ -251,7 +257,7 @@ void FifoState::destroy() {
 // arguments, and whether a wait gave up is counted on the device and read only when
 // the status is asked for.  The thread does wait when the FIFO has to grow or when an
 // operation has more connections than the kernel arguments hold.
-int launch_fifo(FifoState &st, const std::vector<FifoConn> &conns, const Options &opt, int cu_count,
+int launch_fifo(FifoPool &pool, const std::vector<FifoConn> &conns, const Options &opt, int cu_count,
                 hipStream_t stream) {
     const size_t nconn = conns.size();
     // Both sides of every pair must be able to be resident together; keep the grid
@@ -267,14 +273,27 @@ int launch_fifo(FifoState &st, const std::vector<FifoConn> &conns, const Options
     const size_t slots_bytes = nconn * (size_t)opt.fifo_slots * opt.fifo_chunk_bytes;
     const size_t counters_n = nconn * W * 2;
 
-    std::lock_guard<std::mutex> lk(st.mu);
+    std::lock_guard<std::mutex> lk(pool.mu);
+    // The state this stream used last (its operations follow each other anyway), else an
+    // idle one (never used, or its last operation has finished), else the oldest.
+    FifoState *pick = nullptr;
+    for (FifoState &cand : pool.st)
+        if (cand.done && cand.last_stream == stream) pick = &cand;
+    for (int i = 0; i < FifoPool::kStates && !pick; ++i)
+        if (!pool.st[i].done || hipEventQuery(pool.st[i].done) == hipSuccess) pick = &pool.st[i];
+    if (!pick) {
+        pick = &pool.st[pool.next];
+        pool.next = (pool.next + 1) % FifoPool::kStates;
+    }
+    pick->last_stream = stream;
+    FifoState &st = *pick;
     if (!st.done) {
         VCCL_HIP(hipEventCreateWithFlags(&st.done, hipEventDisableTiming));
         VCCL_HIP(hipEventRecord(st.done, stream));
     }
     if (!st.status) {
         VCCL_HIP(hipMalloc((void **)&st.status, 2 * sizeof(uint32_t)));
-        VCCL_HIP(hipMemset(st.status, 0, 2 * sizeof(uint32_t)));
+        VCCL_HIP(hipMemsetAsync(st.status, 0, 2 * sizeof(uint32_t), stream));   // ordered before the first use
         VCCL_HIP(hipHostMalloc((void **)&st.errors_host, sizeof(uint32_t), hipHostMallocDefault));
         *st.errors_host = 0;
     }
@@ -315,7 +334,7 @@ int launch_fifo(FifoState &st, const std::vector<FifoConn> &conns, const Options
     } else {
         for (size_t i = 0; i < nconn; ++i) a.inl[i] = conns[i];
     }
-    // One staged operation at a time owns the FIFO memory, whatever stream it is on.
+    // One staged operation at a time owns this state's FIFO memory, whatever stream it is on.
     VCCL_HIP(hipStreamWaitEvent(stream, st.done, 0));
     fifo_reset_kernel<<<dim3((uint32_t)((counters_n + 255) / 256)), dim3(256), 0, stream>>>(
         st.counters, (uint32_t)counters_n, st.status);
@@ -338,15 +357,17 @@ int launch_fifo(FifoState &st, const std::vector<FifoConn> &conns, const Options
 
 // Waits for the staged operations issued so far; *out is non-zero when one of them,
 // since the last time this was asked, ran out of polls.
-int fifo_last_status(FifoState &st, uint32_t *out) {
-    std::lock_guard<std::mutex> lk(st.mu);
+int fifo_last_status(FifoPool &pool, uint32_t *out) {
+    std::lock_guard<std::mutex> lk(pool.mu);
     *out = 0;
-    if (!st.done || !st.status) return VCCL_OK;
-    VCCL_HIP(hipEventSynchronize(st.done));
-    VCCL_HIP(hipMemcpy(st.errors_host, st.status + 1, sizeof(uint32_t), hipMemcpyDeviceToHost));
-    const uint32_t now = *st.errors_host;
-    *out = now != st.errors_reported ? 1u : 0u;
-    st.errors_reported = now;
+    for (FifoState &st : pool.st) {
+        if (!st.done || !st.status) continue;
+        VCCL_HIP(hipEventSynchronize(st.done));
+        VCCL_HIP(hipMemcpy(st.errors_host, st.status + 1, sizeof(uint32_t), hipMemcpyDeviceToHost));
+        const uint32_t now = *st.errors_host;
+        if (now != st.errors_reported) *out = 1u;
+        st.errors_reported = now;
+    }
     return VCCL_OK;
 }
 

@@ -344,7 +344,8 @@ def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000,
     activations go to the next stage and gradients to the previous one through
     vccl_sendrecv on per-link streams.  Reports the iteration time per transfer mode
     and without any transfer, and the paper's gain I = (T_n - T_v) / (T_v + alpha)
-    with alpha = 0 (no data-parallel traffic here), T_n the compute-unit path."""
+    with alpha = 0 (no data-parallel traffic here), T_n the compute-unit path (also given
+    with T_n the staged chunk-FIFO path, the kernel-driven two-step baseline)."""
     cu = v.vccl_device_cu_count()
     wg = max(1, cu // stages)
     sched = _schedule_1f1b(stages, micro)
@@ -436,17 +437,21 @@ def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000,
     rows = {}
     for name, mode, opts in (("no_transfer", None, {}), ("cu_path", v.MODE_CU, {}),
                              ("cu_path_capped_32wg", v.MODE_CU, {"cu_max_wg": 32, "cu_unroll": 8, "cu_threads": 256}),
+                             ("cu_staged_fifo", v.MODE_CU_STAGED, {}),
                              ("copy_engine", v.MODE_CE, {})):
         saved = _set(opts)
         try:
             iteration(mode)
             rows[name] = statistics.median(iteration(mode) for _ in range(reps)) * 1e3
+            if mode == v.MODE_CU_STAGED:
+                v.vccl_sendrecv_staged_status()
         finally:
             _set(saved)
     t_n, t_v = rows["cu_path"], rows["copy_engine"]
     return {"workload": f"1F1B, {stages} stages x {micro} microbatches, {act_bytes >> 20} MiB per transfer, "
                         f"FMA probe {wg} workgroups per stage, forward {fwd_iters} rounds",
             "iteration_ms": rows, "gain_I_pct": 100.0 * (t_n - t_v) / t_v,
+            "gain_I_pct_over_staged_fifo": 100.0 * (rows["cu_staged_fifo"] - t_v) / t_v,
             "overhead_vs_no_transfer_pct": {k: 100.0 * (val - rows["no_transfer"]) / rows["no_transfer"]
                                             for k, val in rows.items() if k != "no_transfer"}}
 

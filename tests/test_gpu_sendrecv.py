@@ -163,27 +163,24 @@ def test_staged_transfers_in_a_row_never_read_a_stale_slot(vccl, scoped):
 
 
 def test_staged_calls_do_not_wait_for_the_device(vccl):
-    """Staged calls on a stream that a long kernel holds back, and on a second stream,
-    all return while that kernel still runs; the operations then run one after the
-    other on the device (they share the FIFO) and every one arrives whole."""
+    """Staged calls on a stream that a long kernel holds back, and on eleven other
+    streams, all return while that kernel still runs.  Operations on different
+    streams get FIFO memory of their own while the library has some to give (eight at
+    a time) and queue behind each other beyond that; every one arrives whole."""
     torch = require_gpu()
-    P, n, calls = 4, 2 << 20, 4
+    P, n, calls = 4, 2 << 20, 14
     to, frm = wl.ring_peers(P)
     sends = [[to_dev(torch, wl.payload_bytes(4300 + i, s, n)) for s in range(P)] for i in range(calls)]
     recvs = [[to_dev(torch, np.full(n, SENTINEL, np.uint8)) for _ in range(P)] for _ in range(calls)]
-    held, other = torch.cuda.Stream(), torch.cuda.Stream()
+    streams = [torch.cuda.Stream() for _ in range(12)]
+    held = streams[0]
     sink = torch.zeros(256 * 256, dtype=torch.float32, device="cuda")
-    # a first staged call so that the FIFO exists at the size the others need
-    vccl.vccl_sendrecv(sends[0], [n] * P, to, recvs[0], [n] * P, frm, P, vccl.MODE_CU_STAGED, stream_handle(torch))
-    vccl.vccl_sendrecv_staged_status()
-    for r in range(P):
-        recvs[0][r].fill_(SENTINEL)
     torch.cuda.synchronize()
-    vccl.vccl_fma_probe(sink, 256, 256, 60000, int(held.cuda_stream))       # about 9 ms of compute
+    vccl.vccl_fma_probe(sink, 256, 256, 120000, int(held.cuda_stream))       # about 18 ms of compute
     probe_done = torch.cuda.Event()
     probe_done.record(held)
     for i in range(calls):
-        st = held if i % 2 == 0 else other
+        st = streams[i % len(streams)]
         vccl.vccl_sendrecv(sends[i], [n] * P, to, recvs[i], [n] * P, frm, P, vccl.MODE_CU_STAGED,
                            int(st.cuda_stream))
     still_running = not probe_done.query()
