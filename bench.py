@@ -256,6 +256,10 @@ def main():
             fx = lambda: v.vccl_alltoallv(packed, lay["sendcounts"], lay["sdispls"], rcv,
                                           lay["recvcounts"], lay["rdispls"], P, v.MODE_CU, st)
             wx, _ = time_region(torch, fx, 5, 2)
+            # the same exchange on the copy engines (incast on rank 0: 5 of the 7 GiB land there)
+            fxe = lambda: v.vccl_alltoallv(packed, lay["sendcounts"], lay["sdispls"], rcv,
+                                           lay["recvcounts"], lay["rdispls"], P, v.MODE_CE, st)
+            wxe, _ = time_region(torch, fxe, 2, 1)
             outp = [torch.empty(T * K * row, dtype=torch.uint8, device="cuda") for _ in range(P)]
             fu = lambda: v.vccl_moe_unpack(packed, ids, P, T, K, row, E, outp, st)
             wu, _ = time_region(torch, fu, 5, 2)
@@ -265,6 +269,8 @@ def main():
                 "pack_GBps": pack_bytes / (w / 5) / 1e9, "pack_ms": w / 5 * 1e3,
                 "exchange_GBps": 2.0 * float(lay["sendcounts"].sum()) / (wx / 5) / 1e9,
                 "exchange_ms": wx / 5 * 1e3,
+                "exchange_copy_engine_GBps": 2.0 * float(lay["sendcounts"].sum()) / (wxe / 2) / 1e9,
+                "exchange_copy_engine_ms": wxe / 2 * 1e3,
                 "recv_bytes_per_rank": [int(lay["recvcounts"][r].sum()) for r in range(P)]}
             # the same dispatch with one row per (token, destination rank)
             counts_r = torch.zeros((P, P), dtype=torch.int64, device="cuda")

@@ -99,6 +99,8 @@ const char *vccl_last_error(void);
  *       of the two stream operations with a one-lane helper kernel; "host" = no stream
  *       operation at all, the calling thread blocks until the copies are done),
  *       "ce_engines" (read-only: SDMA engines found),
+ *       "ce_engine_bytes" (read-only: bytes handed to each engine since vccl_init, comma
+ *       separated; the pieces of an operation go to the engine with the fewest bytes),
  *       "ce_errors" (read-only: copy-engine operations of which an engine refused a copy
  *       after the call had returned; the next copy-engine call then fails once with
  *       VCCL_ERR_HIP, and vccl_finalize returns VCCL_ERR_HIP if any went unreported),

@@ -169,8 +169,8 @@ def vccl_set_option(key: str, value) -> None:
 
 
 def vccl_get_option(key: str) -> str:
-    buf = ctypes.create_string_buffer(64)
-    _check(load().vccl_get_option(key.encode(), buf, 64))
+    buf = ctypes.create_string_buffer(512)
+    _check(load().vccl_get_option(key.encode(), buf, 512))
     return buf.value.decode()
 
 

@@ -331,7 +331,8 @@ int vccl_set_option(const char *key, const char *value) {
         else return fail(VCCL_ERR_ARG, "ce_kind must be 'sdma', 'hip_nocu' or 'hip_default', got '%s'", value);
         return VCCL_OK;
     }
-    if (k == "ce_engines" || k == "ce_errors") return fail(VCCL_ERR_ARG, "%s is read-only", key);
+    if (k == "ce_engines" || k == "ce_errors" || k == "ce_engine_bytes")
+        return fail(VCCL_ERR_ARG, "%s is read-only", key);
     if (k == "ce_sync") {
         if (!strcmp(value, "memops")) o.ce_sync_host = 0;
         else if (!strcmp(value, "host")) o.ce_sync_host = 1;
@@ -411,6 +412,13 @@ int vccl_get_option(const char *key, char *out, int cap) {
         return VCCL_OK;
     } else if (k == "ce_sync") {
         snprintf(out, (size_t)cap, "%s", o.ce_sync_host ? "host" : "memops");
+        return VCCL_OK;
+    } else if (k == "ce_engine_bytes") {
+        std::string txt;
+        for (int i = 0; i < proxy_engine_count(c->proxy); ++i)
+            txt += (i ? "," : "") + std::to_string((unsigned long long)proxy_engine_bytes(c->proxy, i));
+        if ((int)txt.size() + 1 > cap) return fail(VCCL_ERR_ARG, "ce_engine_bytes needs %zu characters", txt.size() + 1);
+        snprintf(out, (size_t)cap, "%s", txt.c_str());
         return VCCL_OK;
     } else if (k == "ce_engines") v = (unsigned long long)proxy_engine_count(c->proxy);
     else if (k == "ce_errors") v = (unsigned long long)proxy_sdma_errors(c->proxy);

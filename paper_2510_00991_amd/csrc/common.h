@@ -226,5 +226,6 @@ uint64_t proxy_sdma_errors(Proxy *p);
 vccl_monitor *proxy_monitor(Proxy *p, int primitive);
 void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t *issue_ns);
 int proxy_cpu_time(Proxy *p, uint64_t *sender_ns, uint64_t *receiver_ns);
+uint64_t proxy_engine_bytes(Proxy *p, int engine);
 
 }  // namespace vccl

@@ -52,7 +52,8 @@ namespace vccl {
 namespace {
 constexpr int kMaxStreams = 8;
 constexpr int kMaxEngines = 16;
-constexpr uint64_t kMinPiece = 1u << 20;   // large copies are cut no finer than this
+constexpr uint64_t kMinPiece = 1u << 20;   // copies are cut no finer than this
+constexpr uint64_t kMaxPiece = 16u << 20;  // and a piece is no longer than this (engines reach their rate from there)
 
 struct RegInfo {  // one per receiving rank
     std::atomic<void *> receiverRegAddr{nullptr};
@@ -111,6 +112,7 @@ public:
     size_t in_flight = 0;        // queued + waiting + pending
     RegInfo reg[VCCL_MAX_RANKS];
     std::atomic<uint64_t> n_ops{0}, n_copies{0}, n_bytes{0}, issue_ns{0}, sdma_errors{0};
+    std::atomic<uint64_t> engine_bytes[kMaxEngines] = {};   // bytes handed to each engine so far
     // sdma back end
     bool sdma_ok = false;
     std::string sdma_why;
@@ -287,23 +289,23 @@ void Proxy::put_ref(Op *op) {  // mu held
     }
 }
 
-// Few large copies are cut so that every lane (stream or engine) gets a share.
+// Copies are cut into pieces of at most clamp(total / (2 * lanes), 1 MiB, 16 MiB) so
+// that the lanes (streams or engines) can be loaded evenly by bytes, whatever the mix
+// of sizes: a skewed AlltoAllv is a few very large copies among many small ones.
 std::vector<CeCopy> Proxy::expand(const Op *op, size_t lanes) {
     std::vector<CeCopy> work;
-    size_t live = 0;
-    for (const CeCopy &c : op->copies)
-        if (c.bytes) ++live;
-    size_t pieces = 1;
-    if (live && live < 2 * lanes) pieces = (2 * lanes + live - 1) / live;
+    uint64_t total = 0;
+    for (const CeCopy &c : op->copies) total += c.bytes;
+    uint64_t target = total / (2 * (lanes ? lanes : 1));
+    if (target < kMinPiece) target = kMinPiece;
+    if (target > kMaxPiece) target = kMaxPiece;
     for (const CeCopy &c : op->copies) {
         if (c.bytes == 0) continue;
         // A SendRecv copy writes to the address the receiver published in its record.
         uint8_t *dst_base = c.receiver >= 0
             ? (uint8_t *)reg[c.receiver].receiverRegAddr.load(std::memory_order_acquire)
             : (uint8_t *)c.dst;
-        size_t k = pieces;
-        if (c.bytes < kMinPiece * k) k = (size_t)(c.bytes / kMinPiece);
-        if (k < 1) k = 1;
+        const uint64_t k = (c.bytes + target - 1) / target;
         const uint64_t per = ((c.bytes + k - 1) / k + 255u) & ~(uint64_t)255u;
         for (uint64_t off = 0; off < c.bytes; off += per) {
             const uint64_t n = c.bytes - off < per ? c.bytes - off : per;
@@ -384,8 +386,17 @@ bool Proxy::issue_sdma(Op *op) {
     for (auto &c : op->conns) reg[c.first].copyStarted.store(c.second, std::memory_order_release);
     hsa_signal_store_relaxed(op->left, (hsa_signal_value_t)work.size());
     uint64_t bytes = 0;
+    // Each piece goes to the engine with the fewest bytes so far (ties: rotate, so that
+    // equal pieces still spread round-robin and small operations do not all start on
+    // engine 0).
+    uint64_t load[kMaxEngines] = {};
     for (const CeCopy &w : work) {
-        const uint32_t bit = engine_bit[next_engine++ % (unsigned)ne];
+        int best = (int)(next_engine++ % (unsigned)ne);
+        for (int i = 0; i < ne; ++i)
+            if (load[i] < load[best]) best = i;
+        load[best] += w.bytes;
+        engine_bytes[best].fetch_add(w.bytes, std::memory_order_relaxed);
+        const uint32_t bit = engine_bit[best];
         hsa_status_t st = hsa_amd_memory_async_copy_on_engine(
             w.dst, agent, w.src, agent, w.bytes, 0, nullptr, op->left, (hsa_amd_sdma_engine_id_t)bit, true);
         if (st != HSA_STATUS_SUCCESS) {   // keep the count right so that the op still completes
@@ -538,6 +549,10 @@ bool proxy_sdma_available(Proxy *p, const char **why) {
 }
 
 int proxy_engine_count(Proxy *p) { return p->nengines; }
+
+uint64_t proxy_engine_bytes(Proxy *p, int engine) {
+    return engine >= 0 && engine < p->nengines ? p->engine_bytes[engine].load() : 0;
+}
 
 int proxy_drain(Proxy *p) {
     std::unique_lock<std::mutex> lk(p->mu);

@@ -282,6 +282,32 @@ def test_skewed_layout_is_cut_into_pieces(vccl, mode):
     _run_v(torch, vccl, lay, send_np, _mode(vccl, mode))
 
 
+def test_copy_engines_share_a_skewed_exchange_by_bytes(vccl):
+    """An AlltoAllv in which one destination takes most of the bytes (the incast of a
+    skewed MoE dispatch): the copy-engine path cuts the long segments and hands every
+    piece to the engine with the fewest bytes, so no engine ends up with much more than
+    its share (round-robin over the segments put all the long ones on two engines)."""
+    torch = require_gpu()
+    P = 8
+    counts = np.full((P, P), 1 << 20, dtype=np.uint64)
+    counts[:, 0] = 96 << 20                       # everyone sends 96 MiB to rank 0
+    sd = np.zeros((P, P), dtype=np.uint64)
+    rd = np.zeros((P, P), dtype=np.uint64)
+    sd[:, 1:] = np.cumsum(counts[:, :-1], axis=1)
+    rc = counts.T.copy()
+    rd[:, 1:] = np.cumsum(rc[:, :-1], axis=1)
+    lay = {"sendcounts": counts, "sdispls": sd, "recvcounts": rc, "rdispls": rd,
+           "send_sizes": counts.sum(axis=1), "recv_sizes": rc.sum(axis=1)}
+    send_np = [wl.payload_bytes(15, s, int(lay["send_sizes"][s])) for s in range(P)]
+    before = [int(x) for x in vccl.vccl_get_option("ce_engine_bytes").split(",")]
+    _run_v(torch, vccl, lay, send_np, vccl.MODE_CE)
+    after = [int(x) for x in vccl.vccl_get_option("ce_engine_bytes").split(",")]
+    got = np.array(after) - np.array(before)
+    assert got.sum() == int(counts.sum())
+    assert len(got) == int(vccl.vccl_get_option("ce_engines"))
+    assert got.max() <= 1.25 * got.mean(), got.tolist()
+
+
 @pytest.mark.parametrize("opts", [{"cu_max_wg": 1}, {"cu_max_wg": 8}, {"cu_max_wg": 100},
                                   {"cu_wg_per_cu": 1}, {"cu_wg_per_cu": 8}])
 def test_capped_grid_strides_over_descriptors_and_tiles(vccl, opts):
