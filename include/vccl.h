@@ -66,13 +66,14 @@ typedef enum {
 #define VCCL_MAX_RANKS 256
 
 /* Create the library context on `device`: internal copy streams and events, the
- * descriptor staging ring and the host proxy thread of the copy-engine path
- * (the CPU proxy of Section 3.2).  max_ranks bounds P of later calls
+ * descriptor staging ring and the two host proxy threads of the copy-engine path
+ * (the CPU proxy of Section 3.2, which drives the engines, and the receiving side of
+ * the SendRecv handshake).  max_ranks bounds P of later calls
  * (1 .. VCCL_MAX_RANKS).  Calling it again after vccl_finalize is allowed;
  * calling it twice without is VCCL_ERR_ARG. */
 int vccl_init(int device, int max_ranks);
 
-/* Wait for every operation handed to the library, stop the proxy thread and free
+/* Wait for every operation handed to the library, stop the proxy threads and free
  * everything the library owns.  Caller buffers are untouched. */
 int vccl_finalize(void);
 
