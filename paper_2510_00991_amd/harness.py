@@ -190,18 +190,24 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
     bandwidth and the probe's slowdown beside each."""
     import workloads as wl
 
-    sizes = sizes or [4096 << k for k in range(11)]
+    sizes = [c for c in (sizes or [4096 << k for k in range(11)]) if P * P * c <= max_bytes_per_side]
     co = CoRun(torch) if with_corun else None
     st = int(torch.cuda.current_stream().cuda_stream)
     rows = []
+    # The buffers of every size are allocated before the first measurement and freed
+    # after the last (about 64 GiB in all): after device memory has been freed the copy
+    # engines of this device run at about 60 % of their rate for a second or two, which
+    # would distort the size measured next.
+    bufs = {}
     for c in sizes:
-        if P * P * c > max_bytes_per_side:
-            continue
         send = [torch.empty(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
         recv = [torch.empty(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
         for s in range(P):     # seeded payload, first 1 MiB of each buffer (timing does not depend on values)
             n = min(P * c, 1 << 20)
             send[s][:n].copy_(torch.from_numpy(wl.payload_bytes(wl.config_seed(5), s, n)))
+        bufs[c] = (send, recv)
+    for c in sizes:
+        send, recv = bufs[c]
         send_p, recv_p = v.pointer_array(send), v.pointer_array(recv)   # marshalled once, not per call
         moved = 2.0 * P * P * c
         row = {"bytes_per_peer": c, "total_sent_MiB": P * P * c / (1 << 20)}
@@ -220,8 +226,8 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
                 row[name].update(co.beside(lambda s, m=mode: v.vccl_alltoall(send_p, recv_p, c, P, m, s),
                                            moved, t, reps=6))
         rows.append(row)
-        del send, recv
-        torch.cuda.empty_cache()
+    del send, recv, bufs
+    torch.cuda.empty_cache()
     return {"workload": f"AlltoAll sweep, P={P}, per-peer 4 KiB..4 MiB", "rows": rows}
 
 
