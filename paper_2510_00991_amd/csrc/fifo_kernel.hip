@@ -24,8 +24,7 @@ namespace vccl {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kFifoThreads = 256;
-
-constexpr int kFifoInlineConns = 64;
+constexpr int kFifoInlineConns = 64;   // connections that travel in the kernel arguments
 
 struct FifoArgs {
     const FifoConn *conns;   // device array, or null: the connections are in `inl`
@@ -211,9 +210,11 @@ __global__ __launch_bounds__(kFifoThreads) void fifo_sendrecv_kernel(FifoArgs a)
             else copy_range(slot, c.dst + off, b0, b1);
         }
         // Every lane waits for its own loads and stores to finish, the workgroup meets,
-        // then one lane moves the counter.  The sender's release writes the slot data
-        // back so that a receiver on another XCD sees it; the receiver only has to have
-        // finished reading the slot, so its counter store is relaxed.
+        // then one lane moves the counter.  Scoped: the sender's stores were written
+        // through before they were acknowledged, so a relaxed counter store is enough.
+        // Fenced: the sender's release writes the slot data back so that a receiver on
+        // another XCD sees it.  The receiver only has to have finished reading the slot,
+        // so its counter store is relaxed either way.
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (threadIdx.x == 0) {
