@@ -38,6 +38,10 @@ struct FifoArgs {
     uint32_t W;
 };
 
+__global__ void fifo_zero_words_kernel(uint32_t *words, uint32_t n) {
+    if (threadIdx.x < n) words[threadIdx.x] = 0;
+}
+
 __global__ void fifo_reset_kernel(uint64_t *counters, uint32_t n, uint32_t *status) {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) counters[i] = 0;
@@ -294,7 +298,8 @@ int launch_fifo(FifoPool &pool, const std::vector<FifoConn> &conns, const Option
     }
     if (!st.status) {
         VCCL_HIP(hipMalloc((void **)&st.status, 2 * sizeof(uint32_t)));
-        VCCL_HIP(hipMemsetAsync(st.status, 0, 2 * sizeof(uint32_t), stream));   // ordered before the first use
+        fifo_zero_words_kernel<<<dim3(1), dim3(64), 0, stream>>>(st.status, 2);   // ordered before the first use
+        VCCL_HIP(hipGetLastError());
         VCCL_HIP(hipHostMalloc((void **)&st.errors_host, sizeof(uint32_t), hipHostMallocDefault));
         *st.errors_host = 0;
     }
