@@ -43,7 +43,7 @@ def cpu_baseline(P, c, budget_s=12.0):
     oracle.alltoall(send, recv, c, threads=cores)        # touch pages
     t_end = time.perf_counter() + budget_s
     times = []
-    while time.perf_counter() < t_end and len(times) < 20:
+    while time.perf_counter() < t_end and len(times) < 60:     # about 2 s on 8 cores: 10-20 s of processor time
         t0 = time.perf_counter()
         oracle.alltoall(send, recv, c, threads=cores)
         times.append(time.perf_counter() - t0)
