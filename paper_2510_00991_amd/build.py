@@ -48,23 +48,5 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
-def build_native_check(verbose: bool = True) -> str:
-    """Compile tests/native/gpu_native.c, the plain-C program that drives the library
-    without Python (it links libvccl.so, the C oracle and the HIP runtime)."""
-    src = os.path.join(ROOT, "tests", "native", "gpu_native.c")
-    exe = os.path.join(ROOT, "tests", "native", "gpu_native")
-    oracle_dir = os.path.join(ROOT, "oracle")
-    cmd = ["gcc", "-std=c11", "-O1", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__",
-           "-I", os.path.join(ROOT, "include"), "-I", "/opt/rocm/include", src, "-o", exe,
-           "-L", HERE, "-lvccl", "-L", oracle_dir, "-lvccl_oracle", "-L", "/opt/rocm/lib", "-lamdhip64",
-           # found relative to the program, wherever the tree is copied to
-           "-Wl,-rpath,$ORIGIN/../../paper_2510_00991_amd", "-Wl,-rpath,$ORIGIN/../../oracle",
-           "-Wl,-rpath,/opt/rocm/lib"]
-    subprocess.check_call(cmd)
-    if verbose:
-        print(exe)
-    return exe
-
-
 if __name__ == "__main__":
     print(build())

@@ -18,8 +18,10 @@ def test_native_c_program(sync):
     require_gpu()
     if not os.path.exists(EXE):
         # normally built by build(); one gcc call on a C file if the tree arrived without it
-        from paper_2510_00991_amd import build as b
-        b.build_native_check(verbose=False)
+        import sys
+        sys.path.insert(0, os.path.dirname(EXE))
+        import build_native
+        build_native.build_native_check(verbose=False)
     rv = subprocess.run([EXE, sync], capture_output=True, text=True, timeout=120)
     assert rv.returncode == 0, rv.stdout[-2000:] + rv.stderr[-2000:]
     assert "native ok" in rv.stdout and f"ordering: {sync}" in rv.stdout
