@@ -343,7 +343,22 @@ def _schedule_1f1b(stages, micro):
     return out
 
 
-def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000, reps=5):
+def pipeline_links(stages):
+    """Peer tables of the pipeline emulation: every link is a connection of its own (its
+    own pair of virtual ranks), as between real pipeline stages.  Forward links use ranks
+    0..S-1 (stage i sends from rank i to rank i+1), backward links ranks S..2S-1 (stage i
+    sends from rank S+i to rank S+i-1).  Sharing one pair of ranks would queue all links
+    behind each other, because a connection carries its transfers in the order they were
+    posted.  Returns (ranks, (send_to, recv_from) of a forward transfer, the same of a
+    backward transfer)."""
+    S = stages
+    up = [(r + 1) % S if r < S else S + (r - S + 1) % S for r in range(2 * S)]
+    down = [(r - 1) % S if r < S else S + (r - S - 1) % S for r in range(2 * S)]
+    return 2 * S, (up, down), (down, up)
+
+
+def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000, reps=5, modes=None,
+                  payload=None):
     """Emulation of the paper's pipeline figure (1F1B, 8 microbatches, 4 workers) on
     one device: every stage computes on its own stream with the FMA probe sized to a
     quarter of the compute units (forward = fwd_iters rounds, backward twice that),
@@ -351,7 +366,17 @@ def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000,
     vccl_sendrecv on per-link streams.  Reports the iteration time per transfer mode
     and without any transfer, and the paper's gain I = (T_n - T_v) / (T_v + alpha)
     with alpha = 0 (no data-parallel traffic here), T_n the compute-unit path (also given
-    with T_n the staged chunk-FIFO path, the kernel-driven two-step baseline)."""
+    with T_n the staged chunk-FIFO path, the kernel-driven two-step baseline).
+
+    `modes` restricts the run to some of "no_transfer", "cu_path", "cu_path_capped_32wg",
+    "cu_staged_fifo", "copy_engine".  With `payload` (a function (kind, stage, microbatch)
+    -> act_bytes uint8 values, kind "F" for the activation stage `stage` sends forward, "B"
+    for the gradient it sends backward) the run carries real data: a stage's step writes
+    its payload into the send buffer on the compute stream behind its compute kernel, and
+    the receiving stage copies what has arrived out of its receive buffer at the start of
+    the step that consumes it, on its own compute stream.  The result then holds, per
+    mode, "arrivals": {(kind, receiving stage, microbatch): bytes as a CPU tensor}, every
+    transfer with a buffer of its own."""
     cu = v.vccl_device_cu_count()
     wg = max(1, cu // stages)
     sched = _schedule_1f1b(stages, micro)
@@ -359,42 +384,50 @@ def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000,
     link_f = [torch.cuda.Stream() for _ in range(stages)]     # stage i -> i+1
     link_b = [torch.cuda.Stream() for _ in range(stages)]     # stage i -> i-1
     outs = [torch.zeros(wg * 256, dtype=torch.float32, device="cuda") for _ in range(stages)]
-    src_f = [[torch.zeros(act_bytes, dtype=torch.uint8, device="cuda") for _ in range(2)] for _ in range(stages)]
-    dst_f = [[torch.zeros(act_bytes, dtype=torch.uint8, device="cuda") for _ in range(2)] for _ in range(stages)]
-    src_b = [[torch.zeros(act_bytes, dtype=torch.uint8, device="cuda") for _ in range(2)] for _ in range(stages)]
-    dst_b = [[torch.zeros(act_bytes, dtype=torch.uint8, device="cuda") for _ in range(2)] for _ in range(stages)]
-    null = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    nbuf = micro if payload is not None else 2
 
-    # Every link is a connection of its own (its own pair of virtual ranks), as between real
-    # pipeline stages: forward links use ranks 0..S-1 (i -> i+1), backward links S..2S-1
-    # (S+i -> S+i-1).  Sharing one pair of ranks would queue all links behind each other,
-    # because a connection carries its transfers in the order they were posted.
+    def bufs():
+        return [[torch.zeros(act_bytes, dtype=torch.uint8, device="cuda") for _ in range(nbuf)]
+                for _ in range(stages)]
+
+    src_f, dst_f, src_b, dst_b = bufs(), bufs(), bufs(), bufs()
+    null = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    pay = {}
+    if payload is not None:
+        for i in range(stages):
+            for m in range(micro):
+                if i < stages - 1:
+                    pay[("F", i, m)] = torch.as_tensor(payload("F", i, m), dtype=torch.uint8).cuda()
+                if i > 0:
+                    pay[("B", i, m)] = torch.as_tensor(payload("B", i, m), dtype=torch.uint8).cuda()
+
+    PR, fwd_tables, bwd_tables = pipeline_links(stages)
     S = stages
-    PR = 2 * S
-    ring_up = [(r + 1) % S if r < S else S + (r - S + 1) % S for r in range(PR)]
-    ring_up_inv = [(r - 1) % S if r < S else S + (r - S - 1) % S for r in range(PR)]
-    ring_down = [(r - 1) % S if r < S else S + (r - S - 1) % S for r in range(PR)]
-    ring_down_inv = ring_up
 
     def transfer(mode, src, dst, stream, stage, forward):
         sendbuf, recvbuf = [null] * PR, [null] * PR
         sb, rb = [0] * PR, [0] * PR
         if forward:
             s_rank, r_rank = stage, stage + 1
-            to, frm = ring_up, ring_up_inv
+            to, frm = fwd_tables
         else:
             s_rank, r_rank = S + stage, S + stage - 1
-            to, frm = ring_down, ring_down_inv
+            to, frm = bwd_tables
         sendbuf[s_rank], sb[s_rank] = src, act_bytes
         recvbuf[r_rank], rb[r_rank] = dst, act_bytes
         v.vccl_sendrecv(sendbuf, sb, to, recvbuf, rb, frm, PR, mode, int(stream.cuda_stream))
 
-    def iteration(mode):
+    def iteration(mode, got=None):
         """Enqueue one whole iteration; returns the wall time from the first launch to
         the completion of every stream."""
         done = {}                      # (kind, stage, m) -> event after the step's compute
         arrived = {}                   # (kind, stage, m) -> event after the step's input has landed
         pos = [0] * stages
+        if payload is not None:
+            for group in (dst_f, dst_b, src_f, src_b):
+                for per_stage in group:
+                    for t in per_stage:
+                        t.fill_(0xA5)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         progress = True
@@ -417,21 +450,30 @@ def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000,
                         comp[i].wait_event(done[dep])
                     elif need is not None:
                         comp[i].wait_event(arrived[need])
+                        if got is not None:     # what this step consumes, as the compute stream sees it
+                            inbox = dst_f[i - 1][m % nbuf] if kind == "F" else dst_b[i + 1][m % nbuf]
+                            with torch.cuda.stream(comp[i]):
+                                got[need] = inbox.clone()
                     v.vccl_fma_probe(outs[i], wg, 256, fwd_iters * (1 if kind == "F" else 2),
                                      int(comp[i].cuda_stream))
+                    sends = mode is not None and ((kind == "F" and i < stages - 1) or (kind == "B" and i > 0))
+                    if sends and payload is not None:   # the step's result, written behind its compute
+                        outbox = src_f[i][m % nbuf] if kind == "F" else src_b[i][m % nbuf]
+                        with torch.cuda.stream(comp[i]):
+                            outbox.copy_(pay[(kind, i, m)], non_blocking=True)
                     e = torch.cuda.Event()
                     e.record(comp[i])
                     done[(kind, i, m)] = e
                     if mode is not None:
                         if kind == "F" and i < stages - 1:
                             link_f[i].wait_event(e)
-                            transfer(mode, src_f[i][m % 2], dst_f[i][m % 2], link_f[i], i, True)
+                            transfer(mode, src_f[i][m % nbuf], dst_f[i][m % nbuf], link_f[i], i, True)
                             a = torch.cuda.Event()
                             a.record(link_f[i])
                             arrived[("F", i + 1, m)] = a
                         if kind == "B" and i > 0:
                             link_b[i].wait_event(e)
-                            transfer(mode, src_b[i][m % 2], dst_b[i][m % 2], link_b[i], i, False)
+                            transfer(mode, src_b[i][m % nbuf], dst_b[i][m % nbuf], link_b[i], i, False)
                             a = torch.cuda.Event()
                             a.record(link_b[i])
                             arrived[("B", i - 1, m)] = a
@@ -440,26 +482,40 @@ def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000,
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
-    rows = {}
-    for name, mode, opts in (("no_transfer", None, {}), ("cu_path", v.MODE_CU, {}),
-                             ("cu_path_capped_32wg", v.MODE_CU, {"cu_max_wg": 32, "cu_unroll": 8, "cu_threads": 256}),
-                             ("cu_staged_fifo", v.MODE_CU_STAGED, {}),
-                             ("copy_engine", v.MODE_CE, {})):
+    table = (("no_transfer", None, {}), ("cu_path", v.MODE_CU, {}),
+             ("cu_path_capped_32wg", v.MODE_CU, {"cu_max_wg": 32, "cu_unroll": 8, "cu_threads": 256}),
+             ("cu_staged_fifo", v.MODE_CU_STAGED, {}),
+             ("copy_engine", v.MODE_CE, {}))
+    rows, arrivals = {}, {}
+    for name, mode, opts in table:
+        if modes is not None and name not in modes:
+            continue
         saved = _set(opts)
         try:
-            iteration(mode)
-            rows[name] = statistics.median(iteration(mode) for _ in range(reps)) * 1e3
+            if payload is not None and mode is not None:
+                got = {}
+                rows[name] = iteration(mode, got) * 1e3
+                arrivals[name] = {k: t.cpu() for k, t in got.items()}
+            else:
+                iteration(mode)
+                rows[name] = statistics.median(iteration(mode) for _ in range(reps)) * 1e3
             if mode == v.MODE_CU_STAGED:
                 v.vccl_sendrecv_staged_status()
         finally:
             _set(saved)
-    t_n, t_v = rows["cu_path"], rows["copy_engine"]
-    return {"workload": f"1F1B, {stages} stages x {micro} microbatches, {act_bytes >> 20} MiB per transfer, "
-                        f"FMA probe {wg} workgroups per stage, forward {fwd_iters} rounds",
-            "iteration_ms": rows, "gain_I_pct": 100.0 * (t_n - t_v) / t_v,
-            "gain_I_pct_over_staged_fifo": 100.0 * (rows["cu_staged_fifo"] - t_v) / t_v,
-            "overhead_vs_no_transfer_pct": {k: 100.0 * (val - rows["no_transfer"]) / rows["no_transfer"]
-                                            for k, val in rows.items() if k != "no_transfer"}}
+    out = {"workload": f"1F1B, {stages} stages x {micro} microbatches, {act_bytes} bytes per transfer, "
+                       f"FMA probe {wg} workgroups per stage, forward {fwd_iters} rounds",
+           "iteration_ms": rows}
+    if "cu_path" in rows and "copy_engine" in rows:
+        out["gain_I_pct"] = 100.0 * (rows["cu_path"] - rows["copy_engine"]) / rows["copy_engine"]
+    if "cu_staged_fifo" in rows and "copy_engine" in rows:
+        out["gain_I_pct_over_staged_fifo"] = 100.0 * (rows["cu_staged_fifo"] - rows["copy_engine"]) / rows["copy_engine"]
+    if "no_transfer" in rows:
+        out["overhead_vs_no_transfer_pct"] = {k: 100.0 * (val - rows["no_transfer"]) / rows["no_transfer"]
+                                              for k, val in rows.items() if k != "no_transfer"}
+    if payload is not None:
+        out["arrivals"] = arrivals
+    return out
 
 
 def main(argv=None):

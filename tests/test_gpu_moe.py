@@ -20,6 +20,8 @@ def vccl():
 
 
 def _dispatch(torch, v, P, T, K, E, row, seed, mode, x_np=None, ids_np=None):
+    """mode: one exchange mode, or a tuple of modes that all run behind the same pack."""
+    modes = mode if isinstance(mode, tuple) else (mode,)
     epr = E // P
     if x_np is None:
         x_np = [wl.payload_bytes(seed, s, T * row) for s in range(P)]
@@ -50,15 +52,17 @@ def _dispatch(torch, v, P, T, K, E, row, seed, mode, x_np=None, ids_np=None):
     for k in want_lay:
         assert np.array_equal(lay[k], want_lay[k]), k
     rsz = [int(lay["recvcounts"][r].sum()) for r in range(P)]
-    recv = [torch.full((rsz[r] + 16,), SENTINEL, dtype=torch.uint8, device="cuda") for r in range(P)]
-    v.vccl_alltoallv(packed, lay["sendcounts"], lay["sdispls"], recv, lay["recvcounts"],
-                     lay["rdispls"], P, mode, st)
-    torch.cuda.synchronize()
     recv_np = [np.full(rsz[r] + 16, SENTINEL, dtype=np.uint8) for r in range(P)]
     oracle.alltoallv(want_packed, want_lay["sendcounts"], want_lay["sdispls"], recv_np,
                      want_lay["recvcounts"], want_lay["rdispls"], threads=8)
-    for r in range(P):
-        assert_same(to_host(recv[r]), recv_np[r], f"recv[{r}]")
+    for m in modes:
+        recv = [torch.full((rsz[r] + 16,), SENTINEL, dtype=torch.uint8, device="cuda") for r in range(P)]
+        v.vccl_alltoallv(packed, lay["sendcounts"], lay["sdispls"], recv, lay["recvcounts"],
+                         lay["rdispls"], P, m, st)
+        torch.cuda.synchronize()
+        for r in range(P):
+            assert_same(to_host(recv[r]), recv_np[r], f"recv[{r}], mode {m}")
+        del recv
     return rsz
 
 
@@ -508,16 +512,97 @@ def test_unpack_leaves_rows_of_dropped_pairs_untouched(vccl):
 
 def test_config3_moe_dispatch_full_size(vccl):
     """P = 8, 8192 tokens x 7168 bf16 N(0,1) per rank, top-8 of 256 experts with
-    Zipf(1.2) ids: pack (65 536 rows of 14 336 B per rank) then AlltoAllv."""
+    Zipf(1.2) ids: pack (65 536 rows of 14 336 B per rank) then AlltoAllv, on the
+    compute units and on the copy engines.  The copy-engine exchange of this shape is
+    the one with destination offsets beyond 4 GiB (rank 0 receives 5.3 GB) and with
+    several hundred pieces spread over the engines by bytes."""
     torch = require_gpu()
     P, T, K, E, H = 8, 8192, 8, 256, 7168
     row = H * 2
     seed = wl.config_seed(3)
     x_np = [wl.normal_bf16_bits(seed, s, T * H).view(np.uint8) for s in range(P)]
     ids_np = [wl.zipf_topk_expert_ids(seed, s, T, K, E) for s in range(P)]
-    rsz = _dispatch(torch, vccl, P, T, K, E, row, seed, vccl.MODE_CU, x_np=x_np, ids_np=ids_np)
+    ops0 = vccl.vccl_proxy_stats()
+    rsz = _dispatch(torch, vccl, P, T, K, E, row, seed, (vccl.MODE_CU, vccl.MODE_CE), x_np=x_np, ids_np=ids_np)
     assert sum(rsz) == P * T * K * row
     assert rsz[0] == max(rsz), "rank 0 hosts the hot experts"
+    assert rsz[0] > 4 << 30, "the case is meant to reach beyond 4 GiB inside one receive buffer"
+    ops1 = vccl.vccl_proxy_stats()
+    assert ops1["ops"] == ops0["ops"] + 1 and ops1["bytes"] - ops0["bytes"] == sum(rsz)
+    assert ops1["copies"] - ops0["copies"] > 64, "the long segments are cut into pieces for the engines"
+
+
+def test_config3_combine_full_size(vccl):
+    """The way back at config-3 size, both forms: (i) inverse AlltoAllv + vccl_moe_unpack,
+    (ii) vccl_moe_dispatch_fused -> change on the expert side -> vccl_moe_combine_fused,
+    against the oracle chain pack -> layout -> AlltoAllv -> change -> inverse AlltoAllv ->
+    un-permute."""
+    torch = require_gpu()
+    P, T, K, E, H = 8, 8192, 8, 256, 7168
+    row = H * 2
+    seed = wl.config_seed(3)
+    st = stream_handle(torch)
+    x_np = [wl.normal_bf16_bits(seed, s, T * H).view(np.uint8) for s in range(P)]
+    ids_np = [wl.zipf_topk_expert_ids(seed, s, T, K, E) for s in range(P)]
+    # oracle chain
+    want_recv, lay, _ = _oracle_dispatch(P, T, K, E, row, x_np, ids_np)
+    rows = np.array([w.size // row for w in want_recv], dtype=np.uint64)
+    changed = [np.bitwise_not(w) for w in want_recv]
+    del want_recv
+    want_back = [np.full(T * K * row, SENTINEL, np.uint8) for _ in range(P)]
+    oracle.alltoallv(changed, lay["recvcounts"], lay["rdispls"], want_back, lay["sendcounts"], lay["sdispls"],
+                     threads=8)
+    del changed
+    want_out = [oracle.moe_unpack(want_back[s], ids_np[s], row, E) for s in range(P)]
+    # the definition's consequence: every token's row, K times, with the change applied
+    assert np.array_equal(want_out[3].reshape(T, K, row)[:, 5], np.bitwise_not(x_np[3]).reshape(T, row))
+    x = [to_dev(torch, a) for a in x_np]
+    ids = [torch.from_numpy(a.reshape(-1).copy()).cuda() for a in ids_np]
+    # (i) two-step: pack, exchange, change, exchange back, un-permute
+    packed = [torch.zeros(T * K * row, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    counts_dev = torch.zeros((P, E), dtype=torch.int64, device="cuda")
+    counts_host = torch.zeros((P, E), dtype=torch.int64).pin_memory()
+    vccl.vccl_moe_pack(x, ids, P, T, K, row, E, packed, counts_dev, counts_host, None, st)
+    torch.cuda.synchronize()
+    glay = vccl.vccl_moe_exchange_layout(counts_host.numpy().astype(np.uint64), P, E, E // P, row)
+    for k in lay:
+        assert np.array_equal(glay[k], lay[k]), k
+    recv = [torch.zeros(int(rows[r]) * row, dtype=torch.uint8, device="cuda") for r in range(P)]
+    vccl.vccl_alltoallv(packed, glay["sendcounts"], glay["sdispls"], recv, glay["recvcounts"], glay["rdispls"],
+                        P, vccl.MODE_CU, st)
+    for r in range(P):
+        recv[r].bitwise_not_()
+    back = packed                                                      # reuse: it is overwritten in full
+    for b in back:
+        b.fill_(SENTINEL)
+    vccl.vccl_alltoallv(recv, glay["recvcounts"], glay["rdispls"], back, glay["sendcounts"], glay["sdispls"],
+                        P, vccl.MODE_CU, st)
+    out = [torch.full((T * K * row + 16,), SENTINEL, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    vccl.vccl_moe_unpack(back, ids, P, T, K, row, E, out, st)
+    torch.cuda.synchronize()
+    for s in range(P):
+        assert_same(to_host(back[s]), want_back[s], f"inverse exchange, rank {s}")
+        got = to_host(out[s])
+        assert_same(got[:T * K * row], want_out[s], f"un-permute, rank {s}")
+        assert (got[T * K * row:] == SENTINEL).all()
+    del back, packed, want_back
+    # (ii) fused: dispatch straight into the receive buffers, change, combine straight out of them
+    for r in range(P):
+        recv[r].fill_(SENTINEL)
+    for o in out:
+        o.fill_(SENTINEL)
+    layout = torch.zeros((4, P, P), dtype=torch.int64, device="cuda")
+    status = torch.zeros(2, dtype=torch.int32, device="cuda")
+    vccl.vccl_moe_dispatch_fused(x, ids, P, T, K, row, E, E // P, recv, rows, None, layout, None, status, st)
+    for r in range(P):
+        recv[r].bitwise_not_()
+    vccl.vccl_moe_combine_fused(recv, rows, ids, P, T, K, row, E, E // P, out, st)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0]
+    for s in range(P):
+        got = to_host(out[s])
+        assert_same(got[:T * K * row], want_out[s], f"fused combine, rank {s}")
+        assert (got[T * K * row:] == SENTINEL).all()
 
 
 def test_config3_moe_dispatch_per_rank_full_size(vccl):
