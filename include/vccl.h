@@ -216,6 +216,25 @@ int vccl_moe_pack(const void *const *x, const int32_t *const *expert_ids, int P,
                   int topk, uint64_t row_bytes, int num_experts, void *const *packed,
                   uint64_t *counts_dev, uint64_t *counts_host, uint32_t *bad_ids_dev, void *stream);
 
+/* vccl_moe_pack for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * result and stream semantics as vccl_moe_pack (without the pinned copy of the
+ * counts), but nothing is allocated or freed, on the device or through any library:
+ * the index data of the call (per-block histograms, one destination row per pair, the
+ * table of rank pointers) lives in a fixed 8 MiB array that is part of the library's
+ * device image (each device the library runs on holds it until the process ends).
+ * Limits: P <= 16, and 256-byte pointer table + 4 * (P * ceil(tokens*topk / 2048) *
+ * num_experts + P * tokens * topk + 2 * P * num_experts + 4) bytes must fit into the
+ * 8 MiB (P = 8, 8192 tokens, top-8 of 256 experts needs 2.3 MiB); beyond that the call
+ * returns VCCL_ERR_UNSUPPORTED and enqueues nothing.  All calls on one device share the
+ * array: a call may start only after the previous vccl_moe_pack_noalloc on that device
+ * has finished or on the same stream; calls that overlap on one device race.  Nothing
+ * in the array has to be cleared between calls (every word a call reads it has written
+ * first). */
+int vccl_moe_pack_noalloc(const void *const *x, const int32_t *const *expert_ids, int P, int tokens,
+                          int topk, uint64_t row_bytes, int num_experts, void *const *packed,
+                          uint64_t *counts_dev, uint32_t *bad_ids_dev, void *stream);
+
 /* MoE dispatch pack with one row per (token, destination rank): the reading of the
  * dispatch phase (Section 6) in which a token whose experts share a rank crosses the
  * fabric once.  Expert e lives on rank e / experts_per_rank (experts_per_rank divides

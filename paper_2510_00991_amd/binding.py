@@ -47,6 +47,9 @@ EXPORTS = {
     "vccl_moe_pack": (ctypes.c_int, [_vpp, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                      ctypes.c_uint64, ctypes.c_int, _vpp, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+    "vccl_moe_pack_noalloc": (ctypes.c_int, [_vpp, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                             ctypes.c_uint64, ctypes.c_int, _vpp, ctypes.c_void_p,
+                                             ctypes.c_void_p, ctypes.c_void_p]),
     "vccl_moe_pack_per_rank": (ctypes.c_int, [_vpp, _vpp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                               ctypes.c_uint64, ctypes.c_int, ctypes.c_int, _vpp,
                                               ctypes.c_void_p, ctypes.c_void_p, _vpp, ctypes.c_void_p,
@@ -246,6 +249,16 @@ def vccl_moe_pack(x, expert_ids, P: int, tokens: int, topk: int, row_bytes: int,
                                 num_experts, _ptrs(packed), ctypes.c_void_p(_addr(counts_dev)),
                                 ctypes.c_void_p(_addr(counts_host)),
                                 ctypes.c_void_p(_addr(bad_ids_dev)), _stream(stream)))
+
+
+def vccl_moe_pack_noalloc(x, expert_ids, P: int, tokens: int, topk: int, row_bytes: int, num_experts: int,
+                          packed, counts_dev, bad_ids_dev=None, stream=None) -> None:
+    """vccl_moe_pack without any allocation (index data in the library's static device array)."""
+    if len(x) != P or len(expert_ids) != P or len(packed) != P:
+        raise ValueError("per-rank arrays must have P entries")
+    _check(load().vccl_moe_pack_noalloc(_ptrs(x), _ptrs(expert_ids), P, tokens, topk, int(row_bytes),
+                                        num_experts, _ptrs(packed), ctypes.c_void_p(_addr(counts_dev)),
+                                        ctypes.c_void_p(_addr(bad_ids_dev)), _stream(stream)))
 
 
 def vccl_moe_pack_per_rank(x, expert_ids, P: int, tokens: int, topk: int, row_bytes: int, num_experts: int,

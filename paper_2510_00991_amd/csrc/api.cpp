@@ -263,6 +263,11 @@ int vccl_init(int device, int max_ranks) {
         c->ring.destroy();
         return rv;
     }
+    rv = moe_static_scratch_init(device);   // address of the static scratch on this device
+    if (rv) {
+        c->ring.destroy();
+        return rv;
+    }
     c->proxy = proxy_create(device, 8);
     if (!c->proxy) {
         c->ring.destroy();
@@ -557,6 +562,33 @@ int vccl_moe_pack(const void *const *x, const int32_t *const *expert_ids, int P,
                   uint64_t *counts_host, uint32_t *bad_ids_dev, void *stream) {
     return moe_pack_common(x, expert_ids, P, tokens, topk, row_bytes, num_experts, 0, packed, counts_dev,
                            counts_host, nullptr, bad_ids_dev, stream);
+}
+
+int vccl_moe_pack_noalloc(const void *const *x, const int32_t *const *expert_ids, int P, int tokens, int topk,
+                          uint64_t row_bytes, int num_experts, void *const *packed, uint64_t *counts_dev,
+                          uint32_t *bad_ids_dev, void *stream) {
+    auto c = ctx_get();
+    int rv = check_common(c, P, x, packed);
+    if (rv) return rv;
+    if (!expert_ids || !counts_dev) return fail(VCCL_ERR_ARG, "expert_ids or counts_dev is NULL");
+    if (tokens < 0 || topk < 1 || topk > 64)
+        return fail(VCCL_ERR_ARG, "tokens = %d, topk = %d (topk must be 1..64)", tokens, topk);
+    if (num_experts < 1 || num_experts > 1024)
+        return fail(VCCL_ERR_ARG, "num_experts = %d is outside 1..1024", num_experts);
+    if (row_bytes == 0 || (row_bytes & 15u))
+        return fail(VCCL_ERR_ARG, "row_bytes = %llu must be a positive multiple of 16",
+                    (unsigned long long)row_bytes);
+    if ((uint64_t)tokens * (uint64_t)topk > 0x7fffffffull)
+        return fail(VCCL_ERR_UNSUPPORTED, "more than 2^31 (token, slot) pairs per rank");
+    for (int s = 0; s < P; ++s) {
+        if (tokens && (!x[s] || !expert_ids[s] || !packed[s]))
+            return fail(VCCL_ERR_ARG, "NULL buffer for rank %d", s);
+        if ((reinterpret_cast<uintptr_t>(x[s]) | reinterpret_cast<uintptr_t>(packed[s])) & 15u)
+            return fail(VCCL_ERR_ARG, "x / packed of rank %d are not 16-byte aligned", s);
+    }
+    return launch_moe_pack_noalloc(c->device, x, expert_ids, P, tokens, topk, row_bytes, num_experts, packed,
+                                   counts_dev, bad_ids_dev, options_of(*c).moe_gather_variant,
+                                   (hipStream_t)stream);
 }
 
 int vccl_moe_pack_per_rank(const void *const *x, const int32_t *const *expert_ids, int P, int tokens, int topk,

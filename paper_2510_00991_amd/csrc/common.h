@@ -175,6 +175,14 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
                     uint32_t *const *slot_row, uint32_t *bad_ids_dev, int gather_variant,
                     hipStream_t stream);
 
+// The pack for callers that cannot allocate: index data in a file-scope device array
+// whose address moe_static_scratch_init asks for once per device (that device current).
+int moe_static_scratch_init(int device);
+int launch_moe_pack_noalloc(int device, const void *const *x, const int32_t *const *ids, int P, int tokens,
+                            int topk, uint64_t row_bytes, int num_experts, void *const *packed,
+                            uint64_t *counts_dev, uint32_t *bad_ids_dev, int gather_variant,
+                            hipStream_t stream);
+
 // Pack and exchange in one pass: rows go from x[s] straight into recv[r] where the
 // exchange after a pack would have put them.
 int launch_moe_dispatch_fused(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P,

@@ -536,67 +536,106 @@ void MoeScratch::destroy() {
     hist_n = ptrs_n = 0;
 }
 
-// Launches 1-3: per-pair destination rows in the scratch.  `a` / `b` are the two
-// row buffers of every rank in the roles (read side, written side) of launch 4.
-// experts_per_rank > 0 selects the per-rank form: the sort keys are computed into
-// the scratch from the caller's ids and `num_experts` counts ranks from there on.
-static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *const *ids, int P,
-                           int tokens, int topk, int num_experts, int experts_per_rank,
-                           uint32_t *const *slot_row, void *const *b, const uint64_t *capacity_rows,
-                           size_t extra_words, uint64_t *counts_dev, uint32_t *bad_ids_dev,
-                           hipStream_t stream, MoePtrs *ptrs_out, uint32_t **dest_out,
-                           uint64_t **counts_out = nullptr, uint64_t **extra_out = nullptr) {
+// ---- scratch of the entry point that allocates nothing ------------------------
+// vccl_moe_pack_noalloc keeps its index data (histograms, destination rows, counts,
+// the table of rank pointers) in this file-scope array instead of allocated memory.
+// Host code never uses the array's name as an address: its device address is asked
+// for once per device (moe_static_scratch_init) and kept in g_static_scratch.
+constexpr size_t kStaticScratchBytes = 8u << 20;
+constexpr int kStaticMaxRanks = 16;
+constexpr int kStaticMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static void *g_static_scratch[kStaticMaxDevices] = {};
+static std::mutex g_static_mu;
+
+int moe_static_scratch_init(int device) {
+    if (device < 0 || device >= kStaticMaxDevices)
+        return fail(VCCL_ERR_UNSUPPORTED, "device %d is beyond the %d devices the static scratch is kept for", device,
+                    kStaticMaxDevices);
+    std::lock_guard<std::mutex> lk(g_static_mu);
+    if (g_static_scratch[device]) return VCCL_OK;
+    void *ptr = nullptr;
+    VCCL_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));   // the current device's copy of the array
+    if (!ptr) return fail(VCCL_ERR_HIP, "hipGetSymbolAddress gave a null address for the static scratch");
+    g_static_scratch[device] = ptr;
+    return VCCL_OK;
+}
+
+struct PtrBlock {   // the rank-pointer table as a kernel argument
+    void *p[kPtrArrays * kStaticMaxRanks];
+};
+__global__ __launch_bounds__(kMoeThreads) void moe_store_ptrs_kernel(PtrBlock blk, void **table, int n) {
+    const int i = blockIdx.x * kMoeThreads + threadIdx.x;
+    if (i < n) table[i] = blk.p[i];
+}
+
+// Where the index data of one call lives: `words` holds histograms, destination rows,
+// rank keys, counts and the caller's extra room, `ptrs` the device table of
+// kPtrArrays x P rank pointers.
+struct MoeWork {
+    uint32_t *words;
+    void **ptrs;
+};
+
+// 32-bit words one call needs (see moe_index_phase for the layout).
+static size_t moe_words_needed(int P, int tokens, int topk, int num_experts, int experts_per_rank,
+                               size_t extra_words) {
+    const bool per_rank = experts_per_rank > 0;
+    const int nkeys = per_rank ? num_experts / experts_per_rank : num_experts;
+    const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
+    const uint32_t nblk = npairs ? (npairs + kPairsPerBlock - 1) / kPairsPerBlock : 1;
+    const size_t hist_n = (size_t)P * nblk * (size_t)nkeys;
+    const size_t counts_words = 2 * (size_t)P * nkeys;
+    const size_t keys_words = per_rank ? (size_t)P * npairs : 0;
+    // histograms, destination rows, rank keys, counts (8-byte aligned), caller's extra (8-byte aligned)
+    return hist_n + (size_t)P * npairs + keys_words + counts_words + 2 + extra_words + 2;
+}
+
+// Row of the rank-pointer table: what every kernel of the MoE path reads its buffers from.
+static void moe_fill_ptr_table(void **tbl, uint32_t *words, const void *const *a, const int32_t *const *ids,
+                               int P, int tokens, int topk, int num_experts, int experts_per_rank,
+                               uint32_t *const *slot_row, void *const *b, const uint64_t *capacity_rows) {
+    const bool per_rank = experts_per_rank > 0;
+    const int nkeys = per_rank ? num_experts / experts_per_rank : num_experts;
+    const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
+    const uint32_t nblk = npairs ? (npairs + kPairsPerBlock - 1) / kPairsPerBlock : 1;
+    const size_t hist_n = (size_t)P * nblk * (size_t)nkeys;
+    int32_t *keys = reinterpret_cast<int32_t *>(words + hist_n + (size_t)P * npairs);
+    for (int s = 0; s < P; ++s) {
+        tbl[s] = const_cast<void *>(a[s]);
+        tbl[P + s] = per_rank ? static_cast<void *>(keys + (size_t)s * npairs)
+                              : static_cast<void *>(const_cast<int32_t *>(ids[s]));
+        tbl[2 * P + s] = b[s];
+        tbl[3 * P + s] = const_cast<int32_t *>(ids[s]);
+        tbl[4 * P + s] = slot_row ? slot_row[s] : nullptr;
+        tbl[5 * P + s] = reinterpret_cast<void *>((uintptr_t)(capacity_rows ? capacity_rows[s] : 0));
+    }
+}
+
+// Launches 1-3: per-pair destination rows in `w.words`; the pointer table `w.ptrs` is
+// already on its way on `stream`.  experts_per_rank > 0 selects the per-rank form: the
+// sort keys are computed into the scratch from the caller's ids and `num_experts`
+// counts ranks from there on.
+static int moe_index_launches(const MoeWork &w, int P, int tokens, int topk, int num_experts,
+                              int experts_per_rank, uint64_t *counts_dev, uint32_t *bad_ids_dev,
+                              hipStream_t stream, MoePtrs *ptrs_out, uint32_t **dest_out,
+                              uint64_t **counts_out, uint64_t **extra_out) {
     const bool per_rank = experts_per_rank > 0;
     const int nkeys = per_rank ? num_experts / experts_per_rank : num_experts;   // sort-key range
     const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
     const uint32_t nblk = npairs ? (npairs + kPairsPerBlock - 1) / kPairsPerBlock : 1;
     const size_t hist_n = (size_t)P * nblk * (size_t)nkeys;
-    const size_t counts_words = 2 * (size_t)P * nkeys;                  // private uint64 counts
     const size_t keys_words = per_rank ? (size_t)P * npairs : 0;
-    // histograms, destination rows, rank keys, counts (8-byte aligned), caller's extra (8-byte aligned)
-    const size_t need = hist_n + (size_t)P * npairs + keys_words + counts_words + 2 + extra_words + 2;
-    if (!sc.done) VCCL_HIP(hipEventCreateWithFlags(&sc.done, hipEventDisableTiming));
-    // The scratch is shared: a new call starts after the previous one has finished
-    // with it on the device, and the pinned pointer staging is free again.
-    VCCL_HIP(hipEventSynchronize(sc.done));
-    if (need > sc.hist_n) {
-        if (sc.hist) VCCL_HIP(hipFree(sc.hist));
-        sc.hist = nullptr;
-        sc.hist_n = 0;
-        VCCL_HIP(hipMalloc((void **)&sc.hist, need * sizeof(uint32_t)));
-        sc.hist_n = need;
-    }
-    if ((size_t)kPtrArrays * P > sc.ptrs_n) {
-        if (sc.ptrs) VCCL_HIP(hipFree(sc.ptrs));
-        if (sc.ptrs_host) VCCL_HIP(hipHostFree(sc.ptrs_host));
-        sc.ptrs = nullptr;
-        sc.ptrs_host = nullptr;
-        sc.ptrs_n = 0;
-        VCCL_HIP(hipMalloc((void **)&sc.ptrs, (size_t)kPtrArrays * P * sizeof(void *)));
-        VCCL_HIP(hipHostMalloc((void **)&sc.ptrs_host, (size_t)kPtrArrays * P * sizeof(void *), hipHostMallocDefault));
-        sc.ptrs_n = (size_t)kPtrArrays * P;
-    }
-    uint32_t *hist = sc.hist;
-    uint32_t *dest = sc.hist + hist_n;
+    uint32_t *hist = w.words;
+    uint32_t *dest = w.words + hist_n;
     int32_t *keys = reinterpret_cast<int32_t *>(dest + (size_t)P * npairs);
-    for (int s = 0; s < P; ++s) {
-        sc.ptrs_host[s] = const_cast<void *>(a[s]);
-        sc.ptrs_host[P + s] = per_rank ? static_cast<void *>(keys + (size_t)s * npairs)
-                                       : static_cast<void *>(const_cast<int32_t *>(ids[s]));
-        sc.ptrs_host[2 * P + s] = b[s];
-        sc.ptrs_host[3 * P + s] = const_cast<int32_t *>(ids[s]);
-        sc.ptrs_host[4 * P + s] = slot_row ? slot_row[s] : nullptr;
-        sc.ptrs_host[5 * P + s] = reinterpret_cast<void *>((uintptr_t)(capacity_rows ? capacity_rows[s] : 0));
-    }
-    VCCL_HIP(hipMemcpyAsync(sc.ptrs, sc.ptrs_host, (size_t)kPtrArrays * P * sizeof(void *),
-                            hipMemcpyHostToDevice, stream));
     MoePtrs ptrs;
-    ptrs.x = reinterpret_cast<const uint8_t *const *>(sc.ptrs);
-    ptrs.ids = reinterpret_cast<const int32_t *const *>(sc.ptrs + P);
-    ptrs.packed = reinterpret_cast<uint8_t *const *>(sc.ptrs + 2 * P);
-    ptrs.ids_in = reinterpret_cast<const int32_t *const *>(sc.ptrs + 3 * P);
-    ptrs.slot_row = reinterpret_cast<uint32_t *const *>(sc.ptrs + 4 * P);
-    ptrs.capacity_rows = reinterpret_cast<const uint64_t *>(sc.ptrs + 5 * P);
+    ptrs.x = reinterpret_cast<const uint8_t *const *>(w.ptrs);
+    ptrs.ids = reinterpret_cast<const int32_t *const *>(w.ptrs + P);
+    ptrs.packed = reinterpret_cast<uint8_t *const *>(w.ptrs + 2 * P);
+    ptrs.ids_in = reinterpret_cast<const int32_t *const *>(w.ptrs + 3 * P);
+    ptrs.slot_row = reinterpret_cast<uint32_t *const *>(w.ptrs + 4 * P);
+    ptrs.capacity_rows = reinterpret_cast<const uint64_t *>(w.ptrs + 5 * P);
     static_assert(sizeof(void *) == sizeof(uint64_t), "capacities travel in pointer-sized slots");
     uint64_t *counts_scratch =
         reinterpret_cast<uint64_t *>((reinterpret_cast<uintptr_t>(keys + keys_words) + 7u) & ~(uintptr_t)7u);
@@ -628,6 +667,115 @@ static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *
     return VCCL_OK;
 }
 
+// The allocating entry points: grow the library-owned scratch as needed, upload the
+// pointer table through pinned staging, then launches 1-3.  `a` / `b` are the two
+// row buffers of every rank in the roles (read side, written side) of launch 4.
+static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *const *ids, int P,
+                           int tokens, int topk, int num_experts, int experts_per_rank,
+                           uint32_t *const *slot_row, void *const *b, const uint64_t *capacity_rows,
+                           size_t extra_words, uint64_t *counts_dev, uint32_t *bad_ids_dev,
+                           hipStream_t stream, MoePtrs *ptrs_out, uint32_t **dest_out,
+                           uint64_t **counts_out = nullptr, uint64_t **extra_out = nullptr) {
+    const size_t need = moe_words_needed(P, tokens, topk, num_experts, experts_per_rank, extra_words);
+    if (!sc.done) VCCL_HIP(hipEventCreateWithFlags(&sc.done, hipEventDisableTiming));
+    // The scratch is shared: a new call starts after the previous one has finished
+    // with it on the device, and the pinned pointer staging is free again.
+    VCCL_HIP(hipEventSynchronize(sc.done));
+    if (need > sc.hist_n) {
+        if (sc.hist) VCCL_HIP(hipFree(sc.hist));
+        sc.hist = nullptr;
+        sc.hist_n = 0;
+        VCCL_HIP(hipMalloc((void **)&sc.hist, need * sizeof(uint32_t)));
+        sc.hist_n = need;
+    }
+    if ((size_t)kPtrArrays * P > sc.ptrs_n) {
+        if (sc.ptrs) VCCL_HIP(hipFree(sc.ptrs));
+        if (sc.ptrs_host) VCCL_HIP(hipHostFree(sc.ptrs_host));
+        sc.ptrs = nullptr;
+        sc.ptrs_host = nullptr;
+        sc.ptrs_n = 0;
+        VCCL_HIP(hipMalloc((void **)&sc.ptrs, (size_t)kPtrArrays * P * sizeof(void *)));
+        VCCL_HIP(hipHostMalloc((void **)&sc.ptrs_host, (size_t)kPtrArrays * P * sizeof(void *), hipHostMallocDefault));
+        sc.ptrs_n = (size_t)kPtrArrays * P;
+    }
+    moe_fill_ptr_table(sc.ptrs_host, sc.hist, a, ids, P, tokens, topk, num_experts, experts_per_rank, slot_row, b,
+                       capacity_rows);
+    VCCL_HIP(hipMemcpyAsync(sc.ptrs, sc.ptrs_host, (size_t)kPtrArrays * P * sizeof(void *),
+                            hipMemcpyHostToDevice, stream));
+    const MoeWork w{sc.hist, sc.ptrs};
+    return moe_index_launches(w, P, tokens, topk, num_experts, experts_per_rank, counts_dev, bad_ids_dev, stream,
+                              ptrs_out, dest_out, counts_out, extra_out);
+}
+
+// Launch 4 of the pack: the row gather in the selected form.
+static int moe_launch_gather(const MoePtrs &ptrs, const uint32_t *dest, int P, int tokens, int topk,
+                             uint64_t row_bytes, int experts_per_rank, int gather_variant, hipStream_t stream) {
+    const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
+    const uint32_t tok_blocks = ((uint32_t)tokens + kMoeThreads / 64 - 1) / (kMoeThreads / 64);
+    const dim3 g(tok_blocks, P), b(kMoeThreads);
+    const uint32_t rv = (uint32_t)(row_bytes >> 4);
+    const uint32_t pieces = (rv + kPieceVecs - 1) / kPieceVecs;
+    const uint32_t kgroups = ((uint32_t)topk + kSlotWaves - 1) / kSlotWaves;
+    const uint64_t shared_grid = (uint64_t)tokens * pieces * kgroups;
+    if ((gather_variant == 208 || gather_variant == 308) && shared_grid > 0x7fffffffull) gather_variant = 116;
+    // per-rank form: most slots are dropped, the piece-loop kernel wastes no wavefront on them
+    if (experts_per_rank > 0 && (gather_variant == 208 || gather_variant == 308)) gather_variant += 200;
+    const uint64_t loop_grid = (uint64_t)tokens * pieces;
+    if ((gather_variant == 408 || gather_variant == 508) && loop_grid > 0x7fffffffull) gather_variant = 116;
+    const dim3 gl((uint32_t)loop_grid, P), bl(64);
+    const dim3 gs((uint32_t)shared_grid, P), bs(kSlotWaves * 64);
+    switch (gather_variant) {
+        case 408: moe_gather_piece_loop_kernel<true><<<gl, bl, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, dest, npairs); break;
+        case 508: moe_gather_piece_loop_kernel<false><<<gl, bl, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, dest, npairs); break;
+        case 208: moe_gather_shared_kernel<true><<<gs, bs, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, dest, npairs); break;
+        case 308: moe_gather_shared_kernel<false><<<gs, bs, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, dest, npairs); break;
+        case 4: moe_gather_kernel<4, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
+        case 16: moe_gather_kernel<16, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
+        case 108: moe_gather_kernel<8, false><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
+        case 116: moe_gather_kernel<16, false><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
+        default: moe_gather_kernel<8, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
+    }
+    VCCL_HIP(hipGetLastError());
+    return VCCL_OK;
+}
+
+// The pack without any allocation: index data and pointer table in the static scratch.
+// No event guards the scratch: calls that overlap on one device race (documented).
+int launch_moe_pack_noalloc(int device, const void *const *x, const int32_t *const *ids, int P, int tokens,
+                            int topk, uint64_t row_bytes, int num_experts, void *const *packed,
+                            uint64_t *counts_dev, uint32_t *bad_ids_dev, int gather_variant,
+                            hipStream_t stream) {
+    if (device < 0 || device >= kStaticMaxDevices || !g_static_scratch[device])
+        return fail(VCCL_ERR_NOT_INIT, "the static scratch of device %d has not been set up (vccl_init does it)", device);
+    if (P > kStaticMaxRanks)
+        return fail(VCCL_ERR_UNSUPPORTED, "vccl_moe_pack_noalloc takes at most %d ranks, got %d", kStaticMaxRanks, P);
+    constexpr size_t kTableBytes = ((sizeof(PtrBlock) + 255u) / 256u) * 256u;
+    const size_t need = moe_words_needed(P, tokens, topk, num_experts, 0, 0);
+    if (kTableBytes + need * sizeof(uint32_t) > kStaticScratchBytes)
+        return fail(VCCL_ERR_UNSUPPORTED,
+                    "vccl_moe_pack_noalloc: P = %d, tokens = %d, topk = %d, num_experts = %d need %zu bytes of index "
+                    "data, the static scratch holds %zu (use vccl_moe_pack)", P, tokens, topk, num_experts,
+                    kTableBytes + need * sizeof(uint32_t), kStaticScratchBytes);
+    unsigned char *base = static_cast<unsigned char *>(g_static_scratch[device]);
+    const MoeWork w{reinterpret_cast<uint32_t *>(base + kTableBytes), reinterpret_cast<void **>(base)};
+    PtrBlock blk;
+    moe_fill_ptr_table(blk.p, w.words, x, ids, P, tokens, topk, num_experts, 0, nullptr, packed, nullptr);
+    const int n = kPtrArrays * P;
+    for (int i = n; i < kPtrArrays * kStaticMaxRanks; ++i) blk.p[i] = nullptr;
+    moe_store_ptrs_kernel<<<dim3((n + kMoeThreads - 1) / kMoeThreads), dim3(kMoeThreads), 0, stream>>>(blk, w.ptrs, n);
+    VCCL_HIP(hipGetLastError());
+    // Nothing in the scratch has to start at zero: every histogram word, destination row
+    // and count this call reads is written by this call first.
+    MoePtrs ptrs;
+    uint32_t *dest = nullptr;
+    int rc = moe_index_launches(w, P, tokens, topk, num_experts, 0, counts_dev, bad_ids_dev, stream, &ptrs, &dest,
+                                nullptr, nullptr);
+    if (rc) return rc;
+    if ((uint32_t)tokens * (uint32_t)topk)
+        return moe_launch_gather(ptrs, dest, P, tokens, topk, row_bytes, 0, gather_variant, stream);
+    return VCCL_OK;
+}
+
 int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P, int tokens,
                     int topk, uint64_t row_bytes, int num_experts, int experts_per_rank,
                     void *const *packed, uint64_t *counts_dev, uint64_t *counts_host,
@@ -641,31 +789,8 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
                              nullptr, 0, counts_dev, bad_ids_dev, stream, &ptrs, &dest);
     if (rc) return rc;
     if (npairs) {
-        const uint32_t tok_blocks = ((uint32_t)tokens + kMoeThreads / 64 - 1) / (kMoeThreads / 64);
-        const dim3 g(tok_blocks, P), b(kMoeThreads);
-        const uint32_t rv = (uint32_t)(row_bytes >> 4);
-        const uint32_t pieces = (rv + kPieceVecs - 1) / kPieceVecs;
-        const uint32_t kgroups = ((uint32_t)topk + kSlotWaves - 1) / kSlotWaves;
-        const uint64_t shared_grid = (uint64_t)tokens * pieces * kgroups;
-        if ((gather_variant == 208 || gather_variant == 308) && shared_grid > 0x7fffffffull) gather_variant = 116;
-        // per-rank form: most slots are dropped, the piece-loop kernel wastes no wavefront on them
-        if (experts_per_rank > 0 && (gather_variant == 208 || gather_variant == 308)) gather_variant += 200;
-        const uint64_t loop_grid = (uint64_t)tokens * pieces;
-        if ((gather_variant == 408 || gather_variant == 508) && loop_grid > 0x7fffffffull) gather_variant = 116;
-        const dim3 gl((uint32_t)loop_grid, P), bl(64);
-        const dim3 gs((uint32_t)shared_grid, P), bs(kSlotWaves * 64);
-        switch (gather_variant) {
-            case 408: moe_gather_piece_loop_kernel<true><<<gl, bl, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, dest, npairs); break;
-            case 508: moe_gather_piece_loop_kernel<false><<<gl, bl, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, dest, npairs); break;
-            case 208: moe_gather_shared_kernel<true><<<gs, bs, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, dest, npairs); break;
-            case 308: moe_gather_shared_kernel<false><<<gs, bs, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, dest, npairs); break;
-            case 4: moe_gather_kernel<4, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
-            case 16: moe_gather_kernel<16, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
-            case 108: moe_gather_kernel<8, false><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
-            case 116: moe_gather_kernel<16, false><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
-            default: moe_gather_kernel<8, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
-        }
-        VCCL_HIP(hipGetLastError());
+        rc = moe_launch_gather(ptrs, dest, P, tokens, topk, row_bytes, experts_per_rank, gather_variant, stream);
+        if (rc) return rc;
         if (experts_per_rank > 0 && slot_row) {
             moe_slot_row_kernel<<<dim3(((uint32_t)tokens + kMoeThreads - 1) / kMoeThreads, P), dim3(kMoeThreads),
                                   0, stream>>>(ptrs, (uint32_t)tokens, topk, experts_per_rank, dest, npairs);
