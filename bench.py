@@ -6,14 +6,16 @@ peer, 1 GiB sent, random 16-bit patterns) through the C boundary on the
 compute-unit copy path: host planning, launch and the copy itself.  The metric is
 achieved GB/s counted as bytes read plus bytes written, set against the HBM peak.
 The same run also reports the copy-engine path on the same workload, the co-run
-slowdown each path causes to a compute-bound FMA kernel, the MoE pack, the
-SendRecv ring, and the CPU oracle timed on the host cores.
+slowdown each path causes to a compute-bound FMA kernel (headline workload, the
+SendRecv ring in every mode, three points of the P = 64 message sweep), the MoE
+dispatch and combine, and the CPU oracle timed on the host cores.
 
 Prints ONE JSON line.  `python bench.py --gpus 1 --steps K --warmup W`.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import statistics
@@ -24,9 +26,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# Imported before anything touches the GPU: the package asks the HIP runtime to carry out
+# stream waits in the command processor (no helper kernel on the copy-engine path).
 from paper_2510_00991_amd.harness import time_calls, time_region  # noqa: E402  (timing helpers)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+CSRC = os.path.join(ROOT, "paper_2510_00991_amd", "csrc")
 
 
 def cpu_baseline(P, c, budget_s=12.0):
@@ -84,6 +89,7 @@ def headline(torch, v, a2a_cu, args, algo_bytes, P, c, send, recv):
                    "cu_wg_per_cu": int(v.vccl_get_option("cu_wg_per_cu"))},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(),
+                     "traffic_source": "committed rocprofv3 counter summary (profiles/), not this run",
                      "kernel": "copy_aligned_kernel", "kernel_us": kern * 1e6,
                      "kernel_us_single_calls": statistics.mean(per) * 1e6,
                      "algorithmic_bytes": algo_bytes},
@@ -95,26 +101,45 @@ def headline(torch, v, a2a_cu, args, algo_bytes, P, c, send, recv):
     return out, kern
 
 
+def _summary_fields(name, sources):
+    """`key: value` fields of a committed profiler summary; None when the file is missing or
+    the sources it was taken from have changed since (the summary carries their hash)."""
+    try:
+        fields = {}
+        for line in open(os.path.join(ROOT, "profiles", name)):
+            if ":" in line:
+                k, val = line.split(":", 1)
+                fields[k.strip()] = val.strip()
+        digest = hashlib.sha256(b"".join(open(os.path.join(CSRC, n), "rb").read() for n in sources)).hexdigest()
+        if fields.get("kernel_source_sha256", fields.get("source_sha256")) != digest:
+            return None
+        return fields
+    except OSError:
+        return None
+
+
 def measured_traffic():
     """HBM bytes per launch of the headline kernel from the committed counter
     summary (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size); None
     when there is no summary or the kernel source has changed since it was taken."""
-    import hashlib
-    path = os.path.join(ROOT, "profiles", "copy_aligned_kernel_alltoall_p8_16MiB_pmc.txt")
-    csrc = os.path.join(ROOT, "paper_2510_00991_amd", "csrc")
+    f = _summary_fields("copy_aligned_kernel_alltoall_p8_16MiB_pmc.txt", ("copy_kernel.hip", "device_util.h"))
     try:
-        fields = {}
-        for line in open(path):
-            if ":" in line:
-                k, val = line.split(":", 1)
-                fields[k.strip()] = val.strip()
-        # the kernel and the header with its load / store helpers, concatenated
-        digest = hashlib.sha256(b"".join(open(os.path.join(csrc, n), "rb").read()
-                                         for n in ("copy_kernel.hip", "device_util.h"))).hexdigest()
-        if fields.get("kernel_source_sha256") != digest:
-            return None
-        return float(fields["traffic_bytes_per_launch"])
-    except (OSError, KeyError, ValueError):
+        return float(f["traffic_bytes_per_launch"]) if f else None
+    except (KeyError, ValueError):
+        return None
+
+
+def copy_engine_dispatches(sync):
+    """Kernel dispatches and wavefronts (SQ_WAVES) per copy-engine call in the given ordering
+    mode, from the committed counter summary; None when the proxy source has changed since."""
+    f = _summary_fields("copy_engine_sq_waves.txt", ("proxy.cpp",))
+    if not f:
+        return None
+    try:
+        return {"dispatches_per_call": float(f[f"dispatches_per_call_{sync}"]),
+                "sq_waves_per_call": float(f[f"sq_waves_per_call_{sync}"]),
+                "source": "committed rocprofv3 --pmc SQ_WAVES summary (profiles/), not this run"}
+    except (KeyError, ValueError):
         return None
 
 
@@ -123,15 +148,16 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--legs", default="cu,ce,corun,sendrecv,moe,cpu",
-                    help="comma list of legs to run: cu (always), ce, corun, sendrecv, moe, cpu, "
+    ap.add_argument("--legs", default="cu,ce,corun,sendrecv,sweep,moe,cpu",
+                    help="comma list of legs to run: cu (always), ce, corun, sendrecv, sweep, moe, cpu, "
                          "calib (a plain 1 GiB device copy, used to scale profiler counters)")
-    ap.add_argument("--ce-sync", default="memops", choices=["memops", "host"],
-                    help="ordering of the copy-engine path: stream write/wait-value operations, "
-                         "or none (the call blocks)")
+    ap.add_argument("--ce-sync", default="default", choices=["default", "memops", "event", "host"],
+                    help="ordering of the copy-engine path: the library's default for this process, stream "
+                         "write/wait-value operations, event + wait-value, or none (the call blocks)")
+    ap.add_argument("--pairs", type=int, default=20, help="alone/beside pairs per co-run figure")
     args = ap.parse_args()
     legs = set(x.strip() for x in args.legs.split(",") if x.strip())
-    unknown = legs - {"cu", "ce", "corun", "sendrecv", "moe", "cpu", "calib"}
+    unknown = legs - {"cu", "ce", "corun", "sendrecv", "sweep", "moe", "cpu", "calib"}
     if unknown:
         print(f"bench.py: unknown legs {sorted(unknown)}", file=sys.stderr)
         sys.exit(2)
@@ -152,7 +178,9 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     v.vccl_init(0, 64)
-    v.vccl_set_option("ce_sync", args.ce_sync)
+    if args.ce_sync != "default":
+        v.vccl_set_option("ce_sync", args.ce_sync)
+    ce_sync = v.vccl_get_option("ce_sync")
     out = {}
     try:
         P, c = 8, 16 << 20
@@ -162,6 +190,19 @@ def main():
         recv = [torch.zeros(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
         st = int(torch.cuda.current_stream().cuda_stream)
         algo_bytes = 2.0 * total                          # every byte is read once and written once
+        # Buffers of the P = 64 sweep: allocated before the first copy-engine measurement and
+        # freed after the last (after device memory has been freed the copy engines of this
+        # device run at about 60 % of their rate for a second or two).
+        P5, sweep_sizes = 64, (4 << 10, 64 << 10, 4 << 20)
+        sweep_bufs = {}
+        if "sweep" in legs:
+            for c5 in sweep_sizes:
+                s5 = [torch.empty(P5 * c5, dtype=torch.uint8, device="cuda") for _ in range(P5)]
+                r5 = [torch.empty(P5 * c5, dtype=torch.uint8, device="cuda") for _ in range(P5)]
+                for s in range(P5):     # seeded payload in the first MiB of each buffer (timing does not depend on values)
+                    n = min(P5 * c5, 1 << 20)
+                    s5[s][:n].copy_(torch.from_numpy(wl.payload_bytes(wl.config_seed(5), s, n)))
+                sweep_bufs[c5] = (s5, r5)
 
         def a2a_cu():
             v.vccl_alltoall(send, recv, c, P, v.MODE_CU, st)
@@ -180,62 +221,96 @@ def main():
             b = torch.empty_like(a)
             w, _ = time_region(torch, lambda: b.copy_(a), 5, 2)
             out["calib_copy_1GiB"] = {"GBps": 2.0 * (1 << 30) / (w / 5) / 1e9, "launches": 7}
-            del a, b
         if "ce" in legs:
             k_ce = max(3, min(args.steps, 10))
             cpu0 = v.vccl_proxy_cpu_time()
             wall_ce, _ = time_region(torch, a2a_ce, k_ce, 2)
             cpu1 = v.vccl_proxy_cpu_time()
+            proxy_ms = (cpu1["sender_ns"] - cpu0["sender_ns"] + cpu1["receiver_ns"] - cpu0["receiver_ns"]) * 1e-6
             out["copy_engine"] = {"GBps": algo_bytes / (wall_ce / k_ce) / 1e9,
                                   "ms_per_step": wall_ce / k_ce * 1e3, "steps": k_ce,
-                                  "kind": v.vccl_get_option("ce_kind"), "sync": v.vccl_get_option("ce_sync"),
+                                  "kind": v.vccl_get_option("ce_kind"), "sync": ce_sync,
+                                  "stream_wait_in_command_processor": int(v.vccl_get_option("ce_wait_on_cp")),
                                   "engines": int(v.vccl_get_option("ce_engines")),
+                                  "kernels": copy_engine_dispatches(ce_sync),
                                   # processor time of the proxy threads over warm-up + timed calls
-                                  "proxy_cpu_ms_per_step": (cpu1["sender_ns"] - cpu0["sender_ns"]
-                                                            + cpu1["receiver_ns"] - cpu0["receiver_ns"])
-                                  / (k_ce + 2) * 1e-6}
+                                  "proxy_cpu_ms_per_step": proxy_ms / (k_ce + 2),
+                                  "proxy_cpu_ms_per_GB_moved": proxy_ms / ((k_ce + 2) * total / 1e9)}
+            for r, s in ((1, 6), (7, 0)):
+                assert torch.equal(recv[r][s * c:(s + 1) * c], send[s][r * c:(r + 1) * c])
+        co = CoRun(torch) if legs & {"corun", "sendrecv", "sweep"} else None
         if "corun" in legs:
             # co-run: FMA probe alone vs beside each path (protocol in harness.CoRun)
-            co = CoRun(torch)
-            cor_cu = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes, kern)
+            cor_cu = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes, kern,
+                               reps=args.pairs)
             # the same path with its grid capped to one workgroup per compute unit
             # (4 wavefronts of 8 vectors per lane each, so that 256 workgroups can keep HBM busy)
             v.vccl_set_option("cu_max_wg", co.cu)
             v.vccl_set_option("cu_unroll", 8)
             v.vccl_set_option("cu_threads", 256)
             wcap, _ = time_region(torch, a2a_cu, 5, 2)
-            cor_cap = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes, wcap / 5)
+            cor_cap = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes, wcap / 5,
+                                reps=args.pairs)
             cor_cap["GBps_alone"] = algo_bytes / (wcap / 5) / 1e9
             # and to a quarter of that: 64 workgroups
             v.vccl_set_option("cu_max_wg", 64)
             wcap64, _ = time_region(torch, a2a_cu, 3, 1)
             cor_cap64 = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes,
-                                  wcap64 / 3)
+                                  wcap64 / 3, reps=args.pairs)
             cor_cap64["GBps_alone"] = algo_bytes / (wcap64 / 3) / 1e9
             v.vccl_set_option("cu_max_wg", 0)
             v.vccl_set_option("cu_unroll", 1)
             v.vccl_set_option("cu_threads", 64)
             wce, _ = time_region(torch, a2a_ce, 3, 1)
-            cor_ce = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CE, sh), algo_bytes, wce / 3)
+            cor_ce = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CE, sh), algo_bytes, wce / 3,
+                               reps=args.pairs)
             out["corun"] = {"probe": f"FMA kernel, {co.cu} workgroups x {co.threads} threads, "
                                      f"{co.iters} rounds of 64 FMAs per lane",
+                            "protocol": f"{args.pairs} alone/beside pairs in alternating order, median and "
+                                        "quartiles of the paired ratios",
                             "cu_path": cor_cu, "cu_path_capped_1wg_per_cu": cor_cap,
                             "cu_path_capped_64wg": cor_cap64, "copy_engine_path": cor_ce}
         if "sendrecv" in legs:
-            # SendRecv ring, 8 stages x 64 MiB
+            # SendRecv ring, 8 stages x 64 MiB: rate and probe slowdown in every mode
             n = 64 << 20
             to, frm = wl.ring_peers(P)
+            send_p, recv_p = v.pointer_array(send), v.pointer_array(recv)    # marshalled once, not per call
             sr = {}
             for name, mode in (("cu_direct", v.MODE_CU), ("cu_staged", v.MODE_CU_STAGED),
                                ("copy_engine", v.MODE_CE)):
-                fn = lambda m=mode: v.vccl_sendrecv(send, [n] * P, to, recv, [n] * P, frm, P, m, st)
+                fn = lambda sh=st, m=mode: v.vccl_sendrecv(send_p, [n] * P, to, recv_p, [n] * P, frm, P, m, sh)
                 # median of three trains: the copy engines' rate wanders from train to train
-                w = statistics.median(time_region(torch, fn, 5, 2)[0] for _ in range(3))
-                sr[name] = {"GBps": 2.0 * P * n / (w / 5) / 1e9, "ms": w / 5 * 1e3}
+                runs = sorted((time_region(torch, fn, 5, 2) for _ in range(3)), key=lambda t: t[0])
+                w, dev = runs[1]
+                sr[name] = {"GBps": 2.0 * P * n / (w / 5) / 1e9, "ms": w / 5 * 1e3,
+                            # device time of the train / calls: for the kernel modes one call is one launch
+                            "device_us_per_call": dev / 5 * 1e6,
+                            "GBps_device": 2.0 * P * n / (dev / 5) / 1e9}
+                if co is not None and "corun" in legs:
+                    sr[name]["corun"] = co.beside(fn, 2.0 * P * n, w / 5, reps=max(8, args.pairs // 2))
             v.vccl_sendrecv_staged_status()
+            for r in (0, 5):
+                assert torch.equal(recv[r][:n], send[frm[r]][:n])
             out["sendrecv_ring_8x64MiB"] = sr
-        del send, recv
-        torch.cuda.empty_cache()
+        if "sweep" in legs:
+            # three points of the P = 64 message sweep: both paths' rate and the probe's slowdown
+            rows = []
+            for c5 in sweep_sizes:
+                s5, r5 = sweep_bufs[c5]
+                sp, rp = v.pointer_array(s5), v.pointer_array(r5)
+                moved = 2.0 * P5 * P5 * c5
+                row = {"bytes_per_peer": c5}
+                for name, mode in (("cu", v.MODE_CU), ("ce", v.MODE_CE)):
+                    fn = lambda sh=st, m=mode: v.vccl_alltoall(sp, rp, c5, P5, m, sh)
+                    k = 10 if name == "cu" else 3
+                    t = statistics.median(time_region(torch, fn, k, 2)[0] for _ in range(3)) / k
+                    row[name] = {"us": t * 1e6, "GBps": moved / t / 1e9}
+                    if "corun" in legs:
+                        row[name]["corun"] = co.beside(fn, moved, t, reps=max(8, args.pairs // 2))
+                for r, s in ((3, 60), (63, 1)):     # block r of send[s] is block s of recv[r]
+                    assert torch.equal(r5[r][s * c5:(s + 1) * c5], s5[s][r * c5:(r + 1) * c5])
+                rows.append(row)
+            out["alltoall_sweep_p64"] = rows
         if "moe" in legs:
             # MoE pack, config 3 shapes
             T, K, E, H = 8192, 8, 256, 7168
@@ -263,10 +338,10 @@ def main():
             outp = [torch.empty(T * K * row, dtype=torch.uint8, device="cuda") for _ in range(P)]
             fu = lambda: v.vccl_moe_unpack(packed, ids, P, T, K, row, E, outp, st)
             wu, _ = time_region(torch, fu, 5, 2)
-            del outp
             out["moe_combine_unpack"] = {"GBps": 2.0 * P * T * K * row / (wu / 5) / 1e9, "ms": wu / 5 * 1e3}
             out["moe_dispatch"] = {
                 "pack_GBps": pack_bytes / (w / 5) / 1e9, "pack_ms": w / 5 * 1e3,
+                "pack_frac_of_hbm_peak": pack_bytes / (w / 5) / 1e9 / HBM_PEAK_GBS,
                 "exchange_GBps": 2.0 * float(lay["sendcounts"].sum()) / (wx / 5) / 1e9,
                 "exchange_ms": wx / 5 * 1e3,
                 "exchange_copy_engine_GBps": 2.0 * float(lay["sendcounts"].sum()) / (wxe / 2) / 1e9,
@@ -298,16 +373,21 @@ def main():
             wf, _ = time_region(torch, ff, 5, 2)
             assert status_d.cpu().tolist() == [0, 0]
             out["moe_dispatch_fused"] = {"GBps": pack_bytes / (wf / 5) / 1e9, "ms": wf / 5 * 1e3,
+                                         "frac_of_hbm_peak": pack_bytes / (wf / 5) / 1e9 / HBM_PEAK_GBS,
                                          "two_step_ms": (w + wx) / 5 * 1e3}
             # the way back fused: inverse exchange + un-permute in one pass
-            outp = [torch.empty(T * K * row, dtype=torch.uint8, device="cuda") for _ in range(P)]
             fc = lambda: v.vccl_moe_combine_fused(rcv, cap, ids, P, T, K, row, E, E // P, outp, st)
             wc, _ = time_region(torch, fc, 5, 2)
             out["moe_combine_fused"] = {"GBps": 2.0 * P * T * K * row / (wc / 5) / 1e9, "ms": wc / 5 * 1e3,
                                         "two_step_ms": (wx + wu) / 5 * 1e3}
-            del outp
-            del x, ids, packed, rcv
-            torch.cuda.empty_cache()
+            # spot check of what was timed last: the fused round trip gives every token's row back K times
+            t_chk = 4097
+            for s in (0, 6):
+                got = outp[s].view(T, K, row)[t_chk]
+                assert torch.equal(got, x[s].view(T, row)[t_chk].expand(K, row))
+            del x, ids, packed, rcv, outp
+        del send, recv, sweep_bufs
+        torch.cuda.empty_cache()
     finally:
         v.vccl_finalize()
 

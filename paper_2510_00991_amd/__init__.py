@@ -6,7 +6,16 @@ only marshals arguments: every step of the path runs inside the library.
 There is no CPU fallback - if the library has not been built, importing the
 binding's functions raises.
 """
-from .binding import (  # noqa: F401
+import os as _os
+
+# Ask the HIP runtime to carry out stream wait-value operations in the command
+# processor instead of with a helper kernel, so that the copy-engine path dispatches
+# nothing at all (see VCCL_MODE_CE in include/vccl.h).  The runtime reads the variable
+# when it starts, i.e. at the process's first HIP call: import this package before
+# anything touches the GPU.  An explicit setting of the variable is left alone.
+_os.environ.setdefault("GPU_STREAMOPS_CP_WAIT", "1")
+
+from .binding import (  # noqa: E402,F401
     MODE_CU, MODE_CE, MODE_CU_STAGED,
     VcclError,
     lib_path, load, pointer_array,

@@ -93,6 +93,7 @@ struct Context {
     MoeScratch moe;
     Proxy *proxy = nullptr;
     std::atomic<uint64_t> ce_errors_reported{0};
+    bool wait_on_cp = false;   // the process asked the HIP runtime to carry out stream waits in the command processor
 };
 
 static std::mutex g_mu;
@@ -240,6 +241,13 @@ static int alltoallv_impl(Context &c, void *const *sendbuf, const uint64_t *send
 
 using namespace vccl;
 
+// When the library is loaded: ask the HIP runtime to carry out stream wait-value
+// operations in the command processor rather than with a helper kernel, unless the
+// process has already said what it wants.  The runtime reads the variable when it
+// starts (the process's first HIP call), so this is in time for a program that links
+// the library; a process that loads it later sets the variable itself (vccl.h).
+__attribute__((constructor)) static void vccl_request_wait_on_cp() { setenv("GPU_STREAMOPS_CP_WAIT", "1", 0); }
+
 // ================================================================= C boundary ==
 extern "C" {
 
@@ -276,6 +284,16 @@ int vccl_init(int device, int max_ranks) {
     // Default copy-engine back end: SDMA engines through the HSA runtime when the
     // device supports stream wait-value operations, else hipMemcpyAsync(NoCU).
     c->opt.ce_kind = proxy_sdma_available(c->proxy, nullptr) ? VCCL_CE_SDMA : VCCL_CE_HIP_NOCU;
+    // Which ordering dispatches nothing depends on how the HIP runtime carries out
+    // hipStreamWaitValue64: with GPU_STREAMOPS_CP_WAIT=1 in the environment when the
+    // runtime started, the command processor waits on the signal word itself; otherwise
+    // the runtime launches a one-lane helper kernel that holds a wavefront slot for the
+    // length of the transfer.  In the first case the default pairs that wait with an
+    // event for readiness ("event": no kernel at all, and the call does not block);
+    // in the second the default stays "memops".
+    const char *cp = getenv("GPU_STREAMOPS_CP_WAIT");
+    c->wait_on_cp = cp && atoi(cp) != 0;
+    if (c->opt.ce_kind == VCCL_CE_SDMA && c->wait_on_cp) c->opt.ce_sync = VCCL_SYNC_EVENT;
     g_ctx = c;
     return VCCL_OK;
 }
@@ -336,12 +354,13 @@ int vccl_set_option(const char *key, const char *value) {
         else return fail(VCCL_ERR_ARG, "ce_kind must be 'sdma', 'hip_nocu' or 'hip_default', got '%s'", value);
         return VCCL_OK;
     }
-    if (k == "ce_engines" || k == "ce_errors" || k == "ce_engine_bytes")
+    if (k == "ce_engines" || k == "ce_errors" || k == "ce_engine_bytes" || k == "ce_wait_on_cp" || k == "ce_refused")
         return fail(VCCL_ERR_ARG, "%s is read-only", key);
     if (k == "ce_sync") {
-        if (!strcmp(value, "memops")) o.ce_sync_host = 0;
-        else if (!strcmp(value, "host")) o.ce_sync_host = 1;
-        else return fail(VCCL_ERR_ARG, "ce_sync must be 'memops' or 'host', got '%s'", value);
+        if (!strcmp(value, "memops")) o.ce_sync = VCCL_SYNC_MEMOPS;
+        else if (!strcmp(value, "host")) o.ce_sync = VCCL_SYNC_HOST;
+        else if (!strcmp(value, "event")) o.ce_sync = VCCL_SYNC_EVENT;
+        else return fail(VCCL_ERR_ARG, "ce_sync must be 'memops', 'event' or 'host', got '%s'", value);
         return VCCL_OK;
     }
     uint64_t x = 0;
@@ -379,6 +398,9 @@ int vccl_set_option(const char *key, const char *value) {
     } else if (k == "ce_max_engines") {
         if (!in(0, 16)) return fail(VCCL_ERR_ARG, "ce_max_engines must be 0..16");
         o.ce_max_engines = (int)x;
+    } else if (k == "ce_test_refuse") {
+        if (!in(0, 0xffff)) return fail(VCCL_ERR_ARG, "ce_test_refuse must be 0..65535");
+        o.ce_test_refuse = (int)x;
     } else if (k == "check") {
         if (!in(0, 1)) return fail(VCCL_ERR_ARG, "check must be 0 or 1");
         o.check = (int)x;
@@ -416,7 +438,8 @@ int vccl_get_option(const char *key, char *out, int cap) {
                                          : o.ce_kind == VCCL_CE_HIP_NOCU ? "hip_nocu" : "hip_default");
         return VCCL_OK;
     } else if (k == "ce_sync") {
-        snprintf(out, (size_t)cap, "%s", o.ce_sync_host ? "host" : "memops");
+        snprintf(out, (size_t)cap, "%s", o.ce_sync == VCCL_SYNC_HOST ? "host"
+                                         : o.ce_sync == VCCL_SYNC_EVENT ? "event" : "memops");
         return VCCL_OK;
     } else if (k == "ce_engine_bytes") {
         std::string txt;
@@ -427,6 +450,9 @@ int vccl_get_option(const char *key, char *out, int cap) {
         return VCCL_OK;
     } else if (k == "ce_engines") v = (unsigned long long)proxy_engine_count(c->proxy);
     else if (k == "ce_errors") v = (unsigned long long)proxy_sdma_errors(c->proxy);
+    else if (k == "ce_wait_on_cp") v = c->wait_on_cp ? 1 : 0;
+    else if (k == "ce_refused") v = (unsigned long long)proxy_refused_pieces(c->proxy);
+    else if (k == "ce_test_refuse") v = o.ce_test_refuse;
     else if (k == "cu_unroll") v = o.cu_unroll;
     else if (k == "cu_wg_per_cu") v = o.cu_wg_per_cu;
     else if (k == "cu_max_wg") v = o.cu_max_wg;

@@ -34,6 +34,8 @@ static_assert(sizeof(Seg) == 32, "descriptor layout");
 
 // copy-engine back ends
 enum { VCCL_CE_SDMA = 0, VCCL_CE_HIP_NOCU = 1, VCCL_CE_HIP_DEFAULT = 2 };
+// stream ordering of the sdma back end: ready word + done word; blocking caller; ready event + done word
+enum { VCCL_SYNC_MEMOPS = 0, VCCL_SYNC_HOST = 1, VCCL_SYNC_EVENT = 2 };
 
 constexpr int kInlineSegs = 64;     // descriptors carried in the kernel arguments
 
@@ -49,7 +51,8 @@ struct Options {
     int ce_streams = 4;
     int ce_kind = 0;   // VCCL_CE_*
     int ce_max_engines = 0;
-    int ce_sync_host = 0;
+    int ce_test_refuse = 0;   // test hook: bit i set = engine i refuses every copy
+    int ce_sync = 0;   // VCCL_SYNC_*
     int check = 0;
     uint64_t fifo_chunk_bytes = 512u << 10;
     int fifo_slots = 8;
@@ -231,6 +234,7 @@ int proxy_drain(Proxy *p);
 bool proxy_sdma_available(Proxy *p, const char **why);
 int proxy_engine_count(Proxy *p);
 uint64_t proxy_sdma_errors(Proxy *p);
+uint64_t proxy_refused_pieces(Proxy *p);
 vccl_monitor *proxy_monitor(Proxy *p, int primitive);
 void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t *issue_ns);
 int proxy_cpu_time(Proxy *p, uint64_t *sender_ns, uint64_t *receiver_ns);

@@ -36,6 +36,7 @@
 #include <hsa/hsa_ext_amd.h>
 
 #include <pthread.h>
+#include <sys/prctl.h>
 #include <time.h>
 
 #include <chrono>
@@ -89,8 +90,12 @@ struct Op {
     int primitive = 1;                         // 0 SendRecv, 1 AlltoAll(v): which monitor sees the op
     uint64_t monitor_id = 0;
     bool host_sync = false;                    // no stream memory operations: the caller blocks
+    bool ready_event = false;                  // readiness is found by polling the `ready` event, not the ready word
     int max_engines = 0;
+    uint32_t refuse_mask = 0;                  // test hook: engines (by index) treated as refusing every copy
     bool sdma_failed = false;
+    uint64_t bytes = 0;                        // bytes handed to the engines
+    uint64_t t_issue_ns = 0;                   // when they were handed over
 };
 }  // namespace
 
@@ -111,7 +116,7 @@ public:
     bool stop = false;
     size_t in_flight = 0;        // queued + waiting + pending
     RegInfo reg[VCCL_MAX_RANKS];
-    std::atomic<uint64_t> n_ops{0}, n_copies{0}, n_bytes{0}, issue_ns{0}, sdma_errors{0};
+    std::atomic<uint64_t> n_ops{0}, n_copies{0}, n_bytes{0}, issue_ns{0}, sdma_errors{0}, n_refused{0};
     std::atomic<uint64_t> engine_bytes[kMaxEngines] = {};   // bytes handed to each engine so far
     // sdma back end
     bool sdma_ok = false;
@@ -130,12 +135,19 @@ public:
                    std::chrono::steady_clock::now().time_since_epoch()).count();
     }
 
+    // Copy rate (bytes per nanosecond) the engines have shown on large operations: how
+    // long the sender proxy may sleep before it starts polling a pending operation.
+    double rate_bpns = 0.7;
+    std::mutex started_mu;
+    std::condition_variable cv_started;   // copyStarted of some connection has advanced
+    uint64_t nap_ns(uint64_t now, uint64_t last_progress) const;
+    void mark_started(Op *op);
     void run();
     void run_receiver();
     bool receivers_ready(const Op *op) const;
     void issue_events(Op *op);
     bool issue_sdma(Op *op);
-    void poll();
+    bool poll();
     void finish(Op *op);
     Op *get_op();
     void put_ref(Op *op);
@@ -330,7 +342,7 @@ void Proxy::issue_events(Op *op) {
     if ((size_t)ns > work.size()) ns = work.empty() ? 1 : (int)work.size();
     hipError_t err = hipSuccess;
     for (int i = 0; i < ns && err == hipSuccess; ++i) err = hipStreamWaitEvent(streams[i], op->ready, 0);
-    for (auto &c : op->conns) reg[c.first].copyStarted.store(c.second, std::memory_order_release);
+    mark_started(op);
     uint64_t load[kMaxStreams] = {};
     const hipMemcpyKind kind =
         op->kind == VCCL_CE_HIP_NOCU ? hipMemcpyDeviceToDeviceNoCU : hipMemcpyDeviceToDevice;
@@ -372,7 +384,7 @@ void Proxy::issue_events(Op *op) {
 // -------------------------------------------------------- sdma back end ------
 // Returns false while the caller's stream has not yet reached the operation.
 bool Proxy::issue_sdma(Op *op) {
-    if (op->host_sync) {
+    if (op->ready_event) {
         if (hipEventQuery(op->ready) == hipErrorNotReady) return false;
     } else if (__atomic_load_n(op->ready_word, __ATOMIC_ACQUIRE) < op->seq) {
         return false;
@@ -383,28 +395,49 @@ bool Proxy::issue_sdma(Op *op) {
     const auto t0 = std::chrono::steady_clock::now();
     const int ne = op->max_engines > 0 && op->max_engines < nengines ? op->max_engines : nengines;
     std::vector<CeCopy> work = expand(op, (size_t)ne);
-    for (auto &c : op->conns) reg[c.first].copyStarted.store(c.second, std::memory_order_release);
+    mark_started(op);
     hsa_signal_store_relaxed(op->left, (hsa_signal_value_t)work.size());
     uint64_t bytes = 0;
     // Each piece goes to the engine with the fewest bytes so far (ties: rotate, so that
     // equal pieces still spread round-robin and small operations do not all start on
-    // engine 0).
+    // engine 0).  An engine that refuses a piece is passed over: the piece is offered to
+    // the other engines in turn, and if none takes it, it is copied through the HIP
+    // runtime on an internal stream before the operation is allowed to complete.
     uint64_t load[kMaxEngines] = {};
+    std::vector<const CeCopy *> refused;
+    auto offer = [&](const CeCopy &w, int e) {
+        if (op->refuse_mask & (1u << e)) return false;
+        return hsa_amd_memory_async_copy_on_engine(w.dst, agent, w.src, agent, w.bytes, 0, nullptr, op->left,
+                                                   (hsa_amd_sdma_engine_id_t)engine_bit[e], true) == HSA_STATUS_SUCCESS;
+    };
     for (const CeCopy &w : work) {
         int best = (int)(next_engine++ % (unsigned)ne);
         for (int i = 0; i < ne; ++i)
             if (load[i] < load[best]) best = i;
-        load[best] += w.bytes;
-        engine_bytes[best].fetch_add(w.bytes, std::memory_order_relaxed);
-        const uint32_t bit = engine_bit[best];
-        hsa_status_t st = hsa_amd_memory_async_copy_on_engine(
-            w.dst, agent, w.src, agent, w.bytes, 0, nullptr, op->left, (hsa_amd_sdma_engine_id_t)bit, true);
-        if (st != HSA_STATUS_SUCCESS) {   // keep the count right so that the op still completes
-            hsa_signal_subtract_relaxed(op->left, 1);
-            op->sdma_failed = true;
+        bool taken = offer(w, best);
+        for (int t = 1; t < ne && !taken; ++t) {
+            best = (best + 1) % ne;
+            taken = offer(w, best);
+        }
+        if (taken) {
+            load[best] += w.bytes;
+            engine_bytes[best].fetch_add(w.bytes, std::memory_order_relaxed);
+        } else {
+            hsa_signal_subtract_relaxed(op->left, 1);   // keep the count right so that the op still completes
+            refused.push_back(&w);
         }
         bytes += w.bytes;
     }
+    if (!refused.empty()) {
+        n_refused.fetch_add(refused.size(), std::memory_order_relaxed);
+        hipError_t e = hipSuccess;
+        for (const CeCopy *w : refused)
+            if (e == hipSuccess) e = hipMemcpyAsync(w->dst, w->src, w->bytes, hipMemcpyDeviceToDevice, streams[0]);
+        if (e == hipSuccess) e = hipStreamSynchronize(streams[0]);
+        if (e != hipSuccess) op->sdma_failed = true;    // the receive buffers are incomplete: reported by the next call
+    }
+    op->bytes = bytes;
+    op->t_issue_ns = now_ns();
     const auto t1 = std::chrono::steady_clock::now();
     n_ops.fetch_add(1, std::memory_order_relaxed);
     n_copies.fetch_add(work.size(), std::memory_order_relaxed);
@@ -415,6 +448,17 @@ bool Proxy::issue_sdma(Op *op) {
     (void)vccl_monitor_post(monitor[op->primitive], op->monitor_id, bytes, now_ns());
     pending.push_back(op);
     return true;
+}
+
+// copyStarted: the sender has taken the destination out of the record; the receiver
+// proxy may publish the next buffer of the connection.
+void Proxy::mark_started(Op *op) {
+    if (op->conns.empty()) return;
+    {
+        std::lock_guard<std::mutex> lk(started_mu);
+        for (auto &c : op->conns) reg[c.first].copyStarted.store(c.second, std::memory_order_release);
+    }
+    cv_started.notify_all();
 }
 
 bool Proxy::receivers_ready(const Op *op) const {
@@ -437,14 +481,30 @@ void Proxy::run_receiver() {
             recv_queue.pop_front();
         }
         RegInfo &ri = reg[post.rank];
-        while (ri.copyStarted.load(std::memory_order_acquire) != post.seq - 1) std::this_thread::yield();
+        // Poll for a short while (back-to-back transfers start within microseconds of each
+        // other), then sleep until the sender proxy says that a transfer has started.
+        const uint64_t t0 = now_ns();
+        while (ri.copyStarted.load(std::memory_order_acquire) != post.seq - 1) {
+            if (now_ns() - t0 < 20000) {
+                std::this_thread::yield();
+                continue;
+            }
+            std::unique_lock<std::mutex> lk(started_mu);
+            cv_started.wait(lk, [&] { return ri.copyStarted.load(std::memory_order_acquire) == post.seq - 1; });
+        }
         ri.receiverRegAddr.store(post.addr, std::memory_order_relaxed);
         ri.receiverReady.store(post.seq, std::memory_order_release);
     }
 }
 
 void Proxy::finish(Op *op) {
-    (void)vccl_monitor_complete(monitor[op->primitive], op->monitor_id, now_ns(), nullptr);
+    const uint64_t t_done = now_ns();
+    (void)vccl_monitor_complete(monitor[op->primitive], op->monitor_id, t_done, nullptr);
+    if (op->kind == VCCL_CE_SDMA && op->bytes >= (8u << 20) && t_done > op->t_issue_ns) {
+        // what the engines gave this operation, smoothed: the sleep before polling leans on it
+        const double r = (double)op->bytes / (double)(t_done - op->t_issue_ns);
+        rate_bpns = 0.75 * rate_bpns + 0.25 * r;
+    }
     for (auto &c : op->conns) reg[c.first].copyDone.store(c.second, std::memory_order_release);
     if (op->kind == VCCL_CE_SDMA) {
         if (op->sdma_failed) sdma_errors.fetch_add(1, std::memory_order_relaxed);
@@ -461,12 +521,15 @@ void Proxy::finish(Op *op) {
     cv_idle.notify_all();
 }
 
-// Completion polling, as the paper's proxy does; sets copyDone.
-void Proxy::poll() {
+// Completion polling, as the paper's proxy does; sets copyDone.  Returns whether
+// anything moved (an operation was issued or found complete).
+bool Proxy::poll() {
+    bool progress = false;
     for (size_t k = 0; k < waiting.size();) {
         if (issue_sdma(waiting[k])) {
             waiting[k] = waiting.back();
             waiting.pop_back();
+            progress = true;
         } else {
             ++k;
         }
@@ -491,11 +554,42 @@ void Proxy::poll() {
         pending[k] = pending.back();
         pending.pop_back();
         finish(op);
+        progress = true;
     }
+    return progress;
+}
+
+// How long the sender proxy may sleep before its next poll (0 = keep polling).  The
+// paper's proxy polls without pause; here the thread polls only where that buys
+// latency: for a short while after anything has moved, and around the time a
+// pending operation is expected to complete.  In between it sleeps - until shortly
+// before that time for operations on the engines (bytes over the copy rate the
+// engines have shown), in short slices for operations whose stream is not ready yet.
+uint64_t Proxy::nap_ns(uint64_t now, uint64_t last_progress) const {
+    constexpr uint64_t kSpin = 30000;          // keep polling this long after the last progress
+    if (now - last_progress < kSpin) return 0;
+    uint64_t nap = !waiting.empty() ? (now - last_progress < 1000000 ? 10000 : 50000) : 200000;
+    for (const Op *op : pending) {
+        if (op->kind != VCCL_CE_SDMA) return 0;   // event back end: short copies on HIP streams, polled
+        const uint64_t dur = (uint64_t)((double)op->bytes / rate_bpns);
+        const uint64_t margin = 10000 + dur / 16;
+        const uint64_t due = op->t_issue_ns + (dur > margin ? dur - margin : 0);
+        if (now >= due) {
+            // due: poll; if it is late by more than a third of its length the estimate was
+            // wrong (the engines were slow), then look again every 20 us
+            if (now < op->t_issue_ns + dur + dur / 3 + 20000) return 0;
+            nap = nap < 20000 ? nap : 20000;
+        } else if (due - now < nap) {
+            nap = due - now;
+        }
+    }
+    return nap;
 }
 
 void Proxy::run() {
     (void)hipSetDevice(device);
+    prctl(PR_SET_TIMERSLACK, 1000ul);   // short sleeps mean short sleeps (the default slack is 50 us)
+    uint64_t last_progress = now_ns();
     for (;;) {
         Op *op = nullptr;
         {
@@ -503,10 +597,16 @@ void Proxy::run() {
             const bool busy = !pending.empty() || !waiting.empty();
             if (!busy) {
                 cv_work.wait(lk, [&] { return stop || !queue.empty(); });
+                last_progress = now_ns();
             } else if (queue.empty()) {
-                lk.unlock();
-                std::this_thread::yield();   // poll, like the paper's proxy thread
-                lk.lock();
+                const uint64_t nap = nap_ns(now_ns(), last_progress);
+                if (nap) {
+                    cv_work.wait_for(lk, std::chrono::nanoseconds(nap), [&] { return stop || !queue.empty(); });
+                } else {
+                    lk.unlock();
+                    std::this_thread::yield();
+                    lk.lock();
+                }
             }
             if (!queue.empty()) {
                 op = queue.front();
@@ -515,11 +615,13 @@ void Proxy::run() {
                 return;
             }
         }
+        bool progress = op != nullptr;
         if (op) {
             if (op->kind == VCCL_CE_SDMA) waiting.push_back(op);
             else issue_events(op);
         }
-        poll();
+        if (poll()) progress = true;
+        if (progress) last_progress = now_ns();
     }
 }
 
@@ -612,7 +714,8 @@ int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hip
         std::lock_guard<std::mutex> lk(p->mu);
         op = p->get_op();
         if (!op) return fail(VCCL_ERR_HIP, "could not create the resources of a copy-engine operation");
-        op->host_sync = opt.ce_kind == VCCL_CE_SDMA && opt.ce_sync_host;
+        op->host_sync = opt.ce_kind == VCCL_CE_SDMA && opt.ce_sync == VCCL_SYNC_HOST;
+        op->ready_event = op->host_sync || (opt.ce_kind == VCCL_CE_SDMA && opt.ce_sync == VCCL_SYNC_EVENT);
         op->refs = (opt.ce_kind == VCCL_CE_SDMA && !op->host_sync) ? 1 : 2;
         op->state = 0;
     }
@@ -620,6 +723,7 @@ int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hip
     op->want_streams = opt.ce_streams;
     op->kind = opt.ce_kind;
     op->max_engines = opt.ce_max_engines;
+    op->refuse_mask = (uint32_t)opt.ce_test_refuse;
     op->primitive = receivers ? 0 : 1;
     if (op->kind == VCCL_CE_SDMA) return submit_sdma(p, op, stream, receivers);
 
@@ -716,35 +820,36 @@ static int submit_sdma(Proxy *p, Op *op, hipStream_t stream,
                        const std::vector<std::pair<int, void *>> *receivers) {
     if (op->host_sync) return submit_sdma_host_sync(p, op, stream, receivers);
     const uint64_t seq = ++op->seq;
-    // proxyReadyEvent: the stream writes the sequence number once everything before
-    // this call has finished.
-    hipError_t e = hipStreamWriteValue64(stream, (void *)op->ready_word, seq, 0);
-    if (e != hipSuccess) {
-        --op->seq;
+    // proxyReadyEvent: the stream tells the proxy when everything before this call has
+    // finished - by writing the sequence number into the ready word, or (ordering
+    // "event") by an event the proxy polls, which dispatches nothing.
+    hipError_t e = op->ready_event ? hipEventRecord(op->ready, stream)
+                                   : hipStreamWriteValue64(stream, (void *)op->ready_word, seq, 0);
+    // The stream resumes when the proxy stores the sequence number into the done word
+    // (proxyOpCount back at zero).  Enqueued before the proxy gets the operation, so that
+    // a failure here leaves nothing behind.
+    const char *what = op->ready_event ? "hipEventRecord(ready)" : "hipStreamWriteValue64(ready)";
+    if (e == hipSuccess) {
+        what = "hipStreamWaitValue64(done)";
+        e = hipStreamWaitValue64(stream, op->done_word, seq, hipStreamWaitValueGte, ~0ull);
+    }
+    if (e != hipSuccess) {   // the sequence number is spent: the words only ever grow
         std::lock_guard<std::mutex> lk(p->mu);
         p->put_ref(op);
-        return fail(VCCL_ERR_HIP, "hipStreamWriteValue64(ready) failed: %s", hipGetErrorString(e));
+        return fail(VCCL_ERR_HIP, "%s failed: %s", what, hipGetErrorString(e));
+    }
+    std::unique_lock<std::mutex> hs(p->handshake_mu, std::defer_lock);
+    if (receivers) {
+        hs.lock();
+        publish_receivers(p, op, *receivers);
     }
     {
-        std::unique_lock<std::mutex> hs(p->handshake_mu, std::defer_lock);
-        if (receivers) {
-            hs.lock();
-            publish_receivers(p, op, *receivers);
-        }
-        uint64_t *done_word = op->done_word;
-        {
-            std::lock_guard<std::mutex> lk(p->mu);
-            p->queue.push_back(op);
-            ++p->in_flight;
-            p->cv_work.notify_one();
-        }
-        // From here on the proxy owns `op`.  The stream resumes when the proxy stores
-        // the sequence number into the done word (proxyOpCount back at zero).
-        e = hipStreamWaitValue64(stream, done_word, seq, hipStreamWaitValueGte, ~0ull);
+        std::lock_guard<std::mutex> lk(p->mu);
+        p->queue.push_back(op);
+        ++p->in_flight;
+        p->cv_work.notify_one();
     }
-    if (e != hipSuccess)
-        return fail(VCCL_ERR_HIP, "hipStreamWaitValue64(done) failed: %s (the copies still run)",
-                    hipGetErrorString(e));
+    // From here on the proxy owns `op`.
     return VCCL_OK;
 }
 
@@ -756,6 +861,7 @@ void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uin
 }
 
 uint64_t proxy_sdma_errors(Proxy *p) { return p->sdma_errors.load(); }
+uint64_t proxy_refused_pieces(Proxy *p) { return p->n_refused.load(); }
 
 // Processor time the two proxy threads have used so far (what the paper's CPU
 // utilisation figure, Section 4.1, charges to the SM-free design).

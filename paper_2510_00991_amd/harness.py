@@ -99,20 +99,25 @@ class CoRun:
             self._alone = statistics.median(self._time_alone() for _ in range(reps))
         return self._alone
 
-    def beside(self, comm_fn, comm_bytes_per_call, comm_seconds_per_call, reps=12):
+    def beside(self, comm_fn, comm_bytes_per_call, comm_seconds_per_call, reps=20):
         """comm_fn(stream_handle) enqueues one transfer on the given stream.  Each
-        repetition times the probe alone and then beside the transfer; in both cases
-        the timed probe directly follows an untimed one, and the transfers are held
-        back until that untimed probe has finished, so both timed probes start from
-        the same state.  The slowdown is the median of the per-repetition ratios."""
+        repetition is a pair: the probe alone and the probe beside the transfers, in
+        alternating order from pair to pair (alone first, then beside first) so that
+        whatever the measurement before leaves behind - clocks, power state, engines
+        winding down - falls on both sides equally.  In both cases the timed probe
+        directly follows an untimed one, and the transfers are held back until that
+        untimed probe has finished, so both timed probes start from the same state; the
+        device is idle (every stream synchronised, so every copy-engine operation has
+        been completed by the proxy) before each measurement.  The slowdown is the
+        median of the per-pair ratios; the quartiles and extremes of those ratios are
+        reported with it."""
         torch = self.torch
         t_guess = self.alone()
         n_comm = max(1, int(1.25 * t_guess / max(comm_seconds_per_call, 1e-6)) + 1)
         sh = self.comm_stream_handle()
         alone, both, comm_t = [], [], []
-        for _ in range(reps):
-            torch.cuda.synchronize()
-            alone.append(self._time_alone())
+
+        def timed_beside():
             self._probe()                                   # untimed lead-in
             gate = torch.cuda.Event()
             gate.record(self.comp)
@@ -127,13 +132,29 @@ class CoRun:
             torch.cuda.synchronize()
             both.append(a.elapsed_time(b) * 1e-3)
             comm_t.append(c0.elapsed_time(c1) * 1e-3)
+
+        for i in range(reps):
+            torch.cuda.synchronize()
+            if i % 2 == 0:
+                alone.append(self._time_alone())
+                torch.cuda.synchronize()
+                timed_beside()
+            else:
+                timed_beside()
+                torch.cuda.synchronize()
+                alone.append(self._time_alone())
         t_alone = statistics.median(alone)
         t_with = statistics.median(both)
         tc = statistics.median(comm_t)
-        # paired: each repetition's two probes are adjacent in time, so clock drift cancels
-        ratio = statistics.median(b / a for a, b in zip(alone, both))
+        ratios = sorted(b / a for a, b in zip(alone, both))
+        q = statistics.quantiles(ratios, n=4) if len(ratios) >= 4 else [ratios[0], statistics.median(ratios), ratios[-1]]
+        pct = lambda r: 100.0 * (r - 1.0)
         return {"alone_ms": t_alone * 1e3, "corun_ms": t_with * 1e3,
-                "slowdown_pct": 100.0 * (ratio - 1.0),
+                "slowdown_pct": pct(statistics.median(ratios)),
+                "slowdown_pct_q1": pct(q[0]), "slowdown_pct_q3": pct(q[2]),
+                "slowdown_pct_min": pct(ratios[0]), "slowdown_pct_max": pct(ratios[-1]),
+                "alone_ms_min": min(alone) * 1e3, "alone_ms_max": max(alone) * 1e3,
+                "pairs": reps,
                 "comm_calls": n_comm, "comm_ms": tc * 1e3,
                 "comm_GBps_while_corunning": comm_bytes_per_call * n_comm / tc / 1e9}
 
@@ -224,7 +245,7 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
             row[name] = {"us": t * 1e6, "GBps": moved / t / 1e9}
             if co is not None:
                 row[name].update(co.beside(lambda s, m=mode: v.vccl_alltoall(send_p, recv_p, c, P, m, s),
-                                           moved, t, reps=6))
+                                           moved, t, reps=8))
         rows.append(row)
     del send, recv, bufs
     torch.cuda.empty_cache()

@@ -2,7 +2,7 @@
  * memory only) runs AlltoAll on both data paths, AlltoAllv with byte-granular
  * segments, and a SendRecv ring, and compares every receive buffer with the CPU
  * oracle (linked in as a shared library).  argv[1], if given, selects the
- * copy-engine ordering ("memops" or "host").  Exit status 0 = all results right. */
+ * copy-engine ordering ("memops", "event" or "host").  Exit status 0 = all results right. */
 #include <hip/hip_runtime_api.h>
 #include <stdint.h>
 #include <stdio.h>

@@ -42,7 +42,7 @@ def test_fma_probe_runs_and_scales_with_iterations(vccl):
         vccl.vccl_fma_probe(out, 0, 100, 10, st)  # threads must be a multiple of 64
 
 
-@pytest.mark.parametrize("kind", ["sdma", "sdma_host_sync", "hip_nocu"])
+@pytest.mark.parametrize("kind", ["sdma", "sdma_event", "sdma_host_sync", "hip_nocu"])
 def test_copy_engine_progresses_while_all_wave_slots_are_busy(vccl, kind):
     """The acceptance test for "zero compute units": with every wavefront slot of
     the device held by a long compute kernel, the SDMA back end still completes an
@@ -51,7 +51,8 @@ def test_copy_engine_progresses_while_all_wave_slots_are_busy(vccl, kind):
     runtime in the process."""
     torch = require_gpu()
     vccl.vccl_set_option("ce_kind", "hip_nocu" if kind == "hip_nocu" else "sdma")
-    vccl.vccl_set_option("ce_sync", "host" if kind == "sdma_host_sync" else "memops")
+    saved_sync = vccl.vccl_get_option("ce_sync")
+    vccl.vccl_set_option("ce_sync", {"sdma_host_sync": "host", "sdma_event": "event"}.get(kind, "memops"))
     cu = vccl.vccl_device_cu_count()
     P, c = 8, 4 << 20
     send = [torch.from_numpy(wl.payload_bytes(9, s, P * c)).cuda() for s in range(P)]
@@ -83,7 +84,7 @@ def test_copy_engine_progresses_while_all_wave_slots_are_busy(vccl, kind):
     t_compute = a0.elapsed_time(a1)
     t_copy_done = a0.elapsed_time(c1)
     vccl.vccl_set_option("ce_kind", "sdma")
-    vccl.vccl_set_option("ce_sync", "memops")
+    vccl.vccl_set_option("ce_sync", saved_sync)
     print(f"[{kind}] compute kernel {t_compute:.1f} ms; copy-engine AlltoAll finished "
           f"{t_copy_done:.1f} ms after the kernel started")
     if kind.startswith("sdma"):

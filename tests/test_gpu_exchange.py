@@ -405,6 +405,28 @@ def test_sdma_host_sync_mode(vccl, seed):
                   lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CE))
 
 
+@pytest.mark.parametrize("sync", ["memops", "event"])
+def test_engines_that_refuse_a_copy_are_passed_over(vccl, sync):
+    """The error path of the SDMA back end, forced from the host (option ce_test_refuse
+    makes the proxy treat the listed engines as refusing every copy): with some engines
+    refusing, their pieces go to the others; with all of them refusing, the pieces are
+    copied through the HIP runtime before the operation completes.  Either way the call's
+    stream is released only with complete receive buffers, and no error is left behind."""
+    torch = require_gpu()
+    lay = wl.random_layout(4100, 6, 3 << 20, align=16)
+    send_np = [wl.payload_bytes(4101, s, int(lay["send_sizes"][s])) for s in range(6)]
+    refused0 = int(vccl.vccl_get_option("ce_refused"))
+    errors0 = int(vccl.vccl_get_option("ce_errors"))
+    _with_options(vccl, {"ce_sync": sync, "ce_test_refuse": 0x5555},
+                  lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CE))
+    assert int(vccl.vccl_get_option("ce_refused")) == refused0, "another engine takes a refused piece"
+    _with_options(vccl, {"ce_sync": sync, "ce_test_refuse": 0xFFFF},
+                  lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CE))
+    assert int(vccl.vccl_get_option("ce_refused")) > refused0, "no engine left: the pieces took the HIP copy"
+    assert int(vccl.vccl_get_option("ce_errors")) == errors0
+    assert int(vccl.vccl_get_option("ce_test_refuse")) == 0
+
+
 def test_many_copy_engine_operations_in_flight(vccl):
     """Several copy-engine calls queued back to back on two streams before any
     synchronisation: operation slots are recycled and every result is right."""
@@ -453,12 +475,13 @@ def test_edge_cases(vccl, mode):
     assert to_host(r_dev[1]).tolist() == [11, 21, SENTINEL]
 
 
-@pytest.mark.parametrize("mode", MODES + ["ce_host", "ce_hip"])
+@pytest.mark.parametrize("mode", MODES + ["ce_host", "ce_event", "ce_memops", "ce_hip"])
 def test_stream_ordering(vccl, mode):
     """The exchange starts after earlier work on the caller's stream and later work
     on that stream sees the received data (a side stream, repeated)."""
     torch = require_gpu()
-    opts = {"ce_host": {"ce_sync": "host"}, "ce_hip": {"ce_kind": "hip_nocu"}}.get(mode, {})
+    opts = {"ce_host": {"ce_sync": "host"}, "ce_event": {"ce_sync": "event"}, "ce_memops": {"ce_sync": "memops"},
+            "ce_hip": {"ce_kind": "hip_nocu"}}.get(mode, {})
     saved = {k: vccl.vccl_get_option(k) for k in opts}
     for k, val in opts.items():
         vccl.vccl_set_option(k, val)
@@ -565,7 +588,7 @@ def test_cu_path_replays_from_a_hip_graph(vccl, P, c):
             assert_same(to_host(recv[r]), want[r], f"replay {rep} recv[{r}]")
 
 
-@pytest.mark.parametrize("kind,sync", [("sdma", "memops"), ("sdma", "host"), ("hip_nocu", "memops")])
+@pytest.mark.parametrize("kind,sync", [("sdma", "memops"), ("sdma", "event"), ("sdma", "host"), ("hip_nocu", "memops")])
 def test_kernels_after_a_copy_engine_exchange_read_fresh_data(vccl, kind, sync):
     """Cache coherence of the copy-engine path: the receive buffers are small enough to
     stay in the L2 caches, a kernel writes and another reads them right before the

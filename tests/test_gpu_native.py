@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 EXE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "native", "gpu_native")
 
 
-@pytest.mark.parametrize("sync", ["memops", "host"])
+@pytest.mark.parametrize("sync", ["memops", "event", "host"])
 def test_native_c_program(sync):
     require_gpu()
     if not os.path.exists(EXE):

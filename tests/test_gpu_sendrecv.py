@@ -98,11 +98,13 @@ def test_config4_ring_p8_64m_full_size(vccl, mode):
 
 def test_ring_sdma_host_sync(vccl):
     torch = require_gpu()
-    vccl.vccl_set_option("ce_sync", "host")
+    saved = vccl.vccl_get_option("ce_sync")
     try:
-        _ring(torch, vccl, vccl.MODE_CE, [700001, 33, 524288 + 1, 0, 99999], misalign=3)
+        for sync in ("host", "event", "memops"):
+            vccl.vccl_set_option("ce_sync", sync)
+            _ring(torch, vccl, vccl.MODE_CE, [700001, 33, 524288 + 1, 0, 99999], misalign=3)
     finally:
-        vccl.vccl_set_option("ce_sync", "memops")
+        vccl.vccl_set_option("ce_sync", saved)
 
 
 @pytest.mark.parametrize("scoped", [1, 0])
@@ -264,7 +266,7 @@ def test_ce_handshake_record_advances(vccl):
     assert again["sender_ns"] >= cpu["sender_ns"] and again["receiver_ns"] >= cpu["receiver_ns"]
 
 
-@pytest.mark.parametrize("kind,sync", [("sdma", "memops"), ("hip_default", "memops")])
+@pytest.mark.parametrize("kind,sync", [("sdma", "memops"), ("sdma", "event"), ("hip_default", "memops")])
 def test_ce_connection_keeps_order_with_many_transfers_outstanding(vccl, kind, sync):
     """Several copy-engine SendRecv calls on the same connections are handed over
     without any wait in between (the calling thread only draws sequence numbers), the
@@ -317,6 +319,71 @@ def test_ce_connection_keeps_order_with_many_transfers_outstanding(vccl, kind, s
     if kind == "sdma":
         # nothing in the sdma hand-over waits for the device: all calls return while the kernel still runs
         assert still_running, f"handing over {calls} transfers took {issue_s * 1e3:.2f} ms: the held stream's kernel had ended"
+
+
+@pytest.mark.parametrize("kind,sync", [("sdma", "memops"), ("sdma", "event"), ("sdma", "host"), ("hip_nocu", "memops")])
+def test_opposite_directions_on_two_held_streams_all_complete(vccl, kind, sync):
+    """The traffic pattern behind the deadlock the paper met with host callbacks (Section
+    3.2, item 3): two independent streams carry SendRecv in opposite directions between
+    the same pair of ranks, and each transfer is posted while a long kernel still holds
+    its own and the other stream.  A runtime that serialises the two streams' host-side
+    work stalls here; the proxy treats every operation on its own: all transfers complete
+    with the right bytes, and one whose stream becomes ready early is not held up by an
+    earlier-posted one whose stream is still busy."""
+    torch = require_gpu()
+    import time
+    n, rounds = (2 << 20) + 48, 3
+    fwd = ([1, 0], [1, 0])                               # send_to, recv_from for the pair (0 -> 1 and 1 -> 0)
+    a_np = [wl.payload_bytes(7100 + i, 0, n) for i in range(rounds)]      # rank 0 -> rank 1, stream A
+    b_np = [wl.payload_bytes(7200 + i, 1, n) for i in range(rounds)]      # rank 1 -> rank 0, stream B
+    a_src = [to_dev(torch, x) for x in a_np]
+    b_src = [to_dev(torch, x) for x in b_np]
+    a_dst = [to_dev(torch, np.full(n + 16, SENTINEL, np.uint8)) for _ in range(rounds)]
+    b_dst = [to_dev(torch, np.full(n + 16, SENTINEL, np.uint8)) for _ in range(rounds)]
+    null = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    A, B = torch.cuda.Stream(), torch.cuda.Stream()
+    sink = [torch.zeros(256 * 256, dtype=torch.float32, device="cuda") for _ in range(2)]
+    saved = (vccl.vccl_get_option("ce_kind"), vccl.vccl_get_option("ce_sync"))
+    vccl.vccl_set_option("ce_kind", kind)
+    vccl.vccl_set_option("ce_sync", sync)
+    try:
+        torch.cuda.synchronize()
+        vccl.vccl_fma_probe(sink[0], 128, 256, 20000, int(A.cuda_stream))       # about 3 ms: A is ready first
+        vccl.vccl_fma_probe(sink[1], 128, 256, 200000, int(B.cuda_stream))      # about 30 ms
+        b_probe_done = torch.cuda.Event()
+        b_probe_done.record(B)
+        a_first_done = torch.cuda.Event()
+        t0 = time.perf_counter()
+        for i in range(rounds):
+            if not (sync == "host" and i == 0):
+                # B's transfer is posted first, while both streams are held
+                vccl.vccl_sendrecv([null, b_src[i]], [0, n], fwd[0], [b_dst[i], null], [n, 0], fwd[1], 2,
+                                   vccl.MODE_CE, int(B.cuda_stream))
+            vccl.vccl_sendrecv([a_src[i], null], [n, 0], fwd[0], [null, a_dst[i]], [0, n], fwd[1], 2,
+                               vccl.MODE_CE, int(A.cuda_stream))
+            if i == 0:
+                a_first_done.record(A)
+                if sync == "host":     # a blocking caller can post B's transfer only now
+                    vccl.vccl_sendrecv([null, b_src[i]], [0, n], fwd[0], [b_dst[i], null], [n, 0], fwd[1], 2,
+                                       vccl.MODE_CE, int(B.cuda_stream))
+        posted_s = time.perf_counter() - t0
+        a_first_done.synchronize()
+        b_still_held = not b_probe_done.query()
+        torch.cuda.synchronize()
+    finally:
+        vccl.vccl_set_option("ce_kind", saved[0])
+        vccl.vccl_set_option("ce_sync", saved[1])
+    for i in range(rounds):
+        want_a, want_b = np.full(n + 16, SENTINEL, np.uint8), np.full(n + 16, SENTINEL, np.uint8)
+        oracle.sendrecv([a_np[i], np.zeros(0, np.uint8)], [n, 0], fwd[0], [np.zeros(0, np.uint8), want_a], [0, n], fwd[1])
+        oracle.sendrecv([np.zeros(0, np.uint8), b_np[i]], [0, n], fwd[0], [want_b, np.zeros(0, np.uint8)], [n, 0], fwd[1])
+        assert_same(to_host(a_dst[i]), want_a, f"round {i}: rank 0 -> 1")
+        assert_same(to_host(b_dst[i]), want_b, f"round {i}: rank 1 -> 0")
+    if kind == "sdma" and sync != "host":
+        # A's first transfer (posted second) finished while B's kernel, and with it B's
+        # earlier-posted transfer, was still waiting.  (The hipMemcpyAsync back end shares
+        # its internal streams between operations and only has to complete.)
+        assert b_still_held, f"posting took {posted_s * 1e3:.1f} ms; A's transfer waited for B's stream"
 
 
 def test_proxy_window_monitor_sees_copy_engine_operations(vccl):
