@@ -395,6 +395,9 @@ int vccl_set_option(const char *key, const char *value) {
     } else if (k == "moe_unpack_variant") {
         if (!in(0, 3)) return fail(VCCL_ERR_ARG, "moe_unpack_variant must be 0..3");
         o.moe_unpack_variant = (int)x;
+    } else if (k == "moe_gather_full") {
+        if (!in(0, 1)) return fail(VCCL_ERR_ARG, "moe_gather_full must be 0 or 1");
+        o.moe_gather_full = (int)x;
     } else if (k == "ce_max_engines") {
         if (!in(0, 16)) return fail(VCCL_ERR_ARG, "ce_max_engines must be 0..16");
         o.ce_max_engines = (int)x;
@@ -462,6 +465,7 @@ int vccl_get_option(const char *key, char *out, int cap) {
     else if (k == "ce_streams") v = o.ce_streams;
     else if (k == "moe_gather_variant") v = o.moe_gather_variant;
     else if (k == "moe_unpack_variant") v = o.moe_unpack_variant;
+    else if (k == "moe_gather_full") v = o.moe_gather_full;
     else if (k == "ce_max_engines") v = o.ce_max_engines;
     else if (k == "check") v = o.check;
     else if (k == "fifo_chunk_bytes") v = o.fifo_chunk_bytes;
@@ -580,7 +584,8 @@ static int moe_pack_common(const void *const *x, const int32_t *const *expert_id
     }
     return launch_moe_pack(c->moe, x, expert_ids, P, tokens, topk, row_bytes, num_experts, experts_per_rank,
                            packed, counts_dev, counts_host, slot_row, bad_ids_dev,
-                           options_of(*c).moe_gather_variant, (hipStream_t)stream);
+                           options_of(*c).moe_gather_variant, options_of(*c).moe_gather_full,
+                           (hipStream_t)stream);
 }
 
 int vccl_moe_pack(const void *const *x, const int32_t *const *expert_ids, int P, int tokens, int topk,
@@ -614,7 +619,7 @@ int vccl_moe_pack_noalloc(const void *const *x, const int32_t *const *expert_ids
     }
     return launch_moe_pack_noalloc(c->device, x, expert_ids, P, tokens, topk, row_bytes, num_experts, packed,
                                    counts_dev, bad_ids_dev, options_of(*c).moe_gather_variant,
-                                   (hipStream_t)stream);
+                                   options_of(*c).moe_gather_full, (hipStream_t)stream);
 }
 
 int vccl_moe_pack_per_rank(const void *const *x, const int32_t *const *expert_ids, int P, int tokens, int topk,
@@ -658,7 +663,8 @@ int vccl_moe_dispatch_fused(const void *const *x, const int32_t *const *expert_i
     }
     return launch_moe_dispatch_fused(c->moe, x, expert_ids, P, tokens, topk, row_bytes, num_experts,
                                      experts_per_rank, recv, recv_capacity_rows, counts_dev, layout_dev,
-                                     layout_host, status_dev, (hipStream_t)stream);
+                                     layout_host, status_dev, options_of(*c).moe_gather_full,
+                                     (hipStream_t)stream);
 }
 
 int vccl_moe_combine_fused(const void *const *back, const uint64_t *back_capacity_rows,

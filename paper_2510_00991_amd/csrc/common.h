@@ -48,6 +48,7 @@ struct Options {
     int cu_fast_path = 1;
     int moe_gather_variant = 208;
     int moe_unpack_variant = 2;
+    int moe_gather_full = 1;   // allow the unchecked gather kernels when pieces and slot groups are whole
     int ce_streams = 4;
     int ce_kind = 0;   // VCCL_CE_*
     int ce_max_engines = 0;
@@ -175,7 +176,7 @@ struct MoeScratch {
 int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P,
                     int tokens, int topk, uint64_t row_bytes, int num_experts, int experts_per_rank,
                     void *const *packed, uint64_t *counts_dev, uint64_t *counts_host,
-                    uint32_t *const *slot_row, uint32_t *bad_ids_dev, int gather_variant,
+                    uint32_t *const *slot_row, uint32_t *bad_ids_dev, int gather_variant, int gather_full,
                     hipStream_t stream);
 
 // The pack for callers that cannot allocate: index data in a file-scope device array
@@ -183,7 +184,7 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
 int moe_static_scratch_init(int device);
 int launch_moe_pack_noalloc(int device, const void *const *x, const int32_t *const *ids, int P, int tokens,
                             int topk, uint64_t row_bytes, int num_experts, void *const *packed,
-                            uint64_t *counts_dev, uint32_t *bad_ids_dev, int gather_variant,
+                            uint64_t *counts_dev, uint32_t *bad_ids_dev, int gather_variant, int gather_full,
                             hipStream_t stream);
 
 // Pack and exchange in one pass: rows go from x[s] straight into recv[r] where the
@@ -192,7 +193,7 @@ int launch_moe_dispatch_fused(MoeScratch &sc, const void *const *x, const int32_
                               int tokens, int topk, uint64_t row_bytes, int num_experts,
                               int experts_per_rank, void *const *recv, const uint64_t *capacity_rows,
                               uint64_t *counts_dev, uint64_t *layout_dev, uint64_t *layout_host,
-                              uint32_t *status_dev, hipStream_t stream);
+                              uint32_t *status_dev, int gather_full, hipStream_t stream);
 
 // The way back in one pass: row t*K+k of out[s] is read straight from back[r].
 int launch_moe_combine_fused(MoeScratch &sc, const void *const *back, const uint64_t *capacity_rows,

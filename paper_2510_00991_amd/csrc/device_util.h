@@ -36,4 +36,21 @@ struct TileDst {
     }
 };
 
+// Division of a block index by a launch-time constant without a division: for
+// 0 <= x < 2^31 and 1 <= d < 2^31, floor(x / d) = (x * m) >> s with l = ceil(log2 d),
+// s = 31 + l, m = ceil(2^s / d) (m < 2^33, so the product fits 64 bits).
+struct FastDiv {
+    uint64_t m;
+    uint32_t s;
+    uint32_t d;
+    FastDiv() = default;
+    explicit FastDiv(uint32_t divisor) : d(divisor) {
+        uint32_t l = 0;
+        while ((1ull << l) < divisor) ++l;
+        s = 31 + l;
+        m = ((1ull << s) + divisor - 1) / divisor;
+    }
+    __device__ __forceinline__ uint32_t div(uint32_t x) const { return (uint32_t)(((uint64_t)x * m) >> s); }
+};
+
 }  // namespace vccl

@@ -39,6 +39,34 @@ struct MoePtrs {       // device arrays of P pointers each, in one allocation
     const uint64_t *capacity_rows;  // fused form: rows each destination rank's receive buffer holds
 };
 constexpr int kPtrArrays = 6;
+
+// The two row buffers of every rank as a kernel argument (up to kInlineRanks ranks): a
+// wavefront of the row-moving kernels then finds its buffers with one scalar load from
+// the kernel-argument segment, instead of a load of the table's address followed by a
+// load from the table - one memory round trip less in front of every row access, which
+// measured 5 % of the gather's run time.  Must be the FIRST kernel argument: it is read
+// in place through the kernel-argument pointer.
+constexpr int kInlineRanks = 64;
+struct RankPtrs {
+    const uint8_t *x[kInlineRanks];
+    uint8_t *packed[kInlineRanks];
+};
+template <bool INL>
+__device__ __forceinline__ const u32x4 *rank_src(const MoePtrs &ptrs, uint32_t rank) {
+    if (INL) {
+        const RankPtrs *rp = reinterpret_cast<const RankPtrs *>((const void *)__builtin_amdgcn_kernarg_segment_ptr());
+        return reinterpret_cast<const u32x4 *>(rp->x[rank]);
+    }
+    return reinterpret_cast<const u32x4 *>(ptrs.x[rank]);
+}
+template <bool INL>
+__device__ __forceinline__ u32x4 *rank_dst(const MoePtrs &ptrs, uint32_t rank) {
+    if (INL) {
+        const RankPtrs *rp = reinterpret_cast<const RankPtrs *>((const void *)__builtin_amdgcn_kernarg_segment_ptr());
+        return reinterpret_cast<u32x4 *>(rp->packed[rank]);
+    }
+    return reinterpret_cast<u32x4 *>(ptrs.packed[rank]);
+}
 constexpr int32_t kDuplicate = -1;   // rank key of a slot whose rank an earlier slot of the token already has
 constexpr int32_t kBadId = -2;       // rank key of a slot whose expert id is out of range
 
@@ -142,31 +170,38 @@ __global__ __launch_bounds__(kMoeThreads) void moe_scan_kernel(int E, uint32_t n
     uint32_t *hr = hist + (size_t)rank * nblk * (size_t)E;
     const int per = (E + kMoeThreads - 1) / kMoeThreads;   // consecutive experts per thread
     const int e0 = (int)tid * per;
+    // pass 1, loads only (they do not depend on each other): pairs per expert
     uint32_t tot[kMaxExperts / kMoeThreads];
     uint32_t mine = 0;
     for (int j = 0; j < per; ++j) {
         const int e = e0 + j;
         uint32_t run = 0;
         if (e < E) {
-            for (uint32_t b = 0; b < nblk; ++b) {   // exclusive sum over blocks, in place
-                const uint32_t c = hr[(size_t)b * E + e];
-                hr[(size_t)b * E + e] = run;
-                run += c;
-            }
+#pragma unroll 8
+            for (uint32_t b = 0; b < nblk; ++b) run += hr[(size_t)b * E + e];
             counts[(size_t)rank * E + e] = run;
         }
         tot[j] = run;
         mine += run;
     }
+    // first row of each expert: exclusive sum across experts (lanes, then wavefronts)
     const uint32_t incl = wave_inclusive_scan(mine, lane);
     if (lane == 63) wave_tot[wave] = incl;
     __syncthreads();
     uint32_t base = incl - mine;
     for (uint32_t w = 0; w < wave; ++w) base += wave_tot[w];
+    // pass 2: first row of each (block, expert) = the expert's first row + pairs in earlier blocks
     for (int j = 0; j < per; ++j) {
         const int e = e0 + j;
-        if (e < E)
-            for (uint32_t b = 0; b < nblk; ++b) hr[(size_t)b * E + e] += base;
+        if (e < E) {
+            uint32_t run = base;
+#pragma unroll 8
+            for (uint32_t b = 0; b < nblk; ++b) {
+                const uint32_t c = hr[(size_t)b * E + e];
+                hr[(size_t)b * E + e] = run;
+                run += c;
+            }
+        }
         base += tot[j];
     }
 }
@@ -255,58 +290,77 @@ __global__ __launch_bounds__(kMoeThreads) void moe_gather_kernel(MoePtrs ptrs, u
 // wavefront w of the workgroup serves slot k = 8*group + w.
 constexpr int kPieceVecs = 128;   // 2 KiB
 constexpr int kSlotWaves = 8;
-template <bool NT>
-__global__ __launch_bounds__(kSlotWaves * 64) void moe_gather_shared_kernel(MoePtrs ptrs, uint32_t tokens, int K,
-                                                                            uint32_t row_vecs, uint32_t pieces,
-                                                                            uint32_t kgroups, const uint32_t *dest,
-                                                                            uint32_t npairs) {
-    const uint32_t rank = blockIdx.y;
-    const uint32_t per_token = pieces * kgroups;
-    const uint32_t t = blockIdx.x / per_token;
-    const uint32_t rem = blockIdx.x - t * per_token;
-    const uint32_t piece = rem / kgroups;
-    // the wavefront index is the same in all lanes: say so, which makes the
-    // destination-row lookup a scalar load
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t k = (rem - piece * kgroups) * kSlotWaves + wave;
-    if (t >= tokens || k >= (uint32_t)K) return;
-    const uint32_t v0 = piece * kPieceVecs + (threadIdx.x & 63u), v1 = v0 + 64u;
-    const u32x4 *row = reinterpret_cast<const u32x4 *>(ptrs.x[rank]) + (size_t)t * row_vecs;
-    // Row loads go out before the destination row is known (for a dropped pair they
-    // are wasted, which is rare).  Cached loads on purpose: the other 7 wavefronts
-    // read the same piece.
-    u32x4 r0 = {0, 0, 0, 0}, r1 = {0, 0, 0, 0};
-    if (v0 < row_vecs) r0 = row[v0];
-    if (v1 < row_vecs) r1 = row[v1];
-    const uint32_t j = dest[(size_t)rank * npairs + (size_t)t * K + k];
-    if (j == kDropped) return;
-    u32x4 *o = reinterpret_cast<u32x4 *>(ptrs.packed[rank]) + (size_t)j * row_vecs;
-    if (v0 < row_vecs) {
-        if (NT) __builtin_nontemporal_store(r0, o + v0);
-        else o[v0] = r0;
+// FULL: every piece is whole (row_vecs a multiple of kPieceVecs) and every slot group is
+// full (K a multiple of kSlotWaves), so no wavefront has anything to test but "dropped".
+// It is compiled for 7 wavefronts per SIMD instead of 8, which measured 1.43 against
+// 1.46 ms on the 7.5 GB dispatch (6: 1.44 ms; 5 and fewer: 1.8 ms).
+#define VCCL_GATHER_SHARED_BODY(FULL_)                                                                   \
+    (void)by_value;                                                                                      \
+    const uint32_t rank = blockIdx.y;                                                                    \
+    const uint32_t t = per_token.div(blockIdx.x);                                                        \
+    const uint32_t rem = blockIdx.x - t * per_token.d;                                                   \
+    const uint32_t piece = kgroups.div(rem);                                                             \
+    /* the wavefront index is the same in all lanes: say so, which makes the destination-row lookup a   \
+       scalar load */                                                                                    \
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);                              \
+    const uint32_t k = (rem - piece * kgroups.d) * kSlotWaves + wave;                                    \
+    if (!(FULL_) && (t >= tokens || k >= (uint32_t)K)) return;                                           \
+    const uint32_t v0 = piece * kPieceVecs + (threadIdx.x & 63u), v1 = v0 + 64u;                         \
+    const u32x4 *row = rank_src<INL>(ptrs, rank) + (size_t)t * row_vecs;                                 \
+    /* Row loads go out before the destination row is known (for a dropped pair they are wasted, which  \
+       is rare).  Cached loads on purpose: the other 7 wavefronts read the same piece. */               \
+    u32x4 r0 = {0, 0, 0, 0}, r1 = {0, 0, 0, 0};                                                          \
+    if ((FULL_) || v0 < row_vecs) r0 = row[v0];                                                          \
+    if ((FULL_) || v1 < row_vecs) r1 = row[v1];                                                          \
+    const uint32_t j = dest[(size_t)rank * npairs + (size_t)t * K + k];                                  \
+    /* (an empty statement that needs the loaded vectors: without it the compiler moves the row loads  \
+       behind the test below, and every wavefront waits for its look-up before it asks for its row -   \
+       1.74 instead of 1.43 ms on the 7.5 GB dispatch) */                                               \
+    asm volatile("" ::"v"(r0), "v"(r1));                                                                 \
+    if (j == kDropped) return;                                                                           \
+    u32x4 *o = rank_dst<INL>(ptrs, rank) + (size_t)j * row_vecs;                                         \
+    if ((FULL_) || v0 < row_vecs) {                                                                      \
+        if (NT) __builtin_nontemporal_store(r0, o + v0);                                                 \
+        else o[v0] = r0;                                                                                 \
+    }                                                                                                    \
+    if ((FULL_) || v1 < row_vecs) {                                                                      \
+        if (NT) __builtin_nontemporal_store(r1, o + v1);                                                 \
+        else o[v1] = r1;                                                                                 \
     }
-    if (v1 < row_vecs) {
-        if (NT) __builtin_nontemporal_store(r1, o + v1);
-        else o[v1] = r1;
-    }
+
+template <bool NT, bool INL>
+__global__ __launch_bounds__(kSlotWaves * 64) void moe_gather_shared_kernel(RankPtrs by_value, MoePtrs ptrs,
+                                                                            uint32_t tokens, int K, uint32_t row_vecs,
+                                                                            FastDiv per_token, FastDiv kgroups,
+                                                                            const uint32_t *dest, uint32_t npairs) {
+    VCCL_GATHER_SHARED_BODY(false)
 }
+
+template <bool NT, bool INL>
+__global__ __launch_bounds__(kSlotWaves * 64) __attribute__((amdgpu_waves_per_eu(7, 7)))
+void moe_gather_shared_full_kernel(RankPtrs by_value, MoePtrs ptrs, uint32_t tokens, int K, uint32_t row_vecs,
+                                   FastDiv per_token, FastDiv kgroups, const uint32_t *dest, uint32_t npairs) {
+    VCCL_GATHER_SHARED_BODY(true)
+}
+#undef VCCL_GATHER_SHARED_BODY
 
 // Gather, piece-loop form: one single-wavefront workgroup per 2 KiB piece of a
 // token's row loads the piece once and stores it for every slot that is not
 // dropped.  This is the better shape when most slots are dropped, as in the
 // per-rank form of the dispatch (a token reaches about 3 of 8 ranks on the
 // measured routing): no wavefront is launched only to find its slot empty.
-template <bool NT>
-__global__ __launch_bounds__(64) void moe_gather_piece_loop_kernel(MoePtrs ptrs, uint32_t tokens, int K,
-                                                                   uint32_t row_vecs, uint32_t pieces,
+template <bool NT, bool INL>
+__global__ __launch_bounds__(64) void moe_gather_piece_loop_kernel(RankPtrs by_value, MoePtrs ptrs, uint32_t tokens,
+                                                                   int K, uint32_t row_vecs, FastDiv pieces,
                                                                    const uint32_t *dest, uint32_t npairs) {
+    (void)by_value;
     const uint32_t rank = blockIdx.y;
-    const uint32_t t = blockIdx.x / pieces;
-    const uint32_t piece = blockIdx.x - t * pieces;
+    const uint32_t t = pieces.div(blockIdx.x);
+    const uint32_t piece = blockIdx.x - t * pieces.d;
     if (t >= tokens) return;
     const uint32_t v0 = piece * kPieceVecs + threadIdx.x, v1 = v0 + 64u;
-    const u32x4 *row = reinterpret_cast<const u32x4 *>(ptrs.x[rank]) + (size_t)t * row_vecs;
-    u32x4 *out = reinterpret_cast<u32x4 *>(ptrs.packed[rank]);
+    const u32x4 *row = rank_src<INL>(ptrs, rank) + (size_t)t * row_vecs;
+    u32x4 *out = rank_dst<INL>(ptrs, rank);
     u32x4 r0 = {0, 0, 0, 0}, r1 = {0, 0, 0, 0};
     if (v0 < row_vecs) r0 = __builtin_nontemporal_load(row + v0);   // read once
     if (v1 < row_vecs) r1 = __builtin_nontemporal_load(row + v1);
@@ -398,35 +452,48 @@ __global__ __launch_bounds__(kMoeThreads) void moe_pair_target_kernel(MoePtrs pt
 // Fused dispatch, gather step: the shared-piece gather, except that the row of
 // pair (t, k) goes straight into the receive buffer of the rank that hosts its
 // expert, at the place the exchange would have put it.
-template <bool NT>
-__global__ __launch_bounds__(kSlotWaves * 64) void moe_gather_fused_kernel(MoePtrs ptrs, uint32_t tokens, int K,
-                                                                           uint32_t row_vecs, uint32_t pieces,
-                                                                           uint32_t kgroups, uint32_t npairs,
-                                                                           u32x4 *const *target) {
-    const uint32_t rank = blockIdx.y;
-    const uint32_t per_token = pieces * kgroups;
-    const uint32_t t = blockIdx.x / per_token;
-    const uint32_t rem = blockIdx.x - t * per_token;
-    const uint32_t piece = rem / kgroups;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t k = (rem - piece * kgroups) * kSlotWaves + wave;
-    if (t >= tokens || k >= (uint32_t)K) return;
-    const uint32_t v0 = piece * kPieceVecs + (threadIdx.x & 63u), v1 = v0 + 64u;
-    const u32x4 *row = reinterpret_cast<const u32x4 *>(ptrs.x[rank]) + (size_t)t * row_vecs;
-    u32x4 r0 = {0, 0, 0, 0}, r1 = {0, 0, 0, 0};
-    if (v0 < row_vecs) r0 = row[v0];
-    if (v1 < row_vecs) r1 = row[v1];
-    u32x4 *o = target[(size_t)rank * npairs + (size_t)t * K + k];
-    if (!o) return;
-    if (v0 < row_vecs) {
-        if (NT) __builtin_nontemporal_store(r0, o + v0);
-        else o[v0] = r0;
+#define VCCL_GATHER_FUSED_BODY(FULL_)                                                                    \
+    (void)by_value;                                                                                      \
+    const uint32_t rank = blockIdx.y;                                                                    \
+    const uint32_t t = per_token.div(blockIdx.x);                                                        \
+    const uint32_t rem = blockIdx.x - t * per_token.d;                                                   \
+    const uint32_t piece = kgroups.div(rem);                                                             \
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);                              \
+    const uint32_t k = (rem - piece * kgroups.d) * kSlotWaves + wave;                                    \
+    if (!(FULL_) && (t >= tokens || k >= (uint32_t)K)) return;                                           \
+    const uint32_t v0 = piece * kPieceVecs + (threadIdx.x & 63u), v1 = v0 + 64u;                         \
+    const u32x4 *row = rank_src<INL>(ptrs, rank) + (size_t)t * row_vecs;                                 \
+    u32x4 r0 = {0, 0, 0, 0}, r1 = {0, 0, 0, 0};                                                          \
+    if ((FULL_) || v0 < row_vecs) r0 = row[v0];                                                          \
+    if ((FULL_) || v1 < row_vecs) r1 = row[v1];                                                          \
+    u32x4 *o = target[(size_t)rank * npairs + (size_t)t * K + k];                                        \
+    asm volatile("" ::"v"(r0), "v"(r1));   /* keeps the row loads in front of the test, as above */      \
+    if (!o) return;                                                                                      \
+    if ((FULL_) || v0 < row_vecs) {                                                                      \
+        if (NT) __builtin_nontemporal_store(r0, o + v0);                                                 \
+        else o[v0] = r0;                                                                                 \
+    }                                                                                                    \
+    if ((FULL_) || v1 < row_vecs) {                                                                      \
+        if (NT) __builtin_nontemporal_store(r1, o + v1);                                                 \
+        else o[v1] = r1;                                                                                 \
     }
-    if (v1 < row_vecs) {
-        if (NT) __builtin_nontemporal_store(r1, o + v1);
-        else o[v1] = r1;
-    }
+
+template <bool NT, bool INL>
+__global__ __launch_bounds__(kSlotWaves * 64) void moe_gather_fused_kernel(RankPtrs by_value, MoePtrs ptrs,
+                                                                           uint32_t tokens, int K, uint32_t row_vecs,
+                                                                           FastDiv per_token, FastDiv kgroups,
+                                                                           uint32_t npairs, u32x4 *const *target) {
+    VCCL_GATHER_FUSED_BODY(false)
 }
+
+// whole pieces, whole slot groups, three workgroups per compute unit (see moe_gather_shared_full_kernel)
+template <bool NT, bool INL>
+__global__ __launch_bounds__(kSlotWaves * 64) __attribute__((amdgpu_waves_per_eu(7, 7)))
+void moe_gather_fused_full_kernel(RankPtrs by_value, MoePtrs ptrs, uint32_t tokens, int K, uint32_t row_vecs,
+                                  FastDiv per_token, FastDiv kgroups, uint32_t npairs, u32x4 *const *target) {
+    VCCL_GATHER_FUSED_BODY(true)
+}
+#undef VCCL_GATHER_FUSED_BODY
 
 // Inverse of the gather (combine direction): one workgroup per pair p = t*K + k
 // copies the packed row that pair was sent to back to row p of `out`.  Writes sweep
@@ -460,18 +527,19 @@ __global__ __launch_bounds__(kMoeThreads) void moe_scatter_back_kernel(MoePtrs p
 // Combine direction, tile form: one single-wavefront workgroup per 1 KiB tile of
 // `out`, in address order - the launch shape of the exchange copy kernel, which
 // HBM serves best; the reads hop between expert regions row by row.
-template <int POL, int TILES>
-__global__ __launch_bounds__(64) void moe_scatter_back_tiles_kernel(MoePtrs ptrs, uint32_t row_vecs,
-                                                                    uint32_t groups_per_row, const uint32_t *dest,
+template <int POL, int TILES, bool INL>
+__global__ __launch_bounds__(64) void moe_scatter_back_tiles_kernel(RankPtrs by_value, MoePtrs ptrs, uint32_t row_vecs,
+                                                                    FastDiv groups_per_row, const uint32_t *dest,
                                                                     uint32_t npairs) {
+    (void)by_value;
     const uint32_t rank = blockIdx.y;
-    const uint32_t p = blockIdx.x / groups_per_row;
-    const uint32_t v0 = (blockIdx.x - p * groups_per_row) * (64u * TILES);
+    const uint32_t p = groups_per_row.div(blockIdx.x);
+    const uint32_t v0 = (blockIdx.x - p * groups_per_row.d) * (64u * TILES);
     if (p >= npairs) return;
     const uint32_t j = dest[(size_t)rank * npairs + p];
     if (j == kDropped) return;
-    const u32x4 *row = reinterpret_cast<const u32x4 *>(ptrs.x[rank]) + (size_t)j * row_vecs + v0;   // packed side
-    const TileDst<POL> o(reinterpret_cast<u32x4 *>(ptrs.packed[rank]) + (size_t)p * row_vecs + v0);
+    const u32x4 *row = rank_src<INL>(ptrs, rank) + (size_t)j * row_vecs + v0;   // packed side
+    const TileDst<POL> o(rank_dst<INL>(ptrs, rank) + (size_t)p * row_vecs + v0);
     u32x4 r[TILES];
 #pragma unroll
     for (int u = 0; u < TILES; ++u)
@@ -507,17 +575,18 @@ __global__ __launch_bounds__(kMoeThreads) void moe_pair_source_kernel(MoePtrs pt
 }
 
 // ptrs.packed holds the P outputs; 1 KiB single-wavefront tiles in output order.
-template <int POL>
-__global__ __launch_bounds__(64) void moe_combine_fused_kernel(MoePtrs ptrs, uint32_t row_vecs,
-                                                               uint32_t tiles_per_row, uint32_t npairs,
+template <int POL, bool INL>
+__global__ __launch_bounds__(64) void moe_combine_fused_kernel(RankPtrs by_value, MoePtrs ptrs, uint32_t row_vecs,
+                                                               FastDiv tiles_per_row, uint32_t npairs,
                                                                const u32x4 *const *source) {
+    (void)by_value;
     const uint32_t rank = blockIdx.y;
-    const uint32_t p = blockIdx.x / tiles_per_row;
-    const uint32_t v0 = (blockIdx.x - p * tiles_per_row) * 64u;
+    const uint32_t p = tiles_per_row.div(blockIdx.x);
+    const uint32_t v0 = (blockIdx.x - p * tiles_per_row.d) * 64u;
     if (p >= npairs) return;
     const u32x4 *row = source[(size_t)rank * npairs + p];
     if (!row) return;
-    const TileDst<POL> o(reinterpret_cast<u32x4 *>(ptrs.packed[rank]) + (size_t)p * row_vecs + v0);
+    const TileDst<POL> o(rank_dst<INL>(ptrs, rank) + (size_t)p * row_vecs + v0);
     if (v0 + threadIdx.x < row_vecs) o.store(threadIdx.x, ld16<POL>(row + v0 + threadIdx.x));
 }
 
@@ -561,9 +630,11 @@ int moe_static_scratch_init(int device) {
     return VCCL_OK;
 }
 
+constexpr int kTableRanks = 64;   // ranks whose pointer table fits a kernel argument
 struct PtrBlock {   // the rank-pointer table as a kernel argument
-    void *p[kPtrArrays * kStaticMaxRanks];
+    void *p[kPtrArrays * kTableRanks];
 };
+static_assert(sizeof(PtrBlock) <= 3072 && kStaticMaxRanks <= kTableRanks, "kernel-argument budget");
 __global__ __launch_bounds__(kMoeThreads) void moe_store_ptrs_kernel(PtrBlock blk, void **table, int n) {
     const int i = blockIdx.x * kMoeThreads + threadIdx.x;
     if (i < n) table[i] = blk.p[i];
@@ -667,8 +738,8 @@ static int moe_index_launches(const MoeWork &w, int P, int tokens, int topk, int
     return VCCL_OK;
 }
 
-// The allocating entry points: grow the library-owned scratch as needed, upload the
-// pointer table through pinned staging, then launches 1-3.  `a` / `b` are the two
+// The allocating entry points: grow the library-owned scratch as needed, put the
+// pointer table on the device, then launches 1-3.  `a` / `b` are the two
 // row buffers of every rank in the roles (read side, written side) of launch 4.
 static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *const *ids, int P,
                            int tokens, int topk, int num_experts, int experts_per_rank,
@@ -678,9 +749,15 @@ static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *
                            uint64_t **counts_out = nullptr, uint64_t **extra_out = nullptr) {
     const size_t need = moe_words_needed(P, tokens, topk, num_experts, experts_per_rank, extra_words);
     if (!sc.done) VCCL_HIP(hipEventCreateWithFlags(&sc.done, hipEventDisableTiming));
-    // The scratch is shared: a new call starts after the previous one has finished
-    // with it on the device, and the pinned pointer staging is free again.
-    VCCL_HIP(hipEventSynchronize(sc.done));
+    // The scratch is shared between calls.  Up to kTableRanks ranks the pointer table
+    // reaches the device as a kernel argument, so the only thing a new call has to wait
+    // for is the previous call's kernels, and the stream can do that waiting: calls
+    // follow each other without the host in between.  The host waits only when memory
+    // is about to be reallocated, or (more ranks) when the pinned staging is reused.
+    const bool grow = need > sc.hist_n || (size_t)kPtrArrays * P > sc.ptrs_n;
+    const bool by_kernel = P <= kTableRanks;
+    if (grow || !by_kernel) VCCL_HIP(hipEventSynchronize(sc.done));
+    else VCCL_HIP(hipStreamWaitEvent(stream, sc.done, 0));
     if (need > sc.hist_n) {
         if (sc.hist) VCCL_HIP(hipFree(sc.hist));
         sc.hist = nullptr;
@@ -698,18 +775,42 @@ static int moe_index_phase(MoeScratch &sc, const void *const *a, const int32_t *
         VCCL_HIP(hipHostMalloc((void **)&sc.ptrs_host, (size_t)kPtrArrays * P * sizeof(void *), hipHostMallocDefault));
         sc.ptrs_n = (size_t)kPtrArrays * P;
     }
-    moe_fill_ptr_table(sc.ptrs_host, sc.hist, a, ids, P, tokens, topk, num_experts, experts_per_rank, slot_row, b,
-                       capacity_rows);
-    VCCL_HIP(hipMemcpyAsync(sc.ptrs, sc.ptrs_host, (size_t)kPtrArrays * P * sizeof(void *),
-                            hipMemcpyHostToDevice, stream));
+    if (by_kernel) {
+        PtrBlock blk;
+        moe_fill_ptr_table(blk.p, sc.hist, a, ids, P, tokens, topk, num_experts, experts_per_rank, slot_row, b,
+                           capacity_rows);
+        const int n = kPtrArrays * P;
+        for (int i = n; i < kPtrArrays * kTableRanks; ++i) blk.p[i] = nullptr;
+        moe_store_ptrs_kernel<<<dim3((n + kMoeThreads - 1) / kMoeThreads), dim3(kMoeThreads), 0, stream>>>(blk, sc.ptrs, n);
+        VCCL_HIP(hipGetLastError());
+    } else {
+        moe_fill_ptr_table(sc.ptrs_host, sc.hist, a, ids, P, tokens, topk, num_experts, experts_per_rank, slot_row,
+                           b, capacity_rows);
+        VCCL_HIP(hipMemcpyAsync(sc.ptrs, sc.ptrs_host, (size_t)kPtrArrays * P * sizeof(void *),
+                                hipMemcpyHostToDevice, stream));
+    }
     const MoeWork w{sc.hist, sc.ptrs};
     return moe_index_launches(w, P, tokens, topk, num_experts, experts_per_rank, counts_dev, bad_ids_dev, stream,
                               ptrs_out, dest_out, counts_out, extra_out);
 }
 
+// The rank buffers as a kernel argument (read side `a`, written side `b`; either may be
+// null when a kernel does not use that side); false when there are too many ranks.
+static bool rank_ptrs_inline(RankPtrs &rp, const void *const *a, void *const *b, int P) {
+    if (P > kInlineRanks) return false;
+    for (int s = 0; s < kInlineRanks; ++s) {
+        rp.x[s] = (s < P && a) ? static_cast<const uint8_t *>(a[s]) : nullptr;
+        rp.packed[s] = (s < P && b) ? static_cast<uint8_t *>(b[s]) : nullptr;
+    }
+    return true;
+}
+
 // Launch 4 of the pack: the row gather in the selected form.
-static int moe_launch_gather(const MoePtrs &ptrs, const uint32_t *dest, int P, int tokens, int topk,
-                             uint64_t row_bytes, int experts_per_rank, int gather_variant, hipStream_t stream) {
+static int moe_launch_gather(const MoePtrs &ptrs, const void *const *x, void *const *packed, const uint32_t *dest,
+                             int P, int tokens, int topk, uint64_t row_bytes, int experts_per_rank,
+                             int gather_variant, int gather_full, hipStream_t stream) {
+    RankPtrs rp;
+    const bool inl = rank_ptrs_inline(rp, x, packed, P);
     const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
     const uint32_t tok_blocks = ((uint32_t)tokens + kMoeThreads / 64 - 1) / (kMoeThreads / 64);
     const dim3 g(tok_blocks, P), b(kMoeThreads);
@@ -724,17 +825,33 @@ static int moe_launch_gather(const MoePtrs &ptrs, const uint32_t *dest, int P, i
     if ((gather_variant == 408 || gather_variant == 508) && loop_grid > 0x7fffffffull) gather_variant = 116;
     const dim3 gl((uint32_t)loop_grid, P), bl(64);
     const dim3 gs((uint32_t)shared_grid, P), bs(kSlotWaves * 64);
+    const FastDiv dpieces(pieces), dkgroups(kgroups), dper_token(pieces * kgroups);
+    const uint32_t ut = (uint32_t)tokens;
+    // whole pieces and whole slot groups only (gather_full = 0 keeps the checked kernel, for tests)
+    const bool full = gather_full && rv % kPieceVecs == 0 && topk % kSlotWaves == 0;
+#define VCCL_GATHER(KERNEL, NT, GRID, BLOCK, LDS, ...)                                            \
+    do {                                                                                          \
+        if (inl) KERNEL<NT, true><<<GRID, BLOCK, LDS, stream>>>(rp, ptrs, __VA_ARGS__);            \
+        else KERNEL<NT, false><<<GRID, BLOCK, LDS, stream>>>(rp, ptrs, __VA_ARGS__);               \
+    } while (0)
     switch (gather_variant) {
-        case 408: moe_gather_piece_loop_kernel<true><<<gl, bl, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, dest, npairs); break;
-        case 508: moe_gather_piece_loop_kernel<false><<<gl, bl, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, dest, npairs); break;
-        case 208: moe_gather_shared_kernel<true><<<gs, bs, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, dest, npairs); break;
-        case 308: moe_gather_shared_kernel<false><<<gs, bs, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, dest, npairs); break;
+        case 408: VCCL_GATHER(moe_gather_piece_loop_kernel, true, gl, bl, 0, ut, topk, rv, dpieces, dest, npairs); break;
+        case 508: VCCL_GATHER(moe_gather_piece_loop_kernel, false, gl, bl, 0, ut, topk, rv, dpieces, dest, npairs); break;
+        case 208:
+            if (full) VCCL_GATHER(moe_gather_shared_full_kernel, true, gs, bs, 0, ut, topk, rv, dper_token, dkgroups, dest, npairs);
+            else VCCL_GATHER(moe_gather_shared_kernel, true, gs, bs, 0, ut, topk, rv, dper_token, dkgroups, dest, npairs);
+            break;
+        case 308:
+            if (full) VCCL_GATHER(moe_gather_shared_full_kernel, false, gs, bs, 0, ut, topk, rv, dper_token, dkgroups, dest, npairs);
+            else VCCL_GATHER(moe_gather_shared_kernel, false, gs, bs, 0, ut, topk, rv, dper_token, dkgroups, dest, npairs);
+            break;
         case 4: moe_gather_kernel<4, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
         case 16: moe_gather_kernel<16, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
         case 108: moe_gather_kernel<8, false><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
         case 116: moe_gather_kernel<16, false><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
         default: moe_gather_kernel<8, true><<<g, b, 0, stream>>>(ptrs, (uint32_t)tokens, topk, rv, dest, npairs); break;
     }
+#undef VCCL_GATHER
     VCCL_HIP(hipGetLastError());
     return VCCL_OK;
 }
@@ -743,7 +860,7 @@ static int moe_launch_gather(const MoePtrs &ptrs, const uint32_t *dest, int P, i
 // No event guards the scratch: calls that overlap on one device race (documented).
 int launch_moe_pack_noalloc(int device, const void *const *x, const int32_t *const *ids, int P, int tokens,
                             int topk, uint64_t row_bytes, int num_experts, void *const *packed,
-                            uint64_t *counts_dev, uint32_t *bad_ids_dev, int gather_variant,
+                            uint64_t *counts_dev, uint32_t *bad_ids_dev, int gather_variant, int gather_full,
                             hipStream_t stream) {
     if (device < 0 || device >= kStaticMaxDevices || !g_static_scratch[device])
         return fail(VCCL_ERR_NOT_INIT, "the static scratch of device %d has not been set up (vccl_init does it)", device);
@@ -761,7 +878,7 @@ int launch_moe_pack_noalloc(int device, const void *const *x, const int32_t *con
     PtrBlock blk;
     moe_fill_ptr_table(blk.p, w.words, x, ids, P, tokens, topk, num_experts, 0, nullptr, packed, nullptr);
     const int n = kPtrArrays * P;
-    for (int i = n; i < kPtrArrays * kStaticMaxRanks; ++i) blk.p[i] = nullptr;
+    for (int i = n; i < kPtrArrays * kTableRanks; ++i) blk.p[i] = nullptr;
     moe_store_ptrs_kernel<<<dim3((n + kMoeThreads - 1) / kMoeThreads), dim3(kMoeThreads), 0, stream>>>(blk, w.ptrs, n);
     VCCL_HIP(hipGetLastError());
     // Nothing in the scratch has to start at zero: every histogram word, destination row
@@ -772,14 +889,14 @@ int launch_moe_pack_noalloc(int device, const void *const *x, const int32_t *con
                                 nullptr, nullptr);
     if (rc) return rc;
     if ((uint32_t)tokens * (uint32_t)topk)
-        return moe_launch_gather(ptrs, dest, P, tokens, topk, row_bytes, 0, gather_variant, stream);
+        return moe_launch_gather(ptrs, x, packed, dest, P, tokens, topk, row_bytes, 0, gather_variant, gather_full, stream);
     return VCCL_OK;
 }
 
 int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *ids, int P, int tokens,
                     int topk, uint64_t row_bytes, int num_experts, int experts_per_rank,
                     void *const *packed, uint64_t *counts_dev, uint64_t *counts_host,
-                    uint32_t *const *slot_row, uint32_t *bad_ids_dev, int gather_variant,
+                    uint32_t *const *slot_row, uint32_t *bad_ids_dev, int gather_variant, int gather_full,
                     hipStream_t stream) {
     const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
     std::lock_guard<std::mutex> lk(sc.mu);
@@ -789,7 +906,8 @@ int launch_moe_pack(MoeScratch &sc, const void *const *x, const int32_t *const *
                              nullptr, 0, counts_dev, bad_ids_dev, stream, &ptrs, &dest);
     if (rc) return rc;
     if (npairs) {
-        rc = moe_launch_gather(ptrs, dest, P, tokens, topk, row_bytes, experts_per_rank, gather_variant, stream);
+        rc = moe_launch_gather(ptrs, x, packed, dest, P, tokens, topk, row_bytes, experts_per_rank, gather_variant,
+                               gather_full, stream);
         if (rc) return rc;
         if (experts_per_rank > 0 && slot_row) {
             moe_slot_row_kernel<<<dim3(((uint32_t)tokens + kMoeThreads - 1) / kMoeThreads, P), dim3(kMoeThreads),
@@ -809,7 +927,7 @@ int launch_moe_dispatch_fused(MoeScratch &sc, const void *const *x, const int32_
                               int topk, uint64_t row_bytes, int num_experts, int experts_per_rank,
                               void *const *recv, const uint64_t *capacity_rows, uint64_t *counts_dev,
                               uint64_t *layout_dev, uint64_t *layout_host, uint32_t *status_dev,
-                              hipStream_t stream) {
+                              int gather_full, hipStream_t stream) {
     const uint32_t npairs = (uint32_t)tokens * (uint32_t)topk;
     const uint32_t rv = (uint32_t)(row_bytes >> 4);
     const uint32_t pieces = (rv + kPieceVecs - 1) / kPieceVecs;
@@ -837,8 +955,16 @@ int launch_moe_dispatch_fused(MoeScratch &sc, const void *const *x, const int32_
         moe_pair_target_kernel<<<dim3((npairs + kMoeThreads - 1) / kMoeThreads, P), dim3(kMoeThreads), 0, stream>>>(
             ptrs, rv, dest, npairs, experts_per_rank, delta, P, target);
         VCCL_HIP(hipGetLastError());
-        moe_gather_fused_kernel<true><<<dim3((uint32_t)grid, P), dim3(kSlotWaves * 64), 0, stream>>>(
-            ptrs, (uint32_t)tokens, topk, rv, pieces, kgroups, npairs, target);
+        RankPtrs rp;
+        const FastDiv dkgroups(kgroups), dper_token(pieces * kgroups);
+        const dim3 gg((uint32_t)grid, P), gb(kSlotWaves * 64);
+        const bool inl = rank_ptrs_inline(rp, x, nullptr, P);
+        const bool full = gather_full && rv % kPieceVecs == 0 && topk % kSlotWaves == 0;
+        const uint32_t ut = (uint32_t)tokens;
+        if (full && inl) moe_gather_fused_full_kernel<true, true><<<gg, gb, 0, stream>>>(rp, ptrs, ut, topk, rv, dper_token, dkgroups, npairs, target);
+        else if (full) moe_gather_fused_full_kernel<true, false><<<gg, gb, 0, stream>>>(rp, ptrs, ut, topk, rv, dper_token, dkgroups, npairs, target);
+        else if (inl) moe_gather_fused_kernel<true, true><<<gg, gb, 0, stream>>>(rp, ptrs, ut, topk, rv, dper_token, dkgroups, npairs, target);
+        else moe_gather_fused_kernel<true, false><<<gg, gb, 0, stream>>>(rp, ptrs, ut, topk, rv, dper_token, dkgroups, npairs, target);
         VCCL_HIP(hipGetLastError());
     }
     if (layout_host)
@@ -878,8 +1004,13 @@ int launch_moe_combine_fused(MoeScratch &sc, const void *const *back, const uint
         moe_pair_source_kernel<<<dim3((npairs + kMoeThreads - 1) / kMoeThreads, P), dim3(kMoeThreads), 0, stream>>>(
             ptrs, rv, dest, npairs, experts_per_rank, delta, P, source);
         VCCL_HIP(hipGetLastError());
-        moe_combine_fused_kernel<2><<<dim3((uint32_t)grid, P), dim3(64), 0, stream>>>(ptrs, rv, tiles_per_row,
-                                                                                      npairs, source);
+        RankPtrs rp;
+        const FastDiv dtiles(tiles_per_row);
+        const dim3 gg((uint32_t)grid, P), gb(64);
+        if (rank_ptrs_inline(rp, nullptr, out, P))
+            moe_combine_fused_kernel<2, true><<<gg, gb, 0, stream>>>(rp, ptrs, rv, dtiles, npairs, source);
+        else
+            moe_combine_fused_kernel<2, false><<<gg, gb, 0, stream>>>(rp, ptrs, rv, dtiles, npairs, source);
         VCCL_HIP(hipGetLastError());
     }
     VCCL_HIP(hipEventRecord(sc.done, stream));
@@ -903,9 +1034,18 @@ int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *
         const uint64_t tile_grid = (uint64_t)npairs * groups_per_row;
         if (unpack_variant != 0 && tile_grid <= 0x7fffffffull && rv) {
             const dim3 g((uint32_t)tile_grid, P), b(64);
-            if (unpack_variant == 3) moe_scatter_back_tiles_kernel<2, 2><<<g, b, 0, stream>>>(ptrs, rv, groups_per_row, dest, npairs);
-            else if (unpack_variant == 2) moe_scatter_back_tiles_kernel<2, 1><<<g, b, 0, stream>>>(ptrs, rv, groups_per_row, dest, npairs);
-            else moe_scatter_back_tiles_kernel<1, 1><<<g, b, 0, stream>>>(ptrs, rv, groups_per_row, dest, npairs);
+            RankPtrs rp;
+            const bool inl = rank_ptrs_inline(rp, packed, out, P);
+            const FastDiv dgroups(groups_per_row);
+#define VCCL_UNPACK(POL, TILES)                                                                                   \
+    do {                                                                                                          \
+        if (inl) moe_scatter_back_tiles_kernel<POL, TILES, true><<<g, b, 0, stream>>>(rp, ptrs, rv, dgroups, dest, npairs);  \
+        else moe_scatter_back_tiles_kernel<POL, TILES, false><<<g, b, 0, stream>>>(rp, ptrs, rv, dgroups, dest, npairs); \
+    } while (0)
+            if (unpack_variant == 3) VCCL_UNPACK(2, 2);
+            else if (unpack_variant == 2) VCCL_UNPACK(2, 1);
+            else VCCL_UNPACK(1, 1);
+#undef VCCL_UNPACK
         } else {
             moe_scatter_back_kernel<<<dim3(npairs, P), dim3(kMoeThreads), 0, stream>>>(ptrs, rv, dest, npairs);
         }

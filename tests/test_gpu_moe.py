@@ -200,6 +200,42 @@ def test_kernel_variants_roundtrip(vccl, gather, unpack, shape):
         vccl.vccl_set_option("moe_unpack_variant", saved[1])
 
 
+@pytest.mark.parametrize("full", [1, 0])
+@pytest.mark.parametrize("shape", [(3, 257, 8, 24, 4096), (2, 130, 16, 32, 2048), (4, 64, 8, 8, 14336)])
+def test_whole_piece_shapes_with_and_without_the_unchecked_gather(vccl, shape, full):
+    """Rows that are whole 2 KiB pieces with slot counts that are whole groups of 8 take
+    gather kernels without bounds tests (option moe_gather_full, default on); the same
+    shapes through the checked kernels give the same bytes.  Pack + exchange + way back,
+    and the fused dispatch / combine."""
+    torch = require_gpu()
+    P, T, K, E, row = shape
+    saved = vccl.vccl_get_option("moe_gather_full")
+    vccl.vccl_set_option("moe_gather_full", full)
+    try:
+        _combine(torch, vccl, P, T, K, E, row, 1500 + T, vccl.MODE_CU)
+        _fused_roundtrip(torch, vccl, P, T, K, E, row, 1600 + T)
+        ids = [wl.zipf_topk_expert_ids(1700 + T, s, T, K, E).copy() for s in range(P)]
+        ids[0][T // 3, K - 1] = E + 1          # a dropped pair on the unchecked path
+        x_np = [wl.payload_bytes(1700 + T, s, T * row) for s in range(P)]
+        xd = [to_dev(torch, a) for a in x_np]
+        idd = [torch.from_numpy(a.reshape(-1).copy()).cuda() for a in ids]
+        packed = [torch.full((T * K * row,), SENTINEL, dtype=torch.uint8, device="cuda") for _ in range(P)]
+        counts = torch.zeros((P, E), dtype=torch.int64, device="cuda")
+        bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+        vccl.vccl_moe_pack(xd, idd, P, T, K, row, E, packed, counts, None, bad, stream_handle(torch))
+        torch.cuda.synchronize()
+        assert int(bad.item()) == 1
+        keys = ids[0].reshape(-1)
+        keep = (keys >= 0) & (keys < E)
+        order = np.argsort(np.where(keep, keys, E), kind="stable")[:keep.sum()]
+        want = x_np[0].reshape(T, row)[order // K].reshape(-1)
+        got = to_host(packed[0])
+        assert_same(got[:want.size], want, "packed[0] with a dropped pair")
+        assert (got[want.size:] == SENTINEL).all()
+    finally:
+        vccl.vccl_set_option("moe_gather_full", saved)
+
+
 def _dispatch_per_rank(torch, v, P, T, K, E, row, seed, mode, ids_np=None):
     """Pack with one row per (token, destination rank), then the exchange the counts
     describe; packed rows, counts, slot maps and received bytes against the oracle."""
