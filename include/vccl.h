@@ -158,6 +158,45 @@ int vccl_sendrecv_staged_status(void);
 int vccl_p2p_reginfo(int receiver_rank, uint64_t *receiver_ready, uint64_t *copy_started,
                      uint64_t *copy_done, void **receiver_reg_addr);
 
+/* SendRecv between two PROCESSES on the device (the paper's intra-node design, Section
+ * 3.2): the receiver registers an application buffer once - vccl_p2p_export creates the
+ * receiver-owned handshake record (receiverRegAddr, receiverReady, copyStarted, copyDone,
+ * kept as sequence numbers) in POSIX shared memory under `name` ("/" + up to 199
+ * characters) and puts the buffer's IPC handle into it; the sender maps record and buffer
+ * once with vccl_p2p_connect (waits up to timeout_s for the export to appear).  recvbuf_dev
+ * is device memory of this process (any address inside one allocation; the allocation
+ * must be smaller than 2 GiB) and stays the receiver's: it must outlive the connection.
+ * Transfer n of a connection is the n-th vccl_p2p_recv on one side and the n-th
+ * vccl_p2p_send on the other:
+ *   vccl_p2p_recv(conn, offset, bytes, stream)  once `stream` has reached the call (earlier
+ *     work that reads the buffer is done) and transfer n-1 has started, the receiver's proxy
+ *     publishes "n goes to buffer + offset, bytes long" and raises receiverReady; work
+ *     enqueued on `stream` afterwards runs when the record shows copyDone >= n.
+ *   vccl_p2p_send(conn, sendbuf_dev, bytes, stream)  once `stream` has reached the call and
+ *     the record shows receiverReady = n, the sender's proxy marks copyStarted, moves the
+ *     bytes with the copy engines straight from sendbuf_dev into the receiver's buffer, and
+ *     marks copyDone; `stream` resumes then.
+ * Neither call blocks the host (ordering as for VCCL_MODE_CE, "ce_sync"), no kernel runs
+ * in either process.  If the two sides disagree on the byte count, nothing is copied, the
+ * record counts a mismatch and the sender's next copy-engine call fails.  A send without
+ * a matching recv waits, as it would between two machines - until either side calls
+ * vccl_p2p_abort (a peer that died, a deadline that passed): every outstanding transfer of
+ * the connection in either process then ends without copying, its stream is released, the
+ * failure is reported by the next copy-engine call, and later sends / receives on the
+ * connection return VCCL_ERR_TIMEOUT.  vccl_p2p_record reads the
+ * record from either side (any pointer may be NULL).  vccl_p2p_close waits for this
+ * process's outstanding copy-engine operations, unmaps, and (receiver) removes the name.
+ * Needs the "sdma" copy-engine back end. */
+typedef struct vccl_p2p_conn vccl_p2p_conn;
+int vccl_p2p_export(const char *name, void *recvbuf_dev, uint64_t capacity, vccl_p2p_conn **out);
+int vccl_p2p_connect(const char *name, double timeout_s, vccl_p2p_conn **out);
+int vccl_p2p_recv(vccl_p2p_conn *conn, uint64_t offset, uint64_t bytes, void *stream);
+int vccl_p2p_send(vccl_p2p_conn *conn, const void *sendbuf_dev, uint64_t bytes, void *stream);
+int vccl_p2p_record(vccl_p2p_conn *conn, uint64_t *receiver_ready, uint64_t *copy_started,
+                    uint64_t *copy_done, uint64_t *reg_offset, uint64_t *mismatches);
+int vccl_p2p_abort(vccl_p2p_conn *conn);
+int vccl_p2p_close(vccl_p2p_conn *conn);
+
 /* AlltoAll with equal blocks (MoE token routing, Section 2.1): block r
  * (bytes_per_peer bytes at offset r*bytes_per_peer) of sendbuf[s] becomes block s
  * of recvbuf[r].  Every buffer holds at least P*bytes_per_peer bytes.

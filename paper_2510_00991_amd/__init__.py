@@ -21,6 +21,7 @@ from .binding import (  # noqa: E402,F401
     lib_path, load, pointer_array,
     vccl_init, vccl_finalize, vccl_last_error, vccl_set_option, vccl_get_option,
     vccl_sendrecv, vccl_sendrecv_staged_status, vccl_p2p_reginfo,
+    vccl_p2p_export, vccl_p2p_connect, vccl_p2p_recv, vccl_p2p_send, vccl_p2p_record, vccl_p2p_abort, vccl_p2p_close,
     vccl_alltoall, vccl_alltoallv, vccl_plan_alltoallv,
     vccl_moe_pack, vccl_moe_pack_noalloc, vccl_moe_pack_per_rank, vccl_moe_dispatch_fused, vccl_moe_combine_fused, vccl_moe_unpack, vccl_moe_exchange_layout,
     vccl_fma_probe, vccl_hbm_probe, vccl_proxy_stats, vccl_proxy_cpu_time, vccl_device_cu_count,

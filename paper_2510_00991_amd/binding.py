@@ -35,6 +35,13 @@ EXPORTS = {
                                      ctypes.c_int, ctypes.c_void_p]),
     "vccl_sendrecv_staged_status": (ctypes.c_int, []),
     "vccl_p2p_reginfo": (ctypes.c_int, [ctypes.c_int, _u64p, _u64p, _u64p, _vpp]),
+    "vccl_p2p_export": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_void_p, ctypes.c_uint64, _vpp]),
+    "vccl_p2p_connect": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_double, _vpp]),
+    "vccl_p2p_recv": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_void_p]),
+    "vccl_p2p_send": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]),
+    "vccl_p2p_record": (ctypes.c_int, [ctypes.c_void_p, _u64p, _u64p, _u64p, _u64p, _u64p]),
+    "vccl_p2p_abort": (ctypes.c_int, [ctypes.c_void_p]),
+    "vccl_p2p_close": (ctypes.c_int, [ctypes.c_void_p]),
     "vccl_alltoall": (ctypes.c_int, [_vpp, _vpp, ctypes.c_uint64, ctypes.c_int, ctypes.c_int,
                                      ctypes.c_void_p]),
     "vccl_alltoallv": (ctypes.c_int, [_vpp, _u64p, _u64p, _vpp, _u64p, _u64p, ctypes.c_int,
@@ -203,6 +210,42 @@ def vccl_p2p_reginfo(receiver_rank: int):
     _check(load().vccl_p2p_reginfo(receiver_rank, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
                                    ctypes.byref(p)))
     return a.value, b.value, c.value, p.value or 0
+
+
+def vccl_p2p_export(name: str, recvbuf, capacity: int) -> int:
+    """Receiver side of a connection between two processes; returns the connection handle."""
+    h = ctypes.c_void_p()
+    _check(load().vccl_p2p_export(name.encode(), ctypes.c_void_p(_addr(recvbuf)), int(capacity), ctypes.byref(h)))
+    return h.value
+
+
+def vccl_p2p_connect(name: str, timeout_s: float = 30.0) -> int:
+    h = ctypes.c_void_p()
+    _check(load().vccl_p2p_connect(name.encode(), float(timeout_s), ctypes.byref(h)))
+    return h.value
+
+
+def vccl_p2p_recv(conn: int, offset: int, nbytes: int, stream=None) -> None:
+    _check(load().vccl_p2p_recv(ctypes.c_void_p(conn), int(offset), int(nbytes), _stream(stream)))
+
+
+def vccl_p2p_send(conn: int, sendbuf, nbytes: int, stream=None) -> None:
+    _check(load().vccl_p2p_send(ctypes.c_void_p(conn), ctypes.c_void_p(_addr(sendbuf)), int(nbytes), _stream(stream)))
+
+
+def vccl_p2p_record(conn: int):
+    """(receiverReady, copyStarted, copyDone, receiverRegOffset, mismatches) of a cross-process connection."""
+    v = [ctypes.c_uint64() for _ in range(5)]
+    _check(load().vccl_p2p_record(ctypes.c_void_p(conn), *[ctypes.byref(x) for x in v]))
+    return tuple(x.value for x in v)
+
+
+def vccl_p2p_abort(conn: int) -> None:
+    _check(load().vccl_p2p_abort(ctypes.c_void_p(conn)))
+
+
+def vccl_p2p_close(conn: int) -> None:
+    _check(load().vccl_p2p_close(ctypes.c_void_p(conn)))
 
 
 def vccl_alltoall(sendbuf, recvbuf, bytes_per_peer: int, P: int, mode: int, stream=None) -> None:

@@ -2,6 +2,13 @@
 // displacement tables into segment descriptors, and dispatch to the compute-unit
 // or copy-engine path.  Primitive semantics: SendRecv and AlltoAll(v) as the
 // reduction-free P2P primitives of the paper (Section 1, Challenge 1; Section 2.1).
+#include <fcntl.h>
+#include <signal.h>
+#include <sys/mman.h>
+#include <sys/stat.h>
+#include <time.h>
+#include <unistd.h>
+
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
@@ -853,6 +860,211 @@ int vccl_proxy_monitor(int primitive, uint64_t *messages, uint64_t *anomalies, v
     vccl_monitor *m = proxy_monitor(c->proxy, primitive);
     if (!m) return fail(VCCL_ERR_ARG, "primitive must be 0 (SendRecv) or 1 (AlltoAll(v))");
     return vccl_monitor_totals(m, messages, anomalies, last);
+}
+
+}  // extern "C"
+
+// ---- SendRecv between two processes (Section 3.2: the receiver's application buffer is
+// exported once with an IPC handle and mapped into the sender at connect; the handshake
+// record lives in host shared memory; the sender's proxy moves the data with the copy
+// engines straight into the receiver's buffer)
+struct vccl_p2p_conn {
+    int role = 0;                     // 1 sender, 2 receiver
+    std::string name;
+    P2pShared *sh = nullptr;
+    uint8_t *buffer = nullptr;        // receiver: its own buffer; sender: the same memory as mapped here
+    void *mapped_alloc = nullptr;     // sender: what hipIpcOpenMemHandle returned
+    uint64_t next_seq = 0;            // transfers posted so far on this side
+    std::mutex mu;
+};
+
+static int p2p_name_ok(const char *name) {
+    if (!name || name[0] != '/' || strlen(name) < 2 || strlen(name) > 200 || strchr(name + 1, '/'))
+        return fail(VCCL_ERR_ARG, "a connection name is '/' followed by 1..199 characters without '/'");
+    return VCCL_OK;
+}
+
+extern "C" {
+
+int vccl_p2p_export(const char *name, void *recvbuf_dev, uint64_t capacity, vccl_p2p_conn **out) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    int rv = p2p_name_ok(name);
+    if (rv) return rv;
+    if (!recvbuf_dev || !capacity || !out) return fail(VCCL_ERR_ARG, "NULL buffer, zero capacity or NULL out");
+    // The handle names the whole allocation the buffer lies in; the record carries the offset.
+    void *base = nullptr;
+    size_t alloc_size = 0;
+    VCCL_HIP(hipMemGetAddressRange((hipDeviceptr_t *)&base, &alloc_size, (hipDeviceptr_t)recvbuf_dev));
+    const uint64_t off = (uint64_t)((uint8_t *)recvbuf_dev - (uint8_t *)base);
+    if (off + capacity > alloc_size)
+        return fail(VCCL_ERR_ARG, "the buffer (+%llu, %llu bytes) does not lie inside one allocation of %zu bytes",
+                    (unsigned long long)off, (unsigned long long)capacity, alloc_size);
+    if (alloc_size >= (2ull << 30))
+        return fail(VCCL_ERR_UNSUPPORTED, "the allocation holding the buffer has %zu bytes; allocations shared "
+                                          "between processes must stay below 2 GiB", alloc_size);
+    hipIpcMemHandle_t h;
+    static_assert(sizeof(h) <= sizeof(P2pShared::ipc_handle), "handle size");
+    VCCL_HIP(hipIpcGetMemHandle(&h, base));
+    const int fd = shm_open(name, O_CREAT | O_EXCL | O_RDWR, 0600);
+    if (fd < 0) return fail(VCCL_ERR_ARG, "shm_open(%s) failed: %s", name, strerror(errno));
+    if (ftruncate(fd, (off_t)sizeof(P2pShared)) != 0) {
+        const int e = errno;
+        close(fd);
+        shm_unlink(name);
+        return fail(VCCL_ERR_ARG, "ftruncate(%s) failed: %s", name, strerror(e));
+    }
+    void *m = mmap(nullptr, sizeof(P2pShared), PROT_READ | PROT_WRITE, MAP_SHARED, fd, 0);
+    close(fd);
+    if (m == MAP_FAILED) {
+        shm_unlink(name);
+        return fail(VCCL_ERR_ARG, "mmap(%s) failed", name);
+    }
+    P2pShared *sh = new (m) P2pShared();      // a fresh object in zero-filled pages
+    sh->capacity = capacity;
+    sh->alloc_offset = off;
+    sh->receiver_pid = (int32_t)getpid();
+    memcpy(sh->ipc_handle, &h, sizeof(h));
+    std::atomic_thread_fence(std::memory_order_release);
+    reinterpret_cast<std::atomic<uint64_t> *>(&sh->magic)->store(kP2pMagic, std::memory_order_release);
+    vccl_p2p_conn *conn = new vccl_p2p_conn;
+    conn->role = 2;
+    conn->name = name;
+    conn->sh = sh;
+    conn->buffer = (uint8_t *)recvbuf_dev;
+    *out = conn;
+    return VCCL_OK;
+}
+
+int vccl_p2p_connect(const char *name, double timeout_s, vccl_p2p_conn **out) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    int rv = p2p_name_ok(name);
+    if (rv) return rv;
+    if (!out) return fail(VCCL_ERR_ARG, "NULL out");
+    struct timespec t0;
+    clock_gettime(CLOCK_MONOTONIC, &t0);
+    auto waited = [&] {
+        struct timespec t;
+        clock_gettime(CLOCK_MONOTONIC, &t);
+        return (double)(t.tv_sec - t0.tv_sec) + 1e-9 * (double)(t.tv_nsec - t0.tv_nsec);
+    };
+    P2pShared *sh = nullptr;
+    for (;;) {   // the receiver may not have exported yet
+        const int fd = shm_open(name, O_RDWR, 0600);
+        if (fd >= 0) {
+            struct stat st;
+            if (fstat(fd, &st) == 0 && (size_t)st.st_size >= sizeof(P2pShared)) {
+                void *m = mmap(nullptr, sizeof(P2pShared), PROT_READ | PROT_WRITE, MAP_SHARED, fd, 0);
+                if (m != MAP_FAILED) {
+                    sh = static_cast<P2pShared *>(m);
+                    if (reinterpret_cast<std::atomic<uint64_t> *>(&sh->magic)->load(std::memory_order_acquire) ==
+                        kP2pMagic) {
+                        close(fd);
+                        break;
+                    }
+                    munmap(m, sizeof(P2pShared));
+                    sh = nullptr;
+                }
+            }
+            close(fd);
+        }
+        if (waited() > timeout_s) return fail(VCCL_ERR_TIMEOUT, "no exported connection '%s' after %.1f s", name, timeout_s);
+        usleep(2000);
+    }
+    if (sh->sender_attached.exchange(1) != 0) {
+        munmap(sh, sizeof(P2pShared));
+        return fail(VCCL_ERR_ARG, "connection '%s' already has a sender", name);
+    }
+    // a handle whose exporting process is gone must not be opened
+    if (sh->receiver_closed.load() || sh->aborted.load() || (kill((pid_t)sh->receiver_pid, 0) != 0 && errno == ESRCH)) {
+        sh->sender_attached.store(0);
+        munmap(sh, sizeof(P2pShared));
+        return fail(VCCL_ERR_ARG, "the receiver of connection '%s' is gone", name);
+    }
+    hipIpcMemHandle_t h;
+    memcpy(&h, sh->ipc_handle, sizeof(h));
+    void *mapped = nullptr;
+    hipError_t e = hipIpcOpenMemHandle(&mapped, h, hipIpcMemLazyEnablePeerAccess);
+    if (e != hipSuccess) {
+        sh->sender_attached.store(0);
+        munmap(sh, sizeof(P2pShared));
+        return fail(VCCL_ERR_HIP, "hipIpcOpenMemHandle failed: %s", hipGetErrorString(e));
+    }
+    vccl_p2p_conn *conn = new vccl_p2p_conn;
+    conn->role = 1;
+    conn->name = name;
+    conn->sh = sh;
+    conn->mapped_alloc = mapped;
+    conn->buffer = (uint8_t *)mapped + sh->alloc_offset;
+    *out = conn;
+    return VCCL_OK;
+}
+
+int vccl_p2p_recv(vccl_p2p_conn *conn, uint64_t offset, uint64_t bytes, void *stream) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    if (!conn || conn->role != 2) return fail(VCCL_ERR_ARG, "not the receiving end of a connection");
+    if (conn->sh->aborted.load()) return fail(VCCL_ERR_TIMEOUT, "connection '%s' was aborted", conn->name.c_str());
+    if (offset > conn->sh->capacity || bytes > conn->sh->capacity - offset)
+        return fail(VCCL_ERR_ARG, "offset %llu + %llu bytes exceed the registered %llu", (unsigned long long)offset,
+                    (unsigned long long)bytes, (unsigned long long)conn->sh->capacity);
+    std::lock_guard<std::mutex> lk(conn->mu);   // posts of one connection reach the proxy in sequence order
+    const uint64_t seq = conn->next_seq + 1;
+    int rv = proxy_submit_remote(c->proxy, 2, conn->sh, nullptr, seq, nullptr, offset, bytes, options_of(*c),
+                                 (hipStream_t)stream);
+    if (rv == VCCL_OK) conn->next_seq = seq;
+    return rv;
+}
+
+int vccl_p2p_send(vccl_p2p_conn *conn, const void *sendbuf_dev, uint64_t bytes, void *stream) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    if (!conn || conn->role != 1) return fail(VCCL_ERR_ARG, "not the sending end of a connection");
+    if (bytes && !sendbuf_dev) return fail(VCCL_ERR_ARG, "NULL send buffer");
+    if (conn->sh->aborted.load()) return fail(VCCL_ERR_TIMEOUT, "connection '%s' was aborted", conn->name.c_str());
+    std::lock_guard<std::mutex> lk(conn->mu);
+    const uint64_t seq = conn->next_seq + 1;
+    int rv = proxy_submit_remote(c->proxy, 1, conn->sh, conn->buffer, seq, sendbuf_dev, 0, bytes, options_of(*c),
+                                 (hipStream_t)stream);
+    if (rv == VCCL_OK) conn->next_seq = seq;
+    return rv;
+}
+
+int vccl_p2p_record(vccl_p2p_conn *conn, uint64_t *receiver_ready, uint64_t *copy_started, uint64_t *copy_done,
+                    uint64_t *reg_offset, uint64_t *mismatches) {
+    if (!conn || !conn->sh) return fail(VCCL_ERR_ARG, "NULL connection");
+    const P2pShared *sh = conn->sh;
+    if (receiver_ready) *receiver_ready = sh->receiverReady.load(std::memory_order_acquire);
+    if (copy_started) *copy_started = sh->copyStarted.load(std::memory_order_acquire);
+    if (copy_done) *copy_done = sh->copyDone.load(std::memory_order_acquire);
+    if (reg_offset) *reg_offset = sh->receiverRegOffset.load(std::memory_order_acquire);
+    if (mismatches) *mismatches = sh->mismatches.load(std::memory_order_acquire);
+    return VCCL_OK;
+}
+
+int vccl_p2p_abort(vccl_p2p_conn *conn) {
+    if (!conn || !conn->sh) return fail(VCCL_ERR_ARG, "NULL connection");
+    conn->sh->aborted.store(1, std::memory_order_release);
+    return VCCL_OK;
+}
+
+int vccl_p2p_close(vccl_p2p_conn *conn) {
+    if (!conn) return fail(VCCL_ERR_ARG, "NULL connection");
+    auto c = ctx_get();
+    if (c) (void)proxy_drain(c->proxy);      // no operation of this process still points at the record
+    int rv = VCCL_OK;
+    if (conn->role == 1) {
+        if (conn->mapped_alloc && hipIpcCloseMemHandle(conn->mapped_alloc) != hipSuccess)
+            rv = fail(VCCL_ERR_HIP, "hipIpcCloseMemHandle failed");
+        conn->sh->sender_attached.store(0);
+    } else {
+        conn->sh->receiver_closed.store(1);
+        shm_unlink(conn->name.c_str());
+    }
+    munmap(conn->sh, sizeof(P2pShared));
+    delete conn;
+    return rv;
 }
 
 int vccl_p2p_reginfo(int receiver_rank, uint64_t *receiver_ready, uint64_t *copy_started,

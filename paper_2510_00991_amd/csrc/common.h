@@ -219,8 +219,38 @@ struct CeCopy {
     uint64_t bytes;
     int receiver;  // >= 0: SendRecv copy whose destination is read from that rank's handshake record
 };
+// The receiver-owned handshake record of a connection between two PROCESSES (Section
+// 3.2: P2pRegInfo in host shared memory, mapped into the sender at connect).  The
+// paper's 1-bit flags are sequence numbers that only grow: transfer n of the connection
+// is ready / started / done once the field has reached n.
+struct P2pShared {
+    uint64_t magic;                      // written last by the exporting process
+    uint64_t capacity;                   // bytes of the registered receive buffer
+    uint64_t alloc_offset;               // where that buffer starts inside the exported allocation
+    uint8_t ipc_handle[64];              // hipIpcMemHandle_t of the allocation
+    std::atomic<uint64_t> receiverRegOffset;   // receiverRegAddr: offset of transfer n inside the registered buffer,
+    std::atomic<uint64_t> receiverRegBytes;    // and how many bytes the receiver expects (published before ready)
+    std::atomic<uint64_t> receiverReady;
+    std::atomic<uint64_t> copyStarted;
+    std::atomic<uint64_t> copyDone;
+    std::atomic<uint64_t> mismatches;    // transfers whose byte counts disagreed (nothing was copied for them)
+    std::atomic<uint32_t> sender_attached;
+    std::atomic<uint32_t> receiver_closed;
+    std::atomic<uint32_t> aborted;       // either side gave up: every outstanding and later transfer fails
+    int32_t receiver_pid;
+};
+static_assert(std::atomic<uint64_t>::is_always_lock_free, "the record is shared between processes");
+constexpr uint64_t kP2pMagic = 0x5643434c50325031ull;   // "VCCLP2P1"
+
 class Proxy;
 Proxy *proxy_create(int device, int max_streams);
+// One side of a transfer over a cross-process connection, ordered on `stream` like any
+// other copy-engine operation.  role 1 (sender): copy `bytes` from src into the mapped
+// receive buffer once the record shows transfer `seq` ready.  role 2 (receiver): when the
+// stream has reached the operation and transfer seq - 1 has started, publish (offset,
+// bytes) and raise ready; the stream resumes when the record shows transfer seq done.
+int proxy_submit_remote(Proxy *p, int role, P2pShared *sh, uint8_t *mapped_buffer, uint64_t seq, const void *src,
+                        uint64_t offset, uint64_t bytes, const Options &opt, hipStream_t stream);
 void proxy_destroy(Proxy *p);
 // Orders the copies after everything already on `stream`, has the proxy thread
 // issue them on the internal copy streams, and makes `stream` wait for them.

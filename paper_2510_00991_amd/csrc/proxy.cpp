@@ -96,6 +96,11 @@ struct Op {
     bool sdma_failed = false;
     uint64_t bytes = 0;                        // bytes handed to the engines
     uint64_t t_issue_ns = 0;                   // when they were handed over
+    // one side of a transfer over a cross-process connection (0 = none, 1 = sender, 2 = receiver)
+    int remote_role = 0;
+    P2pShared *remote = nullptr;
+    uint8_t *remote_buffer = nullptr;          // sender: the receiver's registered buffer as mapped here
+    uint64_t remote_seq = 0, remote_offset = 0, remote_bytes = 0;
 };
 }  // namespace
 
@@ -147,6 +152,8 @@ public:
     bool receivers_ready(const Op *op) const;
     void issue_events(Op *op);
     bool issue_sdma(Op *op);
+    bool issue_remote_recv(Op *op);
+    bool stream_reached(const Op *op) const;
     bool poll();
     void finish(Op *op);
     Op *get_op();
@@ -297,6 +304,8 @@ void Proxy::put_ref(Op *op) {  // mu held
         op->conns.clear();
         op->state = 0;
         op->sdma_failed = false;
+        op->remote_role = 0;
+        op->remote = nullptr;
         free_ops.push_back(op);
     }
 }
@@ -383,11 +392,60 @@ void Proxy::issue_events(Op *op) {
 
 // -------------------------------------------------------- sdma back end ------
 // Returns false while the caller's stream has not yet reached the operation.
+bool Proxy::stream_reached(const Op *op) const {
+    if (op->ready_event) return hipEventQuery(op->ready) != hipErrorNotReady;
+    return __atomic_load_n(op->ready_word, __ATOMIC_ACQUIRE) >= op->seq;
+}
+
+// Receiving side of a cross-process transfer: once the caller's stream has reached the
+// operation (the buffer may be overwritten) and the previous transfer of the connection
+// has started, publish where this one goes and raise ready.  The operation then stays
+// pending until the sender's process marks it done.
+bool Proxy::issue_remote_recv(Op *op) {
+    if (!stream_reached(op)) return false;
+    P2pShared *sh = op->remote;
+    if (sh->copyStarted.load(std::memory_order_acquire) != op->remote_seq - 1) return false;
+    sh->receiverRegOffset.store(op->remote_offset, std::memory_order_relaxed);
+    sh->receiverRegBytes.store(op->remote_bytes, std::memory_order_relaxed);
+    sh->receiverReady.store(op->remote_seq, std::memory_order_release);
+    op->bytes = 0;
+    op->t_issue_ns = now_ns();
+    op->monitor_id = 0;
+    pending.push_back(op);
+    return true;
+}
+
 bool Proxy::issue_sdma(Op *op) {
-    if (op->ready_event) {
-        if (hipEventQuery(op->ready) == hipErrorNotReady) return false;
-    } else if (__atomic_load_n(op->ready_word, __ATOMIC_ACQUIRE) < op->seq) {
-        return false;
+    if (op->remote_role && op->remote->aborted.load(std::memory_order_acquire)) {
+        // the connection was given up: nothing is copied, the stream is released, the failure is counted
+        op->copies.clear();
+        op->sdma_failed = true;
+        op->remote_role = 3;                       // neither side's protocol step is taken any more
+        hsa_signal_store_relaxed(op->left, 0);
+        op->bytes = 0;
+        op->t_issue_ns = now_ns();
+        op->monitor_id = 0;
+        pending.push_back(op);
+        return true;
+    }
+    if (op->remote_role == 2) return issue_remote_recv(op);
+    if (!stream_reached(op)) return false;
+    if (op->remote_role == 1) {
+        // sender over a cross-process connection: wait for the receiver's ready, read the
+        // destination from the record, mark started
+        P2pShared *sh = op->remote;
+        if (sh->receiverReady.load(std::memory_order_acquire) != op->remote_seq) return false;
+        const uint64_t off = sh->receiverRegOffset.load(std::memory_order_relaxed);
+        const uint64_t want = sh->receiverRegBytes.load(std::memory_order_relaxed);
+        if (want != op->remote_bytes || off > sh->capacity || want > sh->capacity - off) {
+            // the two sides disagree (a distributed library would hang or corrupt): copy nothing, say so
+            sh->mismatches.fetch_add(1, std::memory_order_relaxed);
+            op->copies.clear();
+            op->sdma_failed = true;
+        } else {
+            for (CeCopy &c : op->copies) c.dst = op->remote_buffer + off;
+        }
+        sh->copyStarted.store(op->remote_seq, std::memory_order_release);
     }
     // A connection carries its transfers in the order their numbers were drawn: this
     // one goes when the receiver proxy has published its buffer.
@@ -499,7 +557,8 @@ void Proxy::run_receiver() {
 
 void Proxy::finish(Op *op) {
     const uint64_t t_done = now_ns();
-    (void)vccl_monitor_complete(monitor[op->primitive], op->monitor_id, t_done, nullptr);
+    if (op->monitor_id) (void)vccl_monitor_complete(monitor[op->primitive], op->monitor_id, t_done, nullptr);
+    if (op->remote_role == 1) op->remote->copyDone.store(op->remote_seq, std::memory_order_release);
     if (op->kind == VCCL_CE_SDMA && op->bytes >= (8u << 20) && t_done > op->t_issue_ns) {
         // what the engines gave this operation, smoothed: the sleep before polling leans on it
         const double r = (double)op->bytes / (double)(t_done - op->t_issue_ns);
@@ -537,7 +596,13 @@ bool Proxy::poll() {
     for (size_t k = 0; k < pending.size();) {
         Op *op = pending[k];
         bool complete = true;
-        if (op->kind == VCCL_CE_SDMA) {
+        if (op->remote_role == 2) {
+            complete = op->remote->copyDone.load(std::memory_order_acquire) >= op->remote_seq;
+            if (!complete && op->remote->aborted.load(std::memory_order_acquire)) {
+                op->sdma_failed = true;
+                complete = true;
+            }
+        } else if (op->kind == VCCL_CE_SDMA) {
             complete = hsa_signal_load_scacquire(op->left) <= 0;
         } else {
             for (int i = 0; i < op->nstreams; ++i) {
@@ -570,6 +635,11 @@ uint64_t Proxy::nap_ns(uint64_t now, uint64_t last_progress) const {
     if (now - last_progress < kSpin) return 0;
     uint64_t nap = !waiting.empty() ? (now - last_progress < 1000000 ? 10000 : 50000) : 200000;
     for (const Op *op : pending) {
+        if (op->remote_role == 2) {   // the other process sets the pace: look every 10 us, then every 50
+            const uint64_t slice = now - op->t_issue_ns < 2000000 ? 10000 : 50000;
+            nap = nap < slice ? nap : slice;
+            continue;
+        }
         if (op->kind != VCCL_CE_SDMA) return 0;   // event back end: short copies on HIP streams, polled
         const uint64_t dur = (uint64_t)((double)op->bytes / rate_bpns);
         const uint64_t margin = 10000 + dur / 16;
@@ -851,6 +921,36 @@ static int submit_sdma(Proxy *p, Op *op, hipStream_t stream,
     }
     // From here on the proxy owns `op`.
     return VCCL_OK;
+}
+
+int proxy_submit_remote(Proxy *p, int role, P2pShared *sh, uint8_t *mapped_buffer, uint64_t seq, const void *src,
+                        uint64_t offset, uint64_t bytes, const Options &opt, hipStream_t stream) {
+    if (opt.ce_kind != VCCL_CE_SDMA || !p->sdma_ok)
+        return fail(VCCL_ERR_UNSUPPORTED, "cross-process SendRecv needs the 'sdma' copy-engine back end%s%s",
+                    p->sdma_ok ? "" : ": ", p->sdma_ok ? "" : p->sdma_why.c_str());
+    Op *op;
+    {
+        std::lock_guard<std::mutex> lk(p->mu);
+        op = p->get_op();
+        if (!op) return fail(VCCL_ERR_HIP, "could not create the resources of a copy-engine operation");
+        op->host_sync = opt.ce_sync == VCCL_SYNC_HOST;
+        op->ready_event = op->host_sync || opt.ce_sync == VCCL_SYNC_EVENT;
+        op->refs = op->host_sync ? 2 : 1;
+        op->state = 0;
+    }
+    op->copies.clear();
+    if (role == 1 && bytes) op->copies.push_back(CeCopy{src, nullptr, bytes, -1});
+    op->kind = VCCL_CE_SDMA;
+    op->max_engines = opt.ce_max_engines;
+    op->refuse_mask = (uint32_t)opt.ce_test_refuse;
+    op->primitive = 0;
+    op->remote_role = role;
+    op->remote = sh;
+    op->remote_buffer = mapped_buffer;
+    op->remote_seq = seq;
+    op->remote_offset = offset;
+    op->remote_bytes = bytes;
+    return submit_sdma(p, op, stream, nullptr);
 }
 
 void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t *issue_ns) {
