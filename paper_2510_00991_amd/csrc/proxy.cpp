@@ -289,7 +289,8 @@ Op *Proxy::get_op() {  // mu held
             ok = hipExtMallocWithFlags((void **)&op->done_word, 8, hipMallocSignalMemory) == hipSuccess;
             if (ok) __atomic_store_n(op->done_word, (uint64_t)0, __ATOMIC_RELEASE);
         }
-        ok = ok && hsa_signal_create(0, 0, nullptr, &op->left) == HSA_STATUS_SUCCESS;
+        // never waited on, only loaded: a signal without a host interrupt per completed copy
+        ok = ok && hsa_amd_signal_create(0, 0, nullptr, HSA_AMD_SIGNAL_AMD_GPU_ONLY, &op->left) == HSA_STATUS_SUCCESS;
     }
     if (!ok) {   // events and words of a half-built op are few and leak only on this error path
         delete op;

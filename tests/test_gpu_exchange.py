@@ -427,6 +427,29 @@ def test_engines_that_refuse_a_copy_are_passed_over(vccl, sync):
     assert int(vccl.vccl_get_option("ce_test_refuse")) == 0
 
 
+def test_small_message_alltoall_on_the_copy_engines(vccl):
+    """An AlltoAll of many small blocks on the copy engines (2304 copies of 4 KiB + 16 B,
+    one per block): right bytes, also when some engines refuse and their pieces are offered
+    to the others."""
+    torch = require_gpu()
+    P, c = 48, 4096 + 16
+    send_np = [wl.payload_bytes(6100, s, P * c) for s in range(P)]
+    want = [np.full(P * c + 32, SENTINEL, dtype=np.uint8) for _ in range(P)]
+    oracle.alltoall(send_np, want, c, threads=4)
+    send = [to_dev(torch, a) for a in send_np]
+    st = stream_handle(torch)
+    copies0 = vccl.vccl_proxy_stats()["copies"]
+    for refuse in (0, 0x0A0A):
+        recv = [to_dev(torch, np.full(P * c + 32, SENTINEL, np.uint8)) for _ in range(P)]
+        _with_options(vccl, {"ce_test_refuse": refuse},
+                      lambda: vccl.vccl_alltoall(send, recv, c, P, vccl.MODE_CE, st))
+        torch.cuda.synchronize()
+        for r in range(P):
+            assert_same(to_host(recv[r]), want[r], f"refuse={refuse:#x} recv[{r}]")
+    assert vccl.vccl_proxy_stats()["copies"] - copies0 == 2 * P * P
+    assert int(vccl.vccl_get_option("ce_errors")) == 0
+
+
 def test_many_copy_engine_operations_in_flight(vccl):
     """Several copy-engine calls queued back to back on two streams before any
     synchronisation: operation slots are recycled and every result is right."""
