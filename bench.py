@@ -154,7 +154,11 @@ def main():
     ap.add_argument("--ce-sync", default="default", choices=["default", "memops", "event", "host"],
                     help="ordering of the copy-engine path: the library's default for this process, stream "
                          "write/wait-value operations, event + wait-value, or none (the call blocks)")
-    ap.add_argument("--pairs", type=int, default=20, help="alone/beside pairs per co-run figure")
+    ap.add_argument("--pairs", type=int, default=20, help="alone/beside pairs per co-run figure of a compute-unit path")
+    ap.add_argument("--ce-pairs", type=int, default=60,
+                    help="pairs per co-run figure of the copy-engine path: its effect is looked for at the tenth of a "
+                         "per cent, below the probe's own run-to-run scatter (a few per cent of all probes run 4-5 %% "
+                         "long, alone or not), so it gets more pairs")
     args = ap.parse_args()
     legs = set(x.strip() for x in args.legs.split(",") if x.strip())
     unknown = legs - {"cu", "ce", "corun", "sendrecv", "sweep", "moe", "cpu", "calib"}
@@ -263,11 +267,12 @@ def main():
             v.vccl_set_option("cu_threads", 64)
             wce, _ = time_region(torch, a2a_ce, 3, 1)
             cor_ce = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CE, sh), algo_bytes, wce / 3,
-                               reps=args.pairs)
+                               reps=args.ce_pairs)
             out["corun"] = {"probe": f"FMA kernel, {co.cu} workgroups x {co.threads} threads, "
                                      f"{co.iters} rounds of 64 FMAs per lane",
-                            "protocol": f"{args.pairs} alone/beside pairs in alternating order, median and "
-                                        "quartiles of the paired ratios",
+                            "protocol": f"{args.pairs} alone/beside pairs per compute-unit figure, {args.ce_pairs} per "
+                                        "copy-engine figure, in alternating order; median, mean and quartiles of the "
+                                        "paired ratios",
                             "cu_path": cor_cu, "cu_path_capped_1wg_per_cu": cor_cap,
                             "cu_path_capped_64wg": cor_cap64, "copy_engine_path": cor_ce}
         if "sendrecv" in legs:
@@ -287,7 +292,8 @@ def main():
                             "device_us_per_call": dev / 5 * 1e6,
                             "GBps_device": 2.0 * P * n / (dev / 5) / 1e9}
                 if co is not None and "corun" in legs:
-                    sr[name]["corun"] = co.beside(fn, 2.0 * P * n, w / 5, reps=max(8, args.pairs // 2))
+                    sr[name]["corun"] = co.beside(fn, 2.0 * P * n, w / 5,
+                                                  reps=args.ce_pairs if mode == v.MODE_CE else max(8, args.pairs // 2))
             v.vccl_sendrecv_staged_status()
             for r in (0, 5):
                 assert torch.equal(recv[r][:n], send[frm[r]][:n])
@@ -306,7 +312,8 @@ def main():
                     t = statistics.median(time_region(torch, fn, k, 2)[0] for _ in range(3)) / k
                     row[name] = {"us": t * 1e6, "GBps": moved / t / 1e9}
                     if "corun" in legs:
-                        row[name]["corun"] = co.beside(fn, moved, t, reps=max(8, args.pairs // 2))
+                        row[name]["corun"] = co.beside(fn, moved, t,
+                                                       reps=args.ce_pairs // 2 if name == "ce" else max(8, args.pairs // 2))
                 for r, s in ((3, 60), (63, 1)):     # block r of send[s] is block s of recv[r]
                     assert torch.equal(r5[r][s * c5:(s + 1) * c5], s5[s][r * c5:(r + 1) * c5])
                 rows.append(row)

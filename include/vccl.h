@@ -10,10 +10,31 @@
  * Two data paths exist for every primitive:
  *   VCCL_MODE_CU  a compute-unit copy kernel on the caller's stream (the kind of
  *                 SM-consuming P2P kernel the paper sets out to remove, Section 2.2);
- *   VCCL_MODE_CE  SDMA copy engines driven by a host proxy thread: no kernel is
- *                 launched, no compute unit is used, and stream order is kept by
- *                 stream write/wait-value operations (the paper's SM-free P2P,
- *                 Section 3.2 items 1-3).
+ *   VCCL_MODE_CE  SDMA copy engines driven by a host proxy thread (the paper's SM-free
+ *                 P2P, Section 3.2 items 1-3).  The data never touches a compute unit.
+ *                 What keeps stream order is chosen by option "ce_sync", and what
+ *                 each choice dispatches depends on the HIP runtime (measured with
+ *                 rocprofv3, kernel trace and SQ_WAVES):
+ *                   "event"   readiness by an event the proxy polls, completion by a
+ *                             stream wait-value operation.  With GPU_STREAMOPS_CP_WAIT=1
+ *                             in the environment when the HIP runtime starts, the
+ *                             command processor carries the wait out itself: NO kernel
+ *                             is dispatched and the call does not block.  This is the
+ *                             default whenever the process runs with that setting; the
+ *                             library asks for it at load time (it sets the variable
+ *                             unless it is already set), which is in time if the
+ *                             library is loaded before the process's first HIP call -
+ *                             a program that links it, or a Python process that
+ *                             imports the package before anything touches the GPU.
+ *                             Read-only option "ce_wait_on_cp" tells what vccl_init found.
+ *                   "memops"  readiness by a stream write-value operation as well (the
+ *                             paper's proxyReadyEvent).  The runtime carries the write
+ *                             out with a one-lane helper kernel (a few microseconds),
+ *                             and - without the setting above - the wait with another
+ *                             that holds one wavefront slot for the length of the
+ *                             transfer.  Default when the setting is absent.
+ *                   "host"    no stream operation: the calling thread blocks until the
+ *                             copies are done.  Nothing is dispatched.
  *
  * Conventions
  *   - Every pointer named *_dev / every element of a buffer-pointer array is a
@@ -32,7 +53,9 @@
  *     overlap each other.  With option "check"="1" the library verifies this
  *     and returns VCCL_ERR_OVERLAP.
  *   - Every function returns VCCL_OK (0) or a negative vccl_status.  On error
- *     nothing has been enqueued, and vccl_last_error() describes the cause.
+ *     nothing that moves data has been enqueued (a failing copy-engine call may leave
+ *     an event record or a stream write of a sequence number nobody waits for), and
+ *     vccl_last_error() describes the cause.
  *   - Calls may be made from several host threads; calls on different streams
  *     may overlap on the device.
  */
@@ -47,7 +70,7 @@ extern "C" {
 
 typedef enum {
     VCCL_MODE_CU = 0,        /* compute-unit copy kernel, application buffer to application buffer */
-    VCCL_MODE_CE = 1,        /* copy engines + host proxy thread, no kernel */
+    VCCL_MODE_CE = 1,        /* copy engines + host proxy thread; no kernel in the default ordering */
     VCCL_MODE_CU_STAGED = 2  /* vccl_sendrecv only: two-step copy through the chunk FIFO */
 } vccl_mode;
 
@@ -95,16 +118,21 @@ const char *vccl_last_error(void);
  *       device supports it; "hip_nocu" / "hip_default" = hipMemcpyAsync on internal streams
  *       with event ordering, kind hipMemcpyDeviceToDeviceNoCU / hipMemcpyDeviceToDevice),
  *       "ce_streams" (1..8 internal streams of the hip_* back ends),
- *       "ce_sync" (sdma back end only: "memops" = the stream writes a ready word and
- *       waits on a done word, the call returns at once - the HIP runtime may carry out each
- *       of the two stream operations with a one-lane helper kernel; "host" = no stream
- *       operation at all, the calling thread blocks until the copies are done),
+ *       "ce_sync" (sdma back end only: "event", "memops" or "host", see VCCL_MODE_CE above),
+ *       "ce_wait_on_cp" (read-only: 1 if GPU_STREAMOPS_CP_WAIT was set to a non-zero value
+ *       when vccl_init ran),
  *       "ce_engines" (read-only: SDMA engines found),
  *       "ce_engine_bytes" (read-only: bytes handed to each engine since vccl_init, comma
  *       separated; the pieces of an operation go to the engine with the fewest bytes),
- *       "ce_errors" (read-only: copy-engine operations of which an engine refused a copy
- *       after the call had returned; the next copy-engine call then fails once with
+ *       "ce_errors" (read-only: copy-engine operations that could not move all of their bytes
+ *       after the call had returned - a piece that every engine refused and that the HIP copy
+ *       issued in its place could not move either, or a cross-process transfer that was
+ *       mismatched or aborted; the next copy-engine call then fails once with
  *       VCCL_ERR_HIP, and vccl_finalize returns VCCL_ERR_HIP if any went unreported),
+ *       "ce_refused" (read-only: pieces that no engine took and that went through the HIP
+ *       copy instead, before the operation's stream was released),
+ *       "ce_test_refuse" (test hook, 0..65535: bit i makes the proxy treat engine i as
+ *       refusing every copy),
  *       "ce_max_engines" (0 = all; else use only that many engines),
  *       "check" (0/1 overlap validation),
  *       "moe_gather_variant" (row gather of vccl_moe_pack: 208 / 308 = one workgroup of 8
@@ -113,6 +141,9 @@ const char *vccl_last_error(void);
  *       wavefront per 2 KiB piece looping over the slots, non-temporal / plain stores;
  *       4, 8, 16 = one wavefront per token holding that many vectors per lane,
  *       non-temporal stores; 108, 116 = the same with plain stores),
+ *       "moe_gather_full" (1, default: rows that are whole 2 KiB pieces with slot counts that
+ *       are whole groups of 8 take gather kernels without bounds tests; 0: always the
+ *       checked kernels),
  *       "moe_unpack_variant" (row un-permute of vccl_moe_unpack: 0 = one workgroup per row,
  *       1 / 2 = one wavefront per 1 KiB tile with non-temporal / device-scope stores,
  *       3 = one wavefront per two tiles, device-scope stores),

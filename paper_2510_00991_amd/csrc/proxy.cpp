@@ -6,19 +6,28 @@
 // Two back ends:
 //
 //  "sdma" (default)  The proxy submits every copy straight to an SDMA engine
-//      through the HSA runtime, rotating over the engines, and stream order is
-//      kept with stream memory operations exactly as the paper ends up doing
-//      (Section 3.2 item 3): the caller's stream WRITES a sequence number into a
-//      host-visible ready word when the preceding work is done (the paper's
-//      proxyReadyEvent), the proxy polls that word, issues the copies, polls their
-//      completion signal, and then stores the sequence number into a signal word
-//      the caller's stream WAITS on (the role of proxyOpCount returning to zero).
-//      No kernel, no host callback, and the calling thread never blocks.
+//      through the HSA runtime, each piece to the engine with the fewest bytes so
+//      far.  Stream order is kept the way the paper ends up doing it (Section 3.2
+//      item 3): the caller's stream tells the proxy when the preceding work is done
+//      (the paper's proxyReadyEvent) - by an event the proxy polls (ordering
+//      "event") or by WRITING a sequence number into a host-visible ready word
+//      (ordering "memops") - the proxy issues the copies, polls their completion
+//      signal, and then stores the sequence number into a signal word the caller's
+//      stream WAITS on (the role of proxyOpCount returning to zero).  No kernel of
+//      this library, no host callback, and the calling thread never blocks; whether
+//      the HIP runtime needs a helper kernel for its stream operations is its
+//      business (the wait needs none when the command processor carries it out).
+//      Ordering "host" uses no stream operation at all: the caller blocks.
 //
 //  "hip_nocu" / "hip_default"  hipMemcpyAsync on internal streams, ordered with
 //      events (record `ready`, internal streams wait, record `done[i]`, caller's
 //      stream waits).  Whether hipMemcpyDeviceToDeviceNoCU really avoids compute
 //      units depends on the HIP runtime that is loaded, so this is not the default.
+//
+// The proxy polls only where polling buys latency (right after something moved,
+// and around the time a pending operation is due by the copy rate the engines have
+// shown); in between it sleeps, so a transfer costs a fraction of its length in
+// processor time (Section 4.1 charges the SM-free design about 2 % of host CPU).
 //
 // hipLaunchHostFunc is never used: host callbacks of independent streams may be
 // serialised, which is the deadlock the paper describes.
@@ -32,6 +41,8 @@
 // destination from the record, and marks started / done.  The paper's 1-bit flags
 // are kept here as monotonically increasing sequence numbers, which need no reset
 // between operations; the calling thread only draws the numbers and never waits.
+// Between two PROCESSES the same record lives in shared memory (P2pShared): either
+// side of such a transfer is an operation of its process's proxy like any other.
 #include <hsa/hsa.h>
 #include <hsa/hsa_ext_amd.h>
 

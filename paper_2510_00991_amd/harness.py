@@ -150,7 +150,7 @@ class CoRun:
         q = statistics.quantiles(ratios, n=4) if len(ratios) >= 4 else [ratios[0], statistics.median(ratios), ratios[-1]]
         pct = lambda r: 100.0 * (r - 1.0)
         return {"alone_ms": t_alone * 1e3, "corun_ms": t_with * 1e3,
-                "slowdown_pct": pct(statistics.median(ratios)),
+                "slowdown_pct": pct(statistics.median(ratios)), "slowdown_pct_mean": pct(statistics.mean(ratios)),
                 "slowdown_pct_q1": pct(q[0]), "slowdown_pct_q3": pct(q[2]),
                 "slowdown_pct_min": pct(ratios[0]), "slowdown_pct_max": pct(ratios[-1]),
                 "alone_ms_min": min(alone) * 1e3, "alone_ms_max": max(alone) * 1e3,
