@@ -133,6 +133,10 @@ const char *vccl_last_error(void);
  *       copy instead, before the operation's stream was released),
  *       "ce_test_refuse" (test hook, 0..65535: bit i makes the proxy treat engine i as
  *       refusing every copy),
+ *       "ce_proxy_poll" (0, default: while operations are in flight the sender proxy polls
+ *       around the time each is expected to complete - what operations of the same shape took
+ *       before, a model of the engines for a shape not yet seen - and sleeps in between;
+ *       1: it polls without pause, as the proxy of Section 3.1 does, which keeps one host core busy),
  *       "ce_max_engines" (0 = all; else use only that many engines),
  *       "check" (0/1 overlap validation),
  *       "moe_gather_variant" (row gather of vccl_moe_pack: 208 / 308 = one workgroup of 8

@@ -408,6 +408,10 @@ int vccl_set_option(const char *key, const char *value) {
     } else if (k == "ce_max_engines") {
         if (!in(0, 16)) return fail(VCCL_ERR_ARG, "ce_max_engines must be 0..16");
         o.ce_max_engines = (int)x;
+    } else if (k == "ce_proxy_poll") {
+        if (!in(0, 1)) return fail(VCCL_ERR_ARG, "ce_proxy_poll must be 0 or 1");
+        o.ce_proxy_poll = (int)x;
+        proxy_set_always_poll(c->proxy, x != 0);
     } else if (k == "ce_test_refuse") {
         if (!in(0, 0xffff)) return fail(VCCL_ERR_ARG, "ce_test_refuse must be 0..65535");
         o.ce_test_refuse = (int)x;
@@ -463,6 +467,7 @@ int vccl_get_option(const char *key, char *out, int cap) {
     else if (k == "ce_wait_on_cp") v = c->wait_on_cp ? 1 : 0;
     else if (k == "ce_refused") v = (unsigned long long)proxy_refused_pieces(c->proxy);
     else if (k == "ce_test_refuse") v = o.ce_test_refuse;
+    else if (k == "ce_proxy_poll") v = o.ce_proxy_poll;
     else if (k == "cu_unroll") v = o.cu_unroll;
     else if (k == "cu_wg_per_cu") v = o.cu_wg_per_cu;
     else if (k == "cu_max_wg") v = o.cu_max_wg;

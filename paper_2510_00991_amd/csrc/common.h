@@ -52,6 +52,7 @@ struct Options {
     int ce_streams = 4;
     int ce_kind = 0;   // VCCL_CE_*
     int ce_max_engines = 0;
+    int ce_proxy_poll = 0;   // 1: the sender proxy polls without pause while anything is in flight
     int ce_test_refuse = 0;   // test hook: bit i set = engine i refuses every copy
     int ce_sync = 0;   // VCCL_SYNC_*
     int check = 0;
@@ -266,6 +267,7 @@ bool proxy_sdma_available(Proxy *p, const char **why);
 int proxy_engine_count(Proxy *p);
 uint64_t proxy_sdma_errors(Proxy *p);
 uint64_t proxy_refused_pieces(Proxy *p);
+void proxy_set_always_poll(Proxy *p, bool on);
 vccl_monitor *proxy_monitor(Proxy *p, int primitive);
 void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t *issue_ns);
 int proxy_cpu_time(Proxy *p, uint64_t *sender_ns, uint64_t *receiver_ns);

@@ -56,6 +56,7 @@
 #include <cstring>
 #include <deque>
 #include <thread>
+#include <unordered_map>
 
 #include "common.h"
 
@@ -107,6 +108,9 @@ struct Op {
     bool sdma_failed = false;
     uint64_t bytes = 0;                        // bytes handed to the engines
     uint64_t t_issue_ns = 0;                   // when they were handed over
+    uint64_t est_ns = 0;                       // how long the engines are expected to take
+    uint64_t shape = 0;                        // key of the operation's shape in the proxy's history
+    uint64_t t_seen_busy_ns = 0;               // the last poll that found it incomplete
     // one side of a transfer over a cross-process connection (0 = none, 1 = sender, 2 = receiver)
     int remote_role = 0;
     P2pShared *remote = nullptr;
@@ -151,9 +155,25 @@ public:
                    std::chrono::steady_clock::now().time_since_epoch()).count();
     }
 
-    // Copy rate (bytes per nanosecond) the engines have shown on large operations: how
-    // long the sender proxy may sleep before it starts polling a pending operation.
-    double rate_bpns = 0.7;
+    // How long an operation is expected to take; the sender proxy sleeps on this before it
+    // starts polling.  Collectives repeat: the estimate for a shape (bytes to within 1/16,
+    // number of pieces) is what operations of that shape took before, kept in `history`.
+    // A shape seen for the first time takes a model of the engines: they work in parallel,
+    // each through its own pieces at kEngineRate with kCopyCost of fixed time per piece, and
+    // all together no faster than kAllRate and one piece per kAllCopyCost.  The constants
+    // lean towards too short an estimate: that costs some polling, too long a one costs latency.
+    static constexpr double kEngineRate = 0.09;    // bytes per nanosecond, one engine alone
+    static constexpr double kAllRate = 1.45;       // bytes per nanosecond, all engines together
+    static constexpr double kCopyCost = 6500.0;    // nanoseconds per piece on its engine
+    static constexpr double kAllCopyCost = 980.0;  // nanoseconds per piece over all engines (about a million copies a second)
+    std::unordered_map<uint64_t, uint64_t> history;   // shape -> nanoseconds (proxy thread only)
+    static uint64_t shape_key(uint64_t bytes, size_t pieces) {
+        int top = 63 - __builtin_clzll(bytes | 1);
+        const uint64_t coarse = top > 4 ? (bytes >> (top - 4)) << (top - 4) : bytes;
+        return coarse * 0x9E3779B97F4A7C15ull ^ (uint64_t)pieces;
+    }
+    void learn(const Op *op, uint64_t t_done);
+    std::atomic<bool> always_poll{false};          // option "ce_proxy_poll": never sleep while something is in flight
     std::mutex started_mu;
     std::condition_variable cv_started;   // copyStarted of some connection has advanced
     uint64_t nap_ns(uint64_t now, uint64_t last_progress) const;
@@ -474,6 +494,7 @@ bool Proxy::issue_sdma(Op *op) {
     // the other engines in turn, and if none takes it, it is copied through the HIP
     // runtime on an internal stream before the operation is allowed to complete.
     uint64_t load[kMaxEngines] = {};
+    uint32_t pieces_on[kMaxEngines] = {};
     std::vector<const CeCopy *> refused;
     auto offer = [&](const CeCopy &w, int e) {
         if (op->refuse_mask & (1u << e)) return false;
@@ -491,6 +512,7 @@ bool Proxy::issue_sdma(Op *op) {
         }
         if (taken) {
             load[best] += w.bytes;
+            ++pieces_on[best];
             engine_bytes[best].fetch_add(w.bytes, std::memory_order_relaxed);
         } else {
             hsa_signal_subtract_relaxed(op->left, 1);   // keep the count right so that the op still completes
@@ -508,6 +530,21 @@ bool Proxy::issue_sdma(Op *op) {
     }
     op->bytes = bytes;
     op->t_issue_ns = now_ns();
+    op->t_seen_busy_ns = op->t_issue_ns;
+    op->shape = shape_key(bytes, work.size());
+    double est;
+    auto seen = history.find(op->shape);
+    if (seen != history.end()) {
+        est = (double)seen->second;
+    } else {
+        est = (double)bytes / kAllRate;
+        if ((double)work.size() * kAllCopyCost > est) est = (double)work.size() * kAllCopyCost;
+        for (int i = 0; i < ne; ++i) {
+            const double e = (double)load[i] / kEngineRate + (double)pieces_on[i] * kCopyCost;
+            if (e > est) est = e;
+        }
+    }
+    op->est_ns = (uint64_t)est;
     const auto t1 = std::chrono::steady_clock::now();
     n_ops.fetch_add(1, std::memory_order_relaxed);
     n_copies.fetch_add(work.size(), std::memory_order_relaxed);
@@ -567,15 +604,32 @@ void Proxy::run_receiver() {
     }
 }
 
+// What an operation took goes into the history of its shape.  The proxy knows the
+// completion only to within its own polling: it lies between the last poll that found
+// the operation incomplete and the one that found it complete.  A narrow interval is a
+// measurement and is smoothed in; a wide one (the proxy slept through the completion)
+// moves the estimate to its middle only if the estimate lay outside it, so that sleeping
+// on too long an estimate cannot confirm that estimate.
+void Proxy::learn(const Op *op, uint64_t t_done) {
+    const uint64_t lo = op->t_seen_busy_ns - op->t_issue_ns, hi = t_done - op->t_issue_ns;
+    if (hi <= lo) return;
+    const uint64_t mid = lo + (hi - lo) / 2;
+    auto it = history.find(op->shape);
+    if (it == history.end()) {
+        if (history.size() >= 4096) history.clear();
+        history.emplace(op->shape, mid);
+    } else if (hi - lo < 8000) {
+        it->second = (3 * it->second + mid) / 4;
+    } else if (it->second >= hi || it->second <= lo) {
+        it->second = mid;
+    }
+}
+
 void Proxy::finish(Op *op) {
     const uint64_t t_done = now_ns();
     if (op->monitor_id) (void)vccl_monitor_complete(monitor[op->primitive], op->monitor_id, t_done, nullptr);
     if (op->remote_role == 1) op->remote->copyDone.store(op->remote_seq, std::memory_order_release);
-    if (op->kind == VCCL_CE_SDMA && op->bytes >= (8u << 20) && t_done > op->t_issue_ns) {
-        // what the engines gave this operation, smoothed: the sleep before polling leans on it
-        const double r = (double)op->bytes / (double)(t_done - op->t_issue_ns);
-        rate_bpns = 0.75 * rate_bpns + 0.25 * r;
-    }
+    if (op->kind == VCCL_CE_SDMA && !op->sdma_failed && op->shape) learn(op, t_done);
     for (auto &c : op->conns) reg[c.first].copyDone.store(c.second, std::memory_order_release);
     if (op->kind == VCCL_CE_SDMA) {
         if (op->sdma_failed) sdma_errors.fetch_add(1, std::memory_order_relaxed);
@@ -605,6 +659,7 @@ bool Proxy::poll() {
             ++k;
         }
     }
+    const uint64_t now = now_ns();
     for (size_t k = 0; k < pending.size();) {
         Op *op = pending[k];
         bool complete = true;
@@ -625,6 +680,7 @@ bool Proxy::poll() {
             }
         }
         if (!complete) {
+            op->t_seen_busy_ns = now;
             ++k;
             continue;
         }
@@ -640,9 +696,11 @@ bool Proxy::poll() {
 // paper's proxy polls without pause; here the thread polls only where that buys
 // latency: for a short while after anything has moved, and around the time a
 // pending operation is expected to complete.  In between it sleeps - until shortly
-// before that time for operations on the engines (bytes over the copy rate the
-// engines have shown), in short slices for operations whose stream is not ready yet.
+// before that time for operations on the engines (halving the remaining time with each
+// sleep, so that a wrong estimate costs little), in short slices for operations whose
+// stream is not ready yet.
 uint64_t Proxy::nap_ns(uint64_t now, uint64_t last_progress) const {
+    if (always_poll.load(std::memory_order_relaxed)) return 0;
     constexpr uint64_t kSpin = 30000;          // keep polling this long after the last progress
     if (now - last_progress < kSpin) return 0;
     uint64_t nap = !waiting.empty() ? (now - last_progress < 1000000 ? 10000 : 50000) : 200000;
@@ -653,16 +711,20 @@ uint64_t Proxy::nap_ns(uint64_t now, uint64_t last_progress) const {
             continue;
         }
         if (op->kind != VCCL_CE_SDMA) return 0;   // event back end: short copies on HIP streams, polled
-        const uint64_t dur = (uint64_t)((double)op->bytes / rate_bpns);
-        const uint64_t margin = 10000 + dur / 16;
+        const uint64_t dur = op->est_ns;
+        const uint64_t margin = 10000 + dur / 32;
         const uint64_t due = op->t_issue_ns + (dur > margin ? dur - margin : 0);
         if (now >= due) {
             // due: poll; if it is late by more than a third of its length the estimate was
-            // wrong (the engines were slow), then look again every 20 us
+            // wrong, then look again every 20 us
             if (now < op->t_issue_ns + dur + dur / 3 + 20000) return 0;
             nap = nap < 20000 ? nap : 20000;
-        } else if (due - now < nap) {
-            nap = due - now;
+        } else {
+            // not due yet: sleep half of what is left (an estimate that is too long then costs
+            // at most as much again as the operation took), nothing under 10 us
+            const uint64_t half = (due - now) / 2;
+            if (half < 5000) return 0;
+            nap = nap < half ? nap : half;
         }
     }
     return nap;
@@ -974,6 +1036,7 @@ void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uin
 
 uint64_t proxy_sdma_errors(Proxy *p) { return p->sdma_errors.load(); }
 uint64_t proxy_refused_pieces(Proxy *p) { return p->n_refused.load(); }
+void proxy_set_always_poll(Proxy *p, bool on) { p->always_poll.store(on, std::memory_order_relaxed); }
 
 // Processor time the two proxy threads have used so far (what the paper's CPU
 // utilisation figure, Section 4.1, charges to the SM-free design).

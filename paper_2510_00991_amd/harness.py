@@ -319,6 +319,7 @@ def p2p_sweep(torch, sizes=None, reps=20):
     send_p, recv_p = v.pointer_array(send), v.pointer_array(recv)
     modes = (("cu_direct", v.MODE_CU, {}),
              ("cu_staged_fifo", v.MODE_CU_STAGED, {}),
+             ("copy_engine_event", v.MODE_CE, {"ce_kind": "sdma", "ce_sync": "event"}),
              ("copy_engine_memops", v.MODE_CE, {"ce_kind": "sdma", "ce_sync": "memops"}),
              ("copy_engine_host_sync", v.MODE_CE, {"ce_kind": "sdma", "ce_sync": "host"}))
     rows = []

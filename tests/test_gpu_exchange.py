@@ -427,6 +427,26 @@ def test_engines_that_refuse_a_copy_are_passed_over(vccl, sync):
     assert int(vccl.vccl_get_option("ce_test_refuse")) == 0
 
 
+def test_proxy_sleeping_on_its_estimates_and_polling_without_pause(vccl):
+    """The sender proxy sleeps until an operation is about due (what operations of the same
+    shape took before; a model for a shape not yet seen) or, with ce_proxy_poll = 1, polls
+    without pause as the proxy of Section 3.1 does.  The same exchange repeated under both,
+    with a shape change in between so that remembered and first-seen shapes alternate: right
+    bytes every time."""
+    torch = require_gpu()
+    with pytest.raises(vccl.VcclError):
+        vccl.vccl_set_option("ce_proxy_poll", 2)
+    lays = [wl.random_layout(4200 + k, 5, size, align=16) for k, size in enumerate((64 << 10, 1 << 20, 6 << 20))]
+    sends = [[wl.payload_bytes(4300 + k, s, int(lay["send_sizes"][s])) for s in range(5)]
+             for k, lay in enumerate(lays)]
+    for poll in (0, 1, 0):
+        for rep in range(3):
+            for lay, send_np in zip(lays, sends):
+                _with_options(vccl, {"ce_proxy_poll": poll},
+                              lambda: _run_v(torch, vccl, lay, send_np, vccl.MODE_CE))
+    assert vccl.vccl_get_option("ce_proxy_poll") == "0"
+
+
 def test_small_message_alltoall_on_the_copy_engines(vccl):
     """An AlltoAll of many small blocks on the copy engines (2304 copies of 4 KiB + 16 B,
     one per block): right bytes, also when some engines refuse and their pieces are offered
