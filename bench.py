@@ -7,7 +7,7 @@ compute-unit copy path: host planning, launch and the copy itself.  The metric i
 achieved GB/s counted as bytes read plus bytes written, set against the HBM peak.
 The same run also reports the copy-engine path on the same workload, the co-run
 slowdown each path causes to a compute-bound FMA kernel (headline workload, the
-SendRecv ring in every mode, three points of the P = 64 message sweep), the MoE
+SendRecv ring in every mode, four points of the P = 64 message sweep), the MoE
 dispatch and combine, and the CPU oracle timed on the host cores.
 
 Prints ONE JSON line.  `python bench.py --gpus 1 --steps K --warmup W`.
@@ -197,7 +197,7 @@ def main():
         # Buffers of the P = 64 sweep: allocated before the first copy-engine measurement and
         # freed after the last (after device memory has been freed the copy engines of this
         # device run at about 60 % of their rate for a second or two).
-        P5, sweep_sizes = 64, (4 << 10, 64 << 10, 4 << 20)
+        P5, sweep_sizes = 64, (4 << 10, 16 << 10, 64 << 10, 4 << 20)
         sweep_bufs = {}
         if "sweep" in legs:
             for c5 in sweep_sizes:
@@ -299,7 +299,8 @@ def main():
                 assert torch.equal(recv[r][:n], send[frm[r]][:n])
             out["sendrecv_ring_8x64MiB"] = sr
         if "sweep" in legs:
-            # three points of the P = 64 message sweep: both paths' rate and the probe's slowdown
+            # four points of the P = 64 message sweep: both paths' rate and the probe's slowdown, and
+            # what one device of the 64 does in the exchange (its own 64 outgoing blocks)
             rows = []
             for c5 in sweep_sizes:
                 s5, r5 = sweep_bufs[c5]
@@ -316,6 +317,13 @@ def main():
                                                        reps=args.ce_pairs // 2 if name == "ce" else max(8, args.pairs // 2))
                 for r, s in ((3, 60), (63, 1)):     # block r of send[s] is block s of recv[r]
                     assert torch.equal(r5[r][s * c5:(s + 1) * c5], s5[s][r * c5:(r + 1) * c5])
+                one = np.zeros((P5, P5), dtype=np.uint64)
+                one[0, :] = c5
+                displs = np.tile(np.arange(P5, dtype=np.uint64) * np.uint64(c5), (P5, 1))
+                for name, mode in (("cu", v.MODE_CU), ("ce", v.MODE_CE)):
+                    fn = lambda sh=st, m=mode: v.vccl_alltoallv(sp, one, displs, rp, one.T.copy(), displs, P5, m, sh)
+                    row[name]["one_rank_share_us"] = statistics.median(
+                        time_region(torch, fn, 10, 2)[0] for _ in range(3)) / 10 * 1e6
                 rows.append(row)
             out["alltoall_sweep_p64"] = rows
         if "moe" in legs:

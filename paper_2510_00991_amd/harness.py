@@ -14,6 +14,8 @@ import statistics
 import sys
 import time
 
+import numpy as np
+
 from . import binding as v
 
 
@@ -246,6 +248,16 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
             if co is not None:
                 row[name].update(co.beside(lambda s, m=mode: v.vccl_alltoall(send_p, recv_p, c, P, m, s),
                                            moved, t, reps=8))
+        # What one device of P does in this exchange: its own P outgoing blocks (the other
+        # ranks' blocks are the work of their devices' engines or compute units).
+        one = np.zeros((P, P), dtype=np.uint64)
+        one[0, :] = c
+        displs = np.tile(np.arange(P, dtype=np.uint64) * np.uint64(c), (P, 1))
+        for name, mode in (("cu", v.MODE_CU), ("ce", v.MODE_CE)):
+            fn = lambda s=st, m=mode: v.vccl_alltoallv(send_p, one, displs, recv_p, one.T.copy(), displs, P, m, s)
+            t = statistics.median(time_region(torch, fn, 10, 2)[0] for _ in range(3)) / 10
+            row[name]["one_rank_share_us"] = t * 1e6
+            row[name]["one_rank_share_GBps"] = 2.0 * P * c / t / 1e9
         rows.append(row)
     del send, recv, bufs
     torch.cuda.empty_cache()
