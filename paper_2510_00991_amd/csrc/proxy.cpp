@@ -25,9 +25,10 @@
 //      units depends on the HIP runtime that is loaded, so this is not the default.
 //
 // The proxy polls only where polling buys latency (right after something moved,
-// and around the time a pending operation is due by the copy rate the engines have
-// shown); in between it sleeps, so a transfer costs a fraction of its length in
-// processor time (Section 4.1 charges the SM-free design about 2 % of host CPU).
+// and around the time a pending operation is due, going by what operations of the
+// same shape took before); in between it sleeps, so a transfer costs a fraction of
+// its length in processor time (Section 4.1 charges the SM-free design about 2 % of
+// host CPU).  Option ce_proxy_poll = 1 makes it poll without pause, as in the paper.
 //
 // hipLaunchHostFunc is never used: host callbacks of independent streams may be
 // serialised, which is the deadlock the paper describes.
@@ -338,6 +339,8 @@ void Proxy::put_ref(Op *op) {  // mu held
         op->sdma_failed = false;
         op->remote_role = 0;
         op->remote = nullptr;
+        op->shape = 0;     // only an operation that went to the engines has one
+        op->est_ns = 0;
         free_ops.push_back(op);
     }
 }
