@@ -82,7 +82,8 @@ typedef enum {
     VCCL_ERR_HIP = -4,            /* a HIP runtime call failed; message holds hipGetErrorString */
     VCCL_ERR_NOT_INIT = -5,       /* vccl_init has not been called (or vccl_finalize has) */
     VCCL_ERR_UNSUPPORTED = -6,    /* mode not available for this primitive / device */
-    VCCL_ERR_TIMEOUT = -7         /* a bounded device-side wait of the staged FIFO gave up */
+    VCCL_ERR_TIMEOUT = -7         /* a bounded wait gave up: the staged FIFO's device-side wait, vccl_p2p_connect's
+                                     deadline; also a call on a cross-process connection that was aborted */
 } vccl_status;
 
 /* Largest number of virtual ranks vccl_init accepts. */

@@ -91,3 +91,44 @@ def test_abort_releases_a_receive_whose_sender_never_comes():
         assert not os.path.exists("/dev/shm" + name)
     finally:
         v.vccl_finalize()
+
+
+def test_p2p_calls_reject_what_cannot_work():
+    """Argument errors of the cross-process calls, none of which needs a peer: a bad name, a
+    buffer that reaches past its allocation, a name that is taken, a connect that finds no
+    export before its deadline, a receive beyond the registered bytes, a send on the
+    receiving end.  Nothing is enqueued by a call that fails."""
+    torch = require_gpu()
+    import paper_2510_00991_amd as v
+    v.vccl_init(0, 8)
+    name = f"/vccl_test_{os.getpid()}_args"
+    try:
+        buf = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+        st = int(torch.cuda.current_stream().cuda_stream)
+        for bad in ("no_slash", "/with/two", ""):
+            with pytest.raises(v.VcclError) as e:
+                v.vccl_p2p_export(bad, buf, 1 << 16)
+            assert e.value.code == -1, bad
+        with pytest.raises(v.VcclError) as e:          # torch's allocations are at least 512 B apart, never 1 TiB long
+            v.vccl_p2p_export(name, buf, 1 << 40)
+        assert e.value.code == -1
+        assert not os.path.exists("/dev/shm" + name)
+        conn = v.vccl_p2p_export(name, buf, 1 << 16)
+        with pytest.raises(v.VcclError) as e:          # the name is taken
+            v.vccl_p2p_export(name, buf, 1 << 16)
+        assert e.value.code == -1
+        with pytest.raises(v.VcclError) as e:
+            v.vccl_p2p_connect(name + "_nobody", 0.05)
+        assert e.value.code == -7
+        with pytest.raises(v.VcclError) as e:          # beyond the registered bytes
+            v.vccl_p2p_recv(conn, (1 << 16) - 8, 16, st)
+        assert e.value.code == -1
+        with pytest.raises(v.VcclError) as e:          # the exporting end receives, it does not send
+            v.vccl_p2p_send(conn, buf, 16, st)
+        assert e.value.code == -1
+        assert v.vccl_p2p_record(conn)[:3] == (0, 0, 0)   # none of the failed calls left a transfer behind
+        torch.cuda.synchronize()
+        v.vccl_p2p_close(conn)
+        assert not os.path.exists("/dev/shm" + name)
+    finally:
+        v.vccl_finalize()
