@@ -139,6 +139,7 @@ const char *vccl_last_error(void);
  *       before, a model of the engines for a shape not yet seen - and sleeps in between;
  *       1: it polls without pause, as the proxy of Section 3.1 does, which keeps one host core busy),
  *       "ce_max_engines" (0 = all; else use only that many engines),
+ *       "p2p_close_wait_ms" (0..3600000, default 10000: see vccl_p2p_close),
  *       "check" (0/1 overlap validation),
  *       "moe_gather_variant" (row gather of vccl_moe_pack: 208 / 308 = one workgroup of 8
  *       wavefronts per 2 KiB piece of a token's row, one wavefront per slot, non-temporal /
@@ -221,7 +222,11 @@ int vccl_p2p_reginfo(int receiver_rank, uint64_t *receiver_ready, uint64_t *copy
  * failure is reported by the next copy-engine call, and later sends / receives on the
  * connection return VCCL_ERR_TIMEOUT.  vccl_p2p_record reads the
  * record from either side (any pointer may be NULL).  vccl_p2p_close waits for this
- * process's outstanding copy-engine operations, unmaps, and (receiver) removes the name.
+ * process's outstanding copy-engine operations - for at most 10 seconds (option
+ * "p2p_close_wait_ms"): if transfers of the
+ * connection are still outstanding then (the peer never posted its side), it aborts the
+ * connection as vccl_p2p_abort does and returns VCCL_ERR_TIMEOUT after cleaning up - then
+ * unmaps, and (receiver) removes the name.
  * Needs the "sdma" copy-engine back end. */
 typedef struct vccl_p2p_conn vccl_p2p_conn;
 int vccl_p2p_export(const char *name, void *recvbuf_dev, uint64_t capacity, vccl_p2p_conn **out);

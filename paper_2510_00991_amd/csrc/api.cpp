@@ -399,6 +399,9 @@ int vccl_set_option(const char *key, const char *value) {
         if (!(x == 4 || x == 8 || x == 16 || x == 108 || x == 116 || x == 208 || x == 308 || x == 408 || x == 508))
             return fail(VCCL_ERR_ARG, "moe_gather_variant must be 4, 8, 16, 108, 116, 208, 308, 408 or 508");
         o.moe_gather_variant = (int)x;
+    } else if (k == "p2p_close_wait_ms") {
+        if (!in(0, 3600000)) return fail(VCCL_ERR_ARG, "p2p_close_wait_ms must be 0..3600000");
+        o.p2p_close_wait_ms = (int)x;
     } else if (k == "moe_unpack_variant") {
         if (!in(0, 3)) return fail(VCCL_ERR_ARG, "moe_unpack_variant must be 0..3");
         o.moe_unpack_variant = (int)x;
@@ -477,6 +480,7 @@ int vccl_get_option(const char *key, char *out, int cap) {
     else if (k == "ce_streams") v = o.ce_streams;
     else if (k == "moe_gather_variant") v = o.moe_gather_variant;
     else if (k == "moe_unpack_variant") v = o.moe_unpack_variant;
+    else if (k == "p2p_close_wait_ms") v = o.p2p_close_wait_ms;
     else if (k == "moe_gather_full") v = o.moe_gather_full;
     else if (k == "ce_max_engines") v = o.ce_max_engines;
     else if (k == "check") v = o.check;
@@ -1057,10 +1061,18 @@ int vccl_p2p_abort(vccl_p2p_conn *conn) {
 int vccl_p2p_close(vccl_p2p_conn *conn) {
     if (!conn) return fail(VCCL_ERR_ARG, "NULL connection");
     auto c = ctx_get();
-    if (c) (void)proxy_drain(c->proxy);      // no operation of this process still points at the record
     int rv = VCCL_OK;
+    // No operation of this process may still point at the record when it is unmapped.  A
+    // transfer whose other side never comes would wait for ever: after the deadline the
+    // connection is aborted, which ends every outstanding transfer at the proxy's next poll.
+    if (c && !proxy_drain_for(c->proxy, 1e-3 * options_of(*c).p2p_close_wait_ms) &&
+        conn->sh->copyDone.load(std::memory_order_acquire) < conn->next_seq) {
+        conn->sh->aborted.store(1, std::memory_order_release);
+        rv = fail(VCCL_ERR_TIMEOUT, "connection '%s' closed with transfers outstanding: aborted", conn->name.c_str());
+        if (!proxy_drain_for(c->proxy, 10.0)) return rv;   // an aborted transfer ends at the next poll; something else holds the proxy up: keep the mappings
+    }
     if (conn->role == 1) {
-        if (conn->mapped_alloc && hipIpcCloseMemHandle(conn->mapped_alloc) != hipSuccess)
+        if (conn->mapped_alloc && hipIpcCloseMemHandle(conn->mapped_alloc) != hipSuccess && rv == VCCL_OK)
             rv = fail(VCCL_ERR_HIP, "hipIpcCloseMemHandle failed");
         conn->sh->sender_attached.store(0);
     } else {

@@ -48,6 +48,7 @@ struct Options {
     int cu_fast_path = 1;
     int moe_gather_variant = 208;
     int moe_unpack_variant = 2;
+    int p2p_close_wait_ms = 10000;   // how long vccl_p2p_close waits before it aborts the connection's transfers
     int moe_gather_full = 1;   // allow the unchecked gather kernels when pieces and slot groups are whole
     int ce_streams = 4;
     int ce_kind = 0;   // VCCL_CE_*
@@ -262,6 +263,7 @@ int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hip
 int proxy_reginfo(Proxy *p, int receiver, uint64_t *ready, uint64_t *started, uint64_t *done,
                   void **addr);
 int proxy_drain(Proxy *p);
+bool proxy_drain_for(Proxy *p, double seconds);   // false if operations were still in flight at the deadline
 // Whether the HSA/SDMA back end came up on this device (and, if not, why).
 bool proxy_sdma_available(Proxy *p, const char **why);
 int proxy_engine_count(Proxy *p);

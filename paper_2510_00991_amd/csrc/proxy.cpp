@@ -809,6 +809,11 @@ int proxy_drain(Proxy *p) {
     return VCCL_OK;
 }
 
+bool proxy_drain_for(Proxy *p, double seconds) {
+    std::unique_lock<std::mutex> lk(p->mu);
+    return p->cv_idle.wait_for(lk, std::chrono::duration<double>(seconds), [&] { return p->in_flight == 0; });
+}
+
 void proxy_destroy(Proxy *p) {
     if (!p) return;
     proxy_drain(p);

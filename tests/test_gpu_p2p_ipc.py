@@ -132,3 +132,31 @@ def test_p2p_calls_reject_what_cannot_work():
         assert not os.path.exists("/dev/shm" + name)
     finally:
         v.vccl_finalize()
+
+
+def test_close_with_a_transfer_outstanding_aborts_it_after_its_deadline():
+    """vccl_p2p_close must not wait for ever for a peer that never comes: after its deadline
+    (shortened here) it aborts the connection, the stream is released with the buffer
+    untouched, the name is removed, and the call says what it did."""
+    torch = require_gpu()
+    import paper_2510_00991_amd as v
+    v.vccl_init(0, 8)
+    name = f"/vccl_test_{os.getpid()}_close"
+    try:
+        v.vccl_set_option("p2p_close_wait_ms", 100)
+        buf = torch.full((4096,), 0x3C, dtype=torch.uint8, device="cuda")
+        conn = v.vccl_p2p_export(name, buf, 4096)
+        stream = torch.cuda.Stream()
+        v.vccl_p2p_recv(conn, 0, 4096, int(stream.cuda_stream))
+        with pytest.raises(v.VcclError) as e:
+            v.vccl_p2p_close(conn)
+        assert e.value.code == -7
+        stream.synchronize()                                   # released by the abort
+        assert bool((buf == 0x3C).all())
+        assert not os.path.exists("/dev/shm" + name)
+        with pytest.raises(v.VcclError):                       # the aborted transfer is reported once
+            v.vccl_alltoall([buf], [buf[2048:]], 16, 1, v.MODE_CE, int(stream.cuda_stream))
+        v.vccl_alltoall([buf], [buf[2048:]], 16, 1, v.MODE_CE, int(stream.cuda_stream))
+        stream.synchronize()
+    finally:
+        v.vccl_finalize()
