@@ -203,9 +203,9 @@ def main():
             for c5 in sweep_sizes:
                 s5 = [torch.empty(P5 * c5, dtype=torch.uint8, device="cuda") for _ in range(P5)]
                 r5 = [torch.empty(P5 * c5, dtype=torch.uint8, device="cuda") for _ in range(P5)]
-                for s in range(P5):     # seeded payload in the first MiB of each buffer (timing does not depend on values)
-                    n = min(P5 * c5, 1 << 20)
-                    s5[s][:n].copy_(torch.from_numpy(wl.payload_bytes(wl.config_seed(5), s, n)))
+                for s in range(P5):     # seeded payload: one MiB per rank, repeated through the buffer (what a
+                    n = min(P5 * c5, 1 << 20)   # transfer costs its neighbours depends on the values it moves)
+                    s5[s].view(-1, n).copy_(torch.from_numpy(wl.payload_bytes(wl.config_seed(5), s, n)).cuda())
                 sweep_bufs[c5] = (s5, r5)
 
         def a2a_cu():
@@ -272,7 +272,9 @@ def main():
                                      f"{co.iters} rounds of 64 FMAs per lane",
                             "protocol": f"{args.pairs} alone/beside pairs per compute-unit figure, {args.ce_pairs} per "
                                         "copy-engine figure, in alternating order; median, mean and quartiles of the "
-                                        "paired ratios",
+                                        "paired ratios; probe_shader_ticks_pct = change of the probe's own shader-clock "
+                                        "tick count (held up inside compute units), shader_clock_MHz_* = its ticks per "
+                                        "real-time tick (the chip lowering its clock)",
                             "cu_path": cor_cu, "cu_path_capped_1wg_per_cu": cor_cap,
                             "cu_path_capped_64wg": cor_cap64, "copy_engine_path": cor_ce}
         if "sendrecv" in legs:

@@ -417,6 +417,19 @@ int vccl_hbm_probe(int kind, const void *src, void *dst, uint64_t bytes, int thr
 int vccl_fma_probe(float *out_dev, uint32_t workgroups, uint32_t threads, uint64_t iters,
                    void *stream);
 
+/* The same probe, reporting for every workgroup how long it ran on two counters of the
+ * chip: clocks_dev (device, 2 * workgroups uint64, 8-byte aligned) receives per workgroup
+ * the elapsed ticks of the shader clock, which the chip's power management raises and
+ * lowers, and of the constant-rate real-time counter (vccl_device_wall_clock_khz ticks
+ * per millisecond).  A probe that takes longer beside a transfer with the same shader
+ * ticks was slowed down by a lower clock; one with more shader ticks was held up inside
+ * its compute units (the mechanism Appendix E describes). */
+int vccl_fma_probe_clocks(float *out_dev, uint64_t *clocks_dev, uint32_t workgroups, uint32_t threads,
+                          uint64_t iters, void *stream);
+
+/* Rate of the device's constant real-time counter in kHz (negative: error code). */
+int vccl_device_wall_clock_khz(void);
+
 /* Window-based bandwidth monitor (Section 3.4), host-only and usable on its own:
  * feed it the post and completion times of messages (nanoseconds on any monotonic
  * clock, calls in non-decreasing time order) and it returns, per completion, the

@@ -24,7 +24,7 @@ from .binding import (  # noqa: E402,F401
     vccl_p2p_export, vccl_p2p_connect, vccl_p2p_recv, vccl_p2p_send, vccl_p2p_record, vccl_p2p_abort, vccl_p2p_close,
     vccl_alltoall, vccl_alltoallv, vccl_plan_alltoallv,
     vccl_moe_pack, vccl_moe_pack_noalloc, vccl_moe_pack_per_rank, vccl_moe_dispatch_fused, vccl_moe_combine_fused, vccl_moe_unpack, vccl_moe_exchange_layout,
-    vccl_fma_probe, vccl_hbm_probe, vccl_proxy_stats, vccl_proxy_cpu_time, vccl_device_cu_count,
+    vccl_fma_probe, vccl_fma_probe_clocks, vccl_device_wall_clock_khz, vccl_hbm_probe, vccl_proxy_stats, vccl_proxy_cpu_time, vccl_device_cu_count,
     vccl_monitor_create, vccl_monitor_destroy, vccl_monitor_post, vccl_monitor_complete,
     vccl_monitor_totals, vccl_proxy_monitor,
 )

@@ -77,6 +77,9 @@ EXPORTS = {
                                       ctypes.c_uint64, ctypes.c_void_p]),
     "vccl_fma_probe": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32,
                                       ctypes.c_uint64, ctypes.c_void_p]),
+    "vccl_fma_probe_clocks": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint32,
+                                             ctypes.c_uint64, ctypes.c_void_p]),
+    "vccl_device_wall_clock_khz": (ctypes.c_int, []),
     "vccl_monitor_create": (ctypes.c_void_p, [ctypes.c_int, ctypes.c_uint64]),
     "vccl_monitor_destroy": (None, [ctypes.c_void_p]),
     "vccl_monitor_post": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64]),
@@ -415,6 +418,16 @@ def vccl_hbm_probe(kind: int, src, dst, nbytes: int, threads: int, vecs_per_lane
 def vccl_fma_probe(out_dev, workgroups: int, threads: int, iters: int, stream=None) -> None:
     _check(load().vccl_fma_probe(ctypes.c_void_p(_addr(out_dev)), workgroups, threads, int(iters),
                                  _stream(stream)))
+
+
+def vccl_fma_probe_clocks(out_dev, clocks_dev, workgroups: int, threads: int, iters: int, stream=None) -> None:
+    """clocks_dev: device tensor of 2 * workgroups int64 (shader-clock ticks, real-time ticks per workgroup)."""
+    _check(load().vccl_fma_probe_clocks(ctypes.c_void_p(_addr(out_dev)), ctypes.c_void_p(_addr(clocks_dev)),
+                                        workgroups, threads, int(iters), _stream(stream)))
+
+
+def vccl_device_wall_clock_khz() -> int:
+    return _check(load().vccl_device_wall_clock_khz())
 
 
 def vccl_proxy_stats():

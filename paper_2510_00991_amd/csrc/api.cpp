@@ -810,7 +810,8 @@ int vccl_plan_alltoallv(void *const *sendbuf, const uint64_t *sendcounts, const 
     return VCCL_OK;
 }
 
-int vccl_fma_probe(float *out_dev, uint32_t workgroups, uint32_t threads, uint64_t iters, void *stream) {
+static int fma_probe(float *out_dev, uint64_t *clocks_dev, uint32_t workgroups, uint32_t threads, uint64_t iters,
+                     void *stream) {
     auto c = ctx_get();
     if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
     if (!out_dev) return fail(VCCL_ERR_ARG, "out_dev is NULL");
@@ -818,7 +819,26 @@ int vccl_fma_probe(float *out_dev, uint32_t workgroups, uint32_t threads, uint64
         return fail(VCCL_ERR_ARG, "threads = %u must be a multiple of 64 up to 1024", threads);
     if (workgroups == 0) workgroups = (uint32_t)c->cu_count;
     if (workgroups > (1u << 20)) return fail(VCCL_ERR_ARG, "workgroups = %u is too large", workgroups);
-    return launch_fma_probe(out_dev, workgroups, threads, iters, (hipStream_t)stream);
+    return launch_fma_probe(out_dev, clocks_dev, workgroups, threads, iters, (hipStream_t)stream);
+}
+
+int vccl_fma_probe(float *out_dev, uint32_t workgroups, uint32_t threads, uint64_t iters, void *stream) {
+    return fma_probe(out_dev, nullptr, workgroups, threads, iters, stream);
+}
+
+int vccl_fma_probe_clocks(float *out_dev, uint64_t *clocks_dev, uint32_t workgroups, uint32_t threads,
+                          uint64_t iters, void *stream) {
+    if (!clocks_dev) return fail(VCCL_ERR_ARG, "clocks_dev is NULL");
+    if (reinterpret_cast<uintptr_t>(clocks_dev) & 7u) return fail(VCCL_ERR_ARG, "clocks_dev is not 8-byte aligned");
+    return fma_probe(out_dev, clocks_dev, workgroups, threads, iters, stream);
+}
+
+int vccl_device_wall_clock_khz(void) {
+    auto c = ctx_get();
+    if (!c) return fail(VCCL_ERR_NOT_INIT, "vccl_init has not been called");
+    int khz = 0;
+    VCCL_HIP(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device));
+    return khz;
 }
 
 int vccl_hbm_probe(int kind, const void *src, void *dst, uint64_t bytes, int threads, int vecs_per_lane,

@@ -207,7 +207,7 @@ int launch_moe_unpack(MoeScratch &sc, const void *const *packed, const int32_t *
                       int unpack_variant, hipStream_t stream);
 
 // ---- co-run probe
-int launch_fma_probe(float *out, uint32_t workgroups, uint32_t threads, uint64_t iters,
+int launch_fma_probe(float *out, uint64_t *clocks, uint32_t workgroups, uint32_t threads, uint64_t iters,
                      hipStream_t stream);
 
 // kind: 0 read-only (dst = 64-byte sink), 1 write-only, 2 copy, 3 write rows of row_bytes at row_index[i]

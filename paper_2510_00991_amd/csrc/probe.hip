@@ -7,8 +7,19 @@
 
 namespace vccl {
 
-__global__ void fma_probe_kernel(float *out, uint64_t iters) {
+// CLOCKS: every workgroup also reports how long it ran on two of the chip's counters -
+// the shader clock (which power management raises and lowers) and the constant-rate
+// real-time counter - so that a longer run time can be told apart: more cycles means the
+// workgroup was held up inside its compute unit, the same cycles at a lower clock means
+// the chip slowed its shaders down.
+template <bool CLOCKS>
+__global__ void fma_probe_kernel(float *out, uint64_t iters, uint64_t *clocks) {
     const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
+    uint64_t c0 = 0, r0 = 0;
+    if (CLOCKS) {
+        c0 = clock64();
+        r0 = wall_clock64();
+    }
     // eight independent dependency chains per lane keep the FMA pipe full
     float a0 = 1.0f + gid * 1e-7f, a1 = a0 + 0.125f, a2 = a0 + 0.25f, a3 = a0 + 0.375f;
     float a4 = a0 + 0.5f, a5 = a0 + 0.625f, a6 = a0 + 0.75f, a7 = a0 + 0.875f;
@@ -27,11 +38,19 @@ __global__ void fma_probe_kernel(float *out, uint64_t iters) {
         }
     }
     out[gid] = ((a0 + a1) + (a2 + a3)) + ((a4 + a5) + (a6 + a7));
+    if (CLOCKS) {
+        const uint64_t c1 = clock64(), r1 = wall_clock64();
+        if (threadIdx.x == 0) {
+            clocks[2 * (size_t)blockIdx.x] = c1 - c0;
+            clocks[2 * (size_t)blockIdx.x + 1] = r1 - r0;
+        }
+    }
 }
 
-int launch_fma_probe(float *out, uint32_t workgroups, uint32_t threads, uint64_t iters,
+int launch_fma_probe(float *out, uint64_t *clocks, uint32_t workgroups, uint32_t threads, uint64_t iters,
                      hipStream_t stream) {
-    fma_probe_kernel<<<dim3(workgroups), dim3(threads), 0, stream>>>(out, iters);
+    if (clocks) fma_probe_kernel<true><<<dim3(workgroups), dim3(threads), 0, stream>>>(out, iters, clocks);
+    else fma_probe_kernel<false><<<dim3(workgroups), dim3(threads), 0, stream>>>(out, iters, nullptr);
     VCCL_HIP(hipGetLastError());
     return VCCL_OK;
 }

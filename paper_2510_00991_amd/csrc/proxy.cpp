@@ -158,7 +158,7 @@ public:
 
     // How long an operation is expected to take; the sender proxy sleeps on this before it
     // starts polling.  Collectives repeat: the estimate for a shape (bytes to within 1/16,
-    // number of pieces) is what operations of that shape took before, kept in `history`.
+    // number of pieces, engines in use) is what operations of that shape took before, kept in `history`.
     // A shape seen for the first time takes a model of the engines: they work in parallel,
     // each through its own pieces at kEngineRate with kCopyCost of fixed time per piece, and
     // all together no faster than kAllRate and one piece per kAllCopyCost.  The constants
@@ -168,10 +168,10 @@ public:
     static constexpr double kCopyCost = 6500.0;    // nanoseconds per piece on its engine
     static constexpr double kAllCopyCost = 980.0;  // nanoseconds per piece over all engines (about a million copies a second)
     std::unordered_map<uint64_t, uint64_t> history;   // shape -> nanoseconds (proxy thread only)
-    static uint64_t shape_key(uint64_t bytes, size_t pieces) {
+    static uint64_t shape_key(uint64_t bytes, size_t pieces, int engines) {
         int top = 63 - __builtin_clzll(bytes | 1);
         const uint64_t coarse = top > 4 ? (bytes >> (top - 4)) << (top - 4) : bytes;
-        return coarse * 0x9E3779B97F4A7C15ull ^ (uint64_t)pieces;
+        return (coarse * 0x9E3779B97F4A7C15ull ^ (uint64_t)pieces) + (uint64_t)engines;
     }
     void learn(const Op *op, uint64_t t_done);
     std::atomic<bool> always_poll{false};          // option "ce_proxy_poll": never sleep while something is in flight
@@ -534,7 +534,7 @@ bool Proxy::issue_sdma(Op *op) {
     op->bytes = bytes;
     op->t_issue_ns = now_ns();
     op->t_seen_busy_ns = op->t_issue_ns;
-    op->shape = shape_key(bytes, work.size());
+    op->shape = shape_key(bytes, work.size(), ne);
     double est;
     auto seen = history.find(op->shape);
     if (seen != history.end()) {

@@ -62,7 +62,10 @@ def time_region(torch, fn, steps, warmup):
 
 class CoRun:
     """FMA probe on its own stream, timed alone and while `comm_fn` keeps another
-    stream busy.  slowdown = (T_with - T_alone) / T_alone."""
+    stream busy.  slowdown = (T_with - T_alone) / T_alone.  Every probe also reports the
+    shader-clock ticks and the real-time ticks its workgroups ran for, which splits a
+    slowdown into its two possible causes: more shader ticks (the probe was held up
+    inside its compute units) or the same ticks at a lower shader clock."""
 
     def __init__(self, torch, iters=60000, threads=256, workgroups=0):
         self.torch = torch
@@ -70,6 +73,8 @@ class CoRun:
         self.cu = v.vccl_device_cu_count()
         n = (workgroups or self.cu) * threads
         self.out = torch.zeros(n, dtype=torch.float32, device="cuda")
+        self.clocks = torch.zeros((workgroups or self.cu, 2), dtype=torch.int64, device="cuda")
+        self.wall_khz = v.vccl_device_wall_clock_khz()
         self.comp = torch.cuda.Stream()
         self.comm = torch.cuda.Stream()
         self._alone = None
@@ -82,17 +87,24 @@ class CoRun:
         a, b = _ev(torch), _ev(torch)
         with torch.cuda.stream(self.comp):
             a.record()
-            v.vccl_fma_probe(self.out, self.workgroups, self.threads, self.iters,
-                             int(self.comp.cuda_stream))
+            v.vccl_fma_probe_clocks(self.out, self.clocks, self.workgroups, self.threads, self.iters,
+                                    int(self.comp.cuda_stream))
             b.record()
         return a, b
 
-    def _time_alone(self):
+    def _ticks(self):
+        """(shader-clock ticks, real-time ticks) of the probe launched last: medians over its workgroups."""
+        k = self.clocks.cpu().numpy()
+        return float(np.median(k[:, 0])), float(np.median(k[:, 1]))
+
+    def _time_alone(self, ticks=None):
         """Probe preceded by an untimed probe, so that the timed one always starts
         with the compute units already busy and the clocks settled."""
         self._probe()
         a, b = self._probe()
         self.comp.synchronize()
+        if ticks is not None:
+            ticks.append(self._ticks())
         return a.elapsed_time(b) * 1e-3
 
     def alone(self, reps=10):
@@ -118,6 +130,7 @@ class CoRun:
         n_comm = max(1, int(1.25 * t_guess / max(comm_seconds_per_call, 1e-6)) + 1)
         sh = self.comm_stream_handle()
         alone, both, comm_t = [], [], []
+        ticks_alone, ticks_both = [], []
 
         def timed_beside():
             self._probe()                                   # untimed lead-in
@@ -134,24 +147,29 @@ class CoRun:
             torch.cuda.synchronize()
             both.append(a.elapsed_time(b) * 1e-3)
             comm_t.append(c0.elapsed_time(c1) * 1e-3)
+            ticks_both.append(self._ticks())
 
         for i in range(reps):
             torch.cuda.synchronize()
             if i % 2 == 0:
-                alone.append(self._time_alone())
+                alone.append(self._time_alone(ticks_alone))
                 torch.cuda.synchronize()
                 timed_beside()
             else:
                 timed_beside()
                 torch.cuda.synchronize()
-                alone.append(self._time_alone())
+                alone.append(self._time_alone(ticks_alone))
         t_alone = statistics.median(alone)
         t_with = statistics.median(both)
         tc = statistics.median(comm_t)
         ratios = sorted(b / a for a, b in zip(alone, both))
         q = statistics.quantiles(ratios, n=4) if len(ratios) >= 4 else [ratios[0], statistics.median(ratios), ratios[-1]]
         pct = lambda r: 100.0 * (r - 1.0)
+        mhz = lambda t: statistics.median(c / r for c, r in t) * self.wall_khz * 1e-3
         return {"alone_ms": t_alone * 1e3, "corun_ms": t_with * 1e3,
+                # the two possible causes of a slowdown, from the probe's own counters
+                "probe_shader_ticks_pct": pct(statistics.median(b[0] / a[0] for a, b in zip(ticks_alone, ticks_both))),
+                "shader_clock_MHz_alone": mhz(ticks_alone), "shader_clock_MHz_beside": mhz(ticks_both),
                 "slowdown_pct": pct(statistics.median(ratios)), "slowdown_pct_mean": pct(statistics.mean(ratios)),
                 "slowdown_pct_q1": pct(q[0]), "slowdown_pct_q3": pct(q[2]),
                 "slowdown_pct_min": pct(ratios[0]), "slowdown_pct_max": pct(ratios[-1]),
@@ -225,9 +243,9 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
     for c in sizes:
         send = [torch.empty(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
         recv = [torch.empty(P * c, dtype=torch.uint8, device="cuda") for _ in range(P)]
-        for s in range(P):     # seeded payload, first 1 MiB of each buffer (timing does not depend on values)
-            n = min(P * c, 1 << 20)
-            send[s][:n].copy_(torch.from_numpy(wl.payload_bytes(wl.config_seed(5), s, n)))
+        for s in range(P):     # seeded payload: one MiB per rank, repeated through the buffer (the power a
+            n = min(P * c, 1 << 20)   # transfer draws, and with it what it costs its neighbours, depends on the values)
+            send[s].view(-1, n).copy_(torch.from_numpy(wl.payload_bytes(wl.config_seed(5), s, n)).cuda())
         bufs[c] = (send, recv)
     for c in sizes:
         send, recv = bufs[c]
@@ -287,7 +305,9 @@ def hbm_ceilings(torch, gib=(1, 7), reps=10):
     sink = torch.zeros(64, dtype=torch.uint8, device="cuda")
     for g in gib:
         n = g << 30
-        a = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+        import workloads as wl
+        a = torch.empty(n, dtype=torch.uint8, device="cuda")      # seeded payload, one MiB repeated
+        a.view(-1, 1 << 20).copy_(torch.from_numpy(wl.payload_bytes(wl.config_seed(2), 0, 1 << 20)).cuda())
         b = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(2)
         for kind, name, moved in ((0, "read", n), (1, "write", n), (2, "copy", 2 * n)):
             for threads, vecs in ((64, 1), (64, 2), (64, 4), (64, 16), (256, 1), (256, 4)):
@@ -427,6 +447,15 @@ def pipeline_1f1b(torch, stages=4, micro=8, act_bytes=128 << 20, fwd_iters=4000,
     src_f, dst_f, src_b, dst_b = bufs(), bufs(), bufs(), bufs()
     null = torch.zeros(16, dtype=torch.uint8, device="cuda")
     pay = {}
+    if payload is None:
+        # timing runs move activation-like values (N(0,1) as bf16), not zeros: the power a
+        # transfer draws, and with it what it costs the compute beside it, depends on the values
+        import workloads as wl
+        n = min(act_bytes, 4 << 20) & ~1
+        for i, per_stage in enumerate(src_f + src_b):
+            block = torch.from_numpy(wl.normal_bf16_bits(wl.config_seed(4), i, n // 2).view("uint8")).cuda()
+            for buf in per_stage:
+                buf[:(act_bytes // n) * n].view(-1, n).copy_(block)
     if payload is not None:
         for i in range(stages):
             for m in range(micro):
