@@ -206,7 +206,11 @@ def main():
                 for s in range(P5):     # seeded payload: one MiB per rank, repeated through the buffer (what a
                     n = min(P5 * c5, 1 << 20)   # transfer costs its neighbours depends on the values it moves)
                     s5[s].view(-1, n).copy_(torch.from_numpy(wl.payload_bytes(wl.config_seed(5), s, n)).cuda())
-                sweep_bufs[c5] = (s5, r5)
+                # for small blocks the copy-engine path also gets receive buffers that are slices of one
+                # allocation (a constant stride between the ranks): one pitched copy per rank, not 64 plain ones
+                slab5 = ([b[:P5 * c5] for b in torch.empty((P5, P5 * c5 + 4096), dtype=torch.uint8, device="cuda").unbind(0)]
+                         if c5 <= 32 << 10 else None)
+                sweep_bufs[c5] = (s5, r5, slab5)
 
         def a2a_cu():
             v.vccl_alltoall(send, recv, c, P, v.MODE_CU, st)
@@ -305,20 +309,30 @@ def main():
             # what one device of the 64 does in the exchange (its own 64 outgoing blocks)
             rows = []
             for c5 in sweep_sizes:
-                s5, r5 = sweep_bufs[c5]
+                s5, r5, slab5 = sweep_bufs[c5]
                 sp, rp = v.pointer_array(s5), v.pointer_array(r5)
+                slab_p = v.pointer_array(slab5) if slab5 is not None else rp
                 moved = 2.0 * P5 * P5 * c5
                 row = {"bytes_per_peer": c5}
                 for name, mode in (("cu", v.MODE_CU), ("ce", v.MODE_CE)):
-                    fn = lambda sh=st, m=mode: v.vccl_alltoall(sp, rp, c5, P5, m, sh)
+                    to = slab_p if name == "ce" else rp
+                    fn = lambda sh=st, m=mode, to=to: v.vccl_alltoall(sp, to, c5, P5, m, sh)
                     k = 10 if name == "cu" else 3
                     t = statistics.median(time_region(torch, fn, k, 2)[0] for _ in range(3)) / k
                     row[name] = {"us": t * 1e6, "GBps": moved / t / 1e9}
+                    if name == "ce":     # the same call with plain copies only (one per block)
+                        v.vccl_set_option("ce_pitched", 0)
+                        tp = statistics.median(time_region(torch, fn, k, 2)[0] for _ in range(3)) / k
+                        v.vccl_set_option("ce_pitched", 1)
+                        row[name]["us_plain_copies"] = tp * 1e6
+                        row[name]["receive_buffers"] = ("slices of one allocation" if slab5 is not None
+                                                        else "separate allocations")
                     if "corun" in legs:
                         row[name]["corun"] = co.beside(fn, moved, t,
                                                        reps=args.ce_pairs // 2 if name == "ce" else max(8, args.pairs // 2))
                 for r, s in ((3, 60), (63, 1)):     # block r of send[s] is block s of recv[r]
-                    assert torch.equal(r5[r][s * c5:(s + 1) * c5], s5[s][r * c5:(r + 1) * c5])
+                    for dst in (r5, slab5 or r5):
+                        assert torch.equal(dst[r][s * c5:(s + 1) * c5], s5[s][r * c5:(r + 1) * c5])
                 one = np.zeros((P5, P5), dtype=np.uint64)
                 one[0, :] = c5
                 displs = np.tile(np.arange(P5, dtype=np.uint64) * np.uint64(c5), (P5, 1))

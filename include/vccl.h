@@ -132,12 +132,21 @@ const char *vccl_last_error(void);
  *       VCCL_ERR_HIP, and vccl_finalize returns VCCL_ERR_HIP if any went unreported),
  *       "ce_refused" (read-only: pieces that no engine took and that went through the HIP
  *       copy instead, before the operation's stream was released),
- *       "ce_test_refuse" (test hook, 0..65535: bit i makes the proxy treat engine i as
- *       refusing every copy),
+ *       "ce_test_refuse" (test hook, 0..131071: bit i < 16 makes the proxy treat engine i as
+ *       refusing every copy, bit 16 makes it treat every pitched copy as refused - its rows
+ *       then go as plain copies),
  *       "ce_proxy_poll" (0, default: while operations are in flight the sender proxy polls
  *       around the time each is expected to complete - what operations of the same shape took
  *       before, a model of the engines for a shape not yet seen - and sleeps in between;
  *       1: it polls without pause, as the proxy of Section 3.1 does, which keeps one host core busy),
+ *       "ce_pitched" (vccl_alltoall on the sdma back end when the rank buffers of one side are
+ *       16-byte aligned slices of one allocation at a constant stride and the block size is a
+ *       multiple of 16: the P blocks of a rank are then ONE pitched engine copy, P copies per
+ *       exchange in place of P * P; the engines need microseconds per copy whatever its size,
+ *       and the runtime runs pitched copies one after another on one engine.  1, default: take
+ *       pitched copies where they are expected to finish first - many ranks, small blocks;
+ *       0: never; 2: wherever the layout allows),
+ *       "ce_pitched_copies" (read-only: pitched copies issued since vccl_init),
  *       "ce_max_engines" (0 = all; else use only that many engines),
  *       "p2p_close_wait_ms" (0..3600000, default 10000: see vccl_p2p_close),
  *       "check" (0/1 overlap validation),

@@ -158,6 +158,59 @@ static int check_overlap(const std::vector<Piece> &pieces) {
     return VCCL_OK;
 }
 
+// An engine that refused a copy of an earlier, already returned operation cannot fail that
+// call any more: the first copy-engine call after it does, once.
+static int report_earlier_ce_failure(Context &c) {
+    const uint64_t errs = proxy_sdma_errors(c.proxy);
+    if (errs > c.ce_errors_reported.exchange(errs))
+        return fail(VCCL_ERR_HIP, "an earlier copy-engine operation could not submit all of its copies "
+                                  "(%llu such operations so far): its receive buffers are incomplete",
+                    (unsigned long long)errs);
+    return VCCL_OK;
+}
+
+// Equal-block AlltoAll on the copy engines when the buffers of one side lie at a constant
+// stride (one allocation cut into P rank buffers): the P blocks that a rank sends - or
+// receives - are then P rows at a constant pitch on both sides, i.e. ONE pitched copy, P of
+// them for the exchange in place of P * P plain ones.  Every copy costs the engines several
+// microseconds whatever its size, so for small blocks and many ranks this is what bounds
+// the exchange.  The runtime runs pitched copies one after another on one engine, so they
+// are used only where that is still the shorter way (proxy_pitched_pays), or always under
+// option ce_pitched = 2.  Fills `rects` and returns true if the call takes this form.
+static bool pitched_alltoall(void *const *sendbuf, void *const *recvbuf, uint64_t c, int P, const Options &opt,
+                             std::vector<CeRect> &rects) {
+    if (opt.ce_kind != VCCL_CE_SDMA || opt.ce_pitched == 0 || (c & 15u) || c > 0xffffffffull) return false;
+    if (opt.ce_pitched == 1 && !proxy_pitched_pays(P, c)) return false;
+    auto stride_of = [&](void *const *buf, uint64_t *stride) {
+        const uintptr_t b0 = reinterpret_cast<uintptr_t>(buf[0]), b1 = reinterpret_cast<uintptr_t>(buf[1]);
+        if (!b0 || b1 <= b0 || ((b0 | b1) & 15u)) return false;
+        const uint64_t d = b1 - b0;
+        if (d < (uint64_t)P * c) return false;
+        for (int r = 2; r < P; ++r)
+            if (reinterpret_cast<uintptr_t>(buf[r]) != b0 + (uint64_t)r * d) return false;
+        *stride = d;
+        return true;
+    };
+    for (int r = 0; r < P; ++r)
+        if (!sendbuf[r] || !recvbuf[r] || ((reinterpret_cast<uintptr_t>(sendbuf[r]) | reinterpret_cast<uintptr_t>(recvbuf[r])) & 15u))
+            return false;
+    uint64_t d = 0;
+    rects.clear();
+    if (stride_of(recvbuf, &d)) {
+        // rank s: block r of send[s] -> block s of recv[r] = recv[0] + r * d + s * c
+        for (int s = 0; s < P; ++s)
+            rects.push_back(CeRect{sendbuf[s], (uint8_t *)recvbuf[0] + (uint64_t)s * c, c, (uint64_t)P, c, d});
+        return true;
+    }
+    if (stride_of(sendbuf, &d)) {
+        // rank r: block r of send[s] = send[0] + s * d + r * c -> block s of recv[r]
+        for (int r = 0; r < P; ++r)
+            rects.push_back(CeRect{(const uint8_t *)sendbuf[0] + (uint64_t)r * c, recvbuf[r], c, (uint64_t)P, d, c});
+        return true;
+    }
+    return false;
+}
+
 static int run_pieces(Context &c, std::vector<Piece> &pieces, vccl_mode mode, hipStream_t stream,
                       const std::vector<std::pair<int, void *>> *receivers) {
     const Options opt = options_of(c);
@@ -182,13 +235,8 @@ static int run_pieces(Context &c, std::vector<Piece> &pieces, vccl_mode mode, hi
         for (const Piece &pc : pieces)
             if (pc.bytes) copies.push_back(CeCopy{pc.src, pc.dst, pc.bytes, pc.receiver});
         if (copies.empty()) return VCCL_OK;
-        // An engine that refused a copy of an earlier, already returned operation cannot
-        // fail that call any more: the first copy-engine call after it does, once.
-        const uint64_t errs = proxy_sdma_errors(c.proxy);
-        if (errs > c.ce_errors_reported.exchange(errs))
-            return fail(VCCL_ERR_HIP, "an earlier copy-engine operation could not submit all of its copies "
-                                      "(%llu such operations so far): its receive buffers are incomplete",
-                        (unsigned long long)errs);
+        int rv = report_earlier_ce_failure(c);
+        if (rv) return rv;
         return proxy_submit(c.proxy, std::move(copies), opt, stream, receivers);
     }
     return fail(VCCL_ERR_ARG, "unknown mode %d", (int)mode);
@@ -361,7 +409,8 @@ int vccl_set_option(const char *key, const char *value) {
         else return fail(VCCL_ERR_ARG, "ce_kind must be 'sdma', 'hip_nocu' or 'hip_default', got '%s'", value);
         return VCCL_OK;
     }
-    if (k == "ce_engines" || k == "ce_errors" || k == "ce_engine_bytes" || k == "ce_wait_on_cp" || k == "ce_refused")
+    if (k == "ce_engines" || k == "ce_errors" || k == "ce_engine_bytes" || k == "ce_wait_on_cp" || k == "ce_refused" ||
+        k == "ce_pitched_copies")
         return fail(VCCL_ERR_ARG, "%s is read-only", key);
     if (k == "ce_sync") {
         if (!strcmp(value, "memops")) o.ce_sync = VCCL_SYNC_MEMOPS;
@@ -415,8 +464,11 @@ int vccl_set_option(const char *key, const char *value) {
         if (!in(0, 1)) return fail(VCCL_ERR_ARG, "ce_proxy_poll must be 0 or 1");
         o.ce_proxy_poll = (int)x;
         proxy_set_always_poll(c->proxy, x != 0);
+    } else if (k == "ce_pitched") {
+        if (!in(0, 2)) return fail(VCCL_ERR_ARG, "ce_pitched must be 0, 1 or 2");
+        o.ce_pitched = (int)x;
     } else if (k == "ce_test_refuse") {
-        if (!in(0, 0xffff)) return fail(VCCL_ERR_ARG, "ce_test_refuse must be 0..65535");
+        if (!in(0, 0x1ffff)) return fail(VCCL_ERR_ARG, "ce_test_refuse must be 0..131071");
         o.ce_test_refuse = (int)x;
     } else if (k == "check") {
         if (!in(0, 1)) return fail(VCCL_ERR_ARG, "check must be 0 or 1");
@@ -470,6 +522,8 @@ int vccl_get_option(const char *key, char *out, int cap) {
     else if (k == "ce_wait_on_cp") v = c->wait_on_cp ? 1 : 0;
     else if (k == "ce_refused") v = (unsigned long long)proxy_refused_pieces(c->proxy);
     else if (k == "ce_test_refuse") v = o.ce_test_refuse;
+    else if (k == "ce_pitched") v = o.ce_pitched;
+    else if (k == "ce_pitched_copies") v = (unsigned long long)proxy_pitched_copies(c->proxy);
     else if (k == "ce_proxy_poll") v = o.ce_proxy_poll;
     else if (k == "cu_unroll") v = o.cu_unroll;
     else if (k == "cu_wg_per_cu") v = o.cu_wg_per_cu;
@@ -515,6 +569,24 @@ int vccl_alltoall(void *const *sendbuf, void *const *recvbuf, uint64_t bytes_per
         const Options opt = options_of(*c);
         if (uniform_alltoall_applies(sendbuf, recvbuf, bytes_per_peer, P, opt))
             return launch_uniform_alltoall(sendbuf, recvbuf, bytes_per_peer, P, opt, (hipStream_t)stream);
+    }
+    if (mode == VCCL_MODE_CE && P >= 2 && bytes_per_peer) {
+        std::vector<CeRect> rects;
+        const Options opt = options_of(*c);
+        if (pitched_alltoall(sendbuf, recvbuf, bytes_per_peer, P, opt, rects)) {
+            if (opt.check) {   // the same validation as on the general path
+                std::vector<Piece> pieces;
+                for (int a = 0; a < P; ++a)
+                    for (int b = 0; b < P; ++b)
+                        pieces.push_back(Piece{(const uint8_t *)sendbuf[a] + (uint64_t)b * bytes_per_peer,
+                                               (uint8_t *)recvbuf[b] + (uint64_t)a * bytes_per_peer, bytes_per_peer, -1});
+                rv = check_overlap(pieces);
+                if (rv) return rv;
+            }
+            rv = report_earlier_ce_failure(*c);
+            if (rv) return rv;
+            return proxy_submit(c->proxy, std::vector<CeCopy>(), opt, (hipStream_t)stream, nullptr, &rects);
+        }
     }
     std::vector<uint64_t> cnt((size_t)P * P, bytes_per_peer), dsp((size_t)P * P);
     for (int a = 0; a < P; ++a)

@@ -54,7 +54,9 @@ struct Options {
     int ce_kind = 0;   // VCCL_CE_*
     int ce_max_engines = 0;
     int ce_proxy_poll = 0;   // 1: the sender proxy polls without pause while anything is in flight
-    int ce_test_refuse = 0;   // test hook: bit i set = engine i refuses every copy
+    int ce_test_refuse = 0;   // test hook: bit i set = engine i refuses every copy; bit 16: every pitched copy is refused
+    int ce_pitched = 1;       // equal-block AlltoAll over buffers at a constant stride: 0 plain copies, 1 pitched copies
+                              // where they are expected to pay, 2 pitched copies wherever the layout allows
     int ce_sync = 0;   // VCCL_SYNC_*
     int check = 0;
     uint64_t fifo_chunk_bytes = 512u << 10;
@@ -221,6 +223,14 @@ struct CeCopy {
     uint64_t bytes;
     int receiver;  // >= 0: SendRecv copy whose destination is read from that rank's handshake record
 };
+// `rows` blocks of `width` bytes, row i at src + i * src_pitch going to dst + i * dst_pitch:
+// one pitched engine copy (what the blocks of one rank are in an equal-block AlltoAll whose
+// buffers on the other side lie at a constant stride).
+struct CeRect {
+    const void *src;
+    void *dst;
+    uint64_t width, rows, src_pitch, dst_pitch;
+};
 // The receiver-owned handshake record of a connection between two PROCESSES (Section
 // 3.2: P2pRegInfo in host shared memory, mapped into the sender at connect).  The
 // paper's 1-bit flags are sequence numbers that only grow: transfer n of the connection
@@ -259,7 +269,10 @@ void proxy_destroy(Proxy *p);
 // `receivers` (may be null) lists (receiving rank, application buffer) pairs that
 // go through the per-connection handshake record.
 int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hipStream_t stream,
-                 const std::vector<std::pair<int, void *>> *receivers);
+                 const std::vector<std::pair<int, void *>> *receivers, std::vector<CeRect> *rects = nullptr);
+// Whether P pitched copies of P blocks of `block_bytes` are expected to finish before the
+// P * P plain copies they replace (sdma back end).
+bool proxy_pitched_pays(int P, uint64_t block_bytes);
 int proxy_reginfo(Proxy *p, int receiver, uint64_t *ready, uint64_t *started, uint64_t *done,
                   void **addr);
 int proxy_drain(Proxy *p);
@@ -269,6 +282,7 @@ bool proxy_sdma_available(Proxy *p, const char **why);
 int proxy_engine_count(Proxy *p);
 uint64_t proxy_sdma_errors(Proxy *p);
 uint64_t proxy_refused_pieces(Proxy *p);
+uint64_t proxy_pitched_copies(Proxy *p);
 void proxy_set_always_poll(Proxy *p, bool on);
 vccl_monitor *proxy_monitor(Proxy *p, int primitive);
 void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uint64_t *issue_ns);

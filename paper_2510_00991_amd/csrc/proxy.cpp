@@ -85,6 +85,7 @@ struct RecvPost {   // what the receiver proxy publishes for one transfer on one
 
 struct Op {
     std::vector<CeCopy> copies;
+    std::vector<CeRect> rects;                    // pitched copies (sdma back end only)
     std::vector<std::pair<int, uint64_t>> conns;  // (receiver rank, sequence number)
     int kind = VCCL_CE_SDMA;
     // event back end
@@ -137,7 +138,7 @@ public:
     bool stop = false;
     size_t in_flight = 0;        // queued + waiting + pending
     RegInfo reg[VCCL_MAX_RANKS];
-    std::atomic<uint64_t> n_ops{0}, n_copies{0}, n_bytes{0}, issue_ns{0}, sdma_errors{0}, n_refused{0};
+    std::atomic<uint64_t> n_ops{0}, n_copies{0}, n_bytes{0}, issue_ns{0}, sdma_errors{0}, n_refused{0}, n_pitched{0};
     std::atomic<uint64_t> engine_bytes[kMaxEngines] = {};   // bytes handed to each engine so far
     // sdma back end
     bool sdma_ok = false;
@@ -163,10 +164,14 @@ public:
     // each through its own pieces at kEngineRate with kCopyCost of fixed time per piece, and
     // all together no faster than kAllRate and one piece per kAllCopyCost.  The constants
     // lean towards too short an estimate: that costs some polling, too long a one costs latency.
-    static constexpr double kEngineRate = 0.09;    // bytes per nanosecond, one engine alone
-    static constexpr double kAllRate = 1.45;       // bytes per nanosecond, all engines together
+    static constexpr double kEngineRate = 60.0;    // bytes copied per nanosecond (= GB/s), one engine alone
+    static constexpr double kAllRate = 760.0;      // bytes copied per nanosecond, all engines together
     static constexpr double kCopyCost = 6500.0;    // nanoseconds per piece on its engine
     static constexpr double kAllCopyCost = 980.0;  // nanoseconds per piece over all engines (about a million copies a second)
+    // Pitched copies have no engine argument; the runtime runs them one after another on one
+    // engine, each in about kRectCost plus its bytes at kRectRate.
+    static constexpr double kRectCost = 11000.0;   // nanoseconds per pitched copy
+    static constexpr double kRectRate = 60.0;      // bytes per nanosecond inside a pitched copy
     std::unordered_map<uint64_t, uint64_t> history;   // shape -> nanoseconds (proxy thread only)
     static uint64_t shape_key(uint64_t bytes, size_t pieces, int engines) {
         int top = 63 - __builtin_clzll(bytes | 1);
@@ -334,6 +339,7 @@ Op *Proxy::get_op() {  // mu held
 void Proxy::put_ref(Op *op) {  // mu held
     if (--op->refs == 0) {
         op->copies.clear();
+        op->rects.clear();
         op->conns.clear();
         op->state = 0;
         op->sdma_failed = false;
@@ -489,8 +495,31 @@ bool Proxy::issue_sdma(Op *op) {
     const int ne = op->max_engines > 0 && op->max_engines < nengines ? op->max_engines : nengines;
     std::vector<CeCopy> work = expand(op, (size_t)ne);
     mark_started(op);
-    hsa_signal_store_relaxed(op->left, (hsa_signal_value_t)work.size());
+    hsa_signal_store_relaxed(op->left, (hsa_signal_value_t)(work.size() + op->rects.size()));
     uint64_t bytes = 0;
+    // Pitched copies first.  One that the runtime does not take is replaced by plain copies
+    // of its rows, which join the pieces below.
+    size_t pitched = 0;
+    double pitched_ns = 0;
+    for (const CeRect &rc : op->rects) {
+        hsa_pitched_ptr_t src{const_cast<void *>(rc.src), (size_t)rc.src_pitch, (size_t)(rc.src_pitch * rc.rows)};
+        hsa_pitched_ptr_t dst{rc.dst, (size_t)rc.dst_pitch, (size_t)(rc.dst_pitch * rc.rows)};
+        const hsa_dim3_t zero{0, 0, 0};
+        const hsa_dim3_t range{(uint32_t)rc.width, (uint32_t)rc.rows, 1};
+        const bool taken = !(op->refuse_mask & 0x10000u) &&
+                           hsa_amd_memory_async_copy_rect(&dst, &zero, &src, &zero, &range, agent, hsaDeviceToDevice, 0,
+                                                          nullptr, op->left) == HSA_STATUS_SUCCESS;
+        if (taken) {
+            ++pitched;
+            bytes += rc.width * rc.rows;
+            pitched_ns += kRectCost + (double)(rc.width * rc.rows) / kRectRate;
+            continue;
+        }
+        hsa_signal_add_relaxed(op->left, (hsa_signal_value_t)rc.rows - 1);
+        for (uint64_t i = 0; i < rc.rows; ++i)
+            work.push_back(CeCopy{(const uint8_t *)rc.src + i * rc.src_pitch, (uint8_t *)rc.dst + i * rc.dst_pitch,
+                                  rc.width, -1});
+    }
     // Each piece goes to the engine with the fewest bytes so far (ties: rotate, so that
     // equal pieces still spread round-robin and small operations do not all start on
     // engine 0).  An engine that refuses a piece is passed over: the piece is offered to
@@ -534,7 +563,7 @@ bool Proxy::issue_sdma(Op *op) {
     op->bytes = bytes;
     op->t_issue_ns = now_ns();
     op->t_seen_busy_ns = op->t_issue_ns;
-    op->shape = shape_key(bytes, work.size(), ne);
+    op->shape = shape_key(bytes, work.size() + (pitched << 32), ne);
     double est;
     auto seen = history.find(op->shape);
     if (seen != history.end()) {
@@ -546,11 +575,13 @@ bool Proxy::issue_sdma(Op *op) {
             const double e = (double)load[i] / kEngineRate + (double)pieces_on[i] * kCopyCost;
             if (e > est) est = e;
         }
+        if (pitched_ns > est) est = pitched_ns;
     }
     op->est_ns = (uint64_t)est;
     const auto t1 = std::chrono::steady_clock::now();
     n_ops.fetch_add(1, std::memory_order_relaxed);
-    n_copies.fetch_add(work.size(), std::memory_order_relaxed);
+    n_copies.fetch_add(work.size() + pitched, std::memory_order_relaxed);
+    n_pitched.fetch_add(pitched, std::memory_order_relaxed);
     n_bytes.fetch_add(bytes, std::memory_order_relaxed);
     issue_ns.fetch_add((uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(t1 - t0).count(),
                        std::memory_order_relaxed);
@@ -857,7 +888,8 @@ static int submit_sdma(Proxy *p, Op *op, hipStream_t stream,
 static void publish_receivers(Proxy *p, Op *op, const std::vector<std::pair<int, void *>> &receivers);
 
 int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hipStream_t stream,
-                 const std::vector<std::pair<int, void *>> *receivers) {
+                 const std::vector<std::pair<int, void *>> *receivers, std::vector<CeRect> *rects) {
+    if (rects && opt.ce_kind != VCCL_CE_SDMA) return fail(VCCL_ERR_ARG, "pitched copies need the 'sdma' back end");
     if (opt.ce_kind == VCCL_CE_SDMA && !p->sdma_ok)
         return fail(VCCL_ERR_UNSUPPORTED, "copy-engine back end 'sdma' is not available: %s",
                     p->sdma_why.c_str());
@@ -872,6 +904,7 @@ int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hip
         op->state = 0;
     }
     op->copies = std::move(copies);
+    if (rects) op->rects = std::move(*rects);
     op->want_streams = opt.ce_streams;
     op->kind = opt.ce_kind;
     op->max_engines = opt.ce_max_engines;
@@ -1044,6 +1077,17 @@ void proxy_stats(Proxy *p, uint64_t *ops, uint64_t *copies, uint64_t *bytes, uin
 
 uint64_t proxy_sdma_errors(Proxy *p) { return p->sdma_errors.load(); }
 uint64_t proxy_refused_pieces(Proxy *p) { return p->n_refused.load(); }
+uint64_t proxy_pitched_copies(Proxy *p) { return p->n_pitched.load(); }
+
+// P pitched copies run one after another on one engine; P * P plain copies spread over all
+// engines but are bound by the engines' copy rate.
+bool proxy_pitched_pays(int P, uint64_t block_bytes) {
+    const double pitched = (double)P * (Proxy::kRectCost + (double)P * (double)block_bytes / Proxy::kRectRate);
+    double plain = (double)P * (double)P * Proxy::kAllCopyCost;
+    const double by_rate = (double)P * (double)P * (double)block_bytes / Proxy::kAllRate;
+    if (by_rate > plain) plain = by_rate;
+    return pitched < plain;
+}
 void proxy_set_always_poll(Proxy *p, bool on) { p->always_poll.store(on, std::memory_order_relaxed); }
 
 // Processor time the two proxy threads have used so far (what the paper's CPU

@@ -246,14 +246,21 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
         for s in range(P):     # seeded payload: one MiB per rank, repeated through the buffer (the power a
             n = min(P * c, 1 << 20)   # transfer draws, and with it what it costs its neighbours, depends on the values)
             send[s].view(-1, n).copy_(torch.from_numpy(wl.payload_bytes(wl.config_seed(5), s, n)).cuda())
-        bufs[c] = (send, recv)
+        # For small blocks the copy-engine path is also given receive buffers that are slices of
+        # one allocation (a constant stride between the ranks), the layout that lets it take one
+        # pitched copy per rank in place of P plain ones.
+        slab = ([b[:P * c] for b in torch.empty((P, P * c + 4096), dtype=torch.uint8, device="cuda").unbind(0)]
+                if c <= 32 << 10 else None)
+        bufs[c] = (send, recv, slab)
     for c in sizes:
-        send, recv = bufs[c]
+        send, recv, slab = bufs[c]
         send_p, recv_p = v.pointer_array(send), v.pointer_array(recv)   # marshalled once, not per call
+        slab_p = v.pointer_array(slab) if slab is not None else recv_p
         moved = 2.0 * P * P * c
         row = {"bytes_per_peer": c, "total_sent_MiB": P * P * c / (1 << 20)}
         for name, mode in (("cu", v.MODE_CU), ("ce", v.MODE_CE)):
-            fn = lambda s=st, m=mode: v.vccl_alltoall(send_p, recv_p, c, P, m, s)
+            to = slab_p if name == "ce" else recv_p
+            fn = lambda s=st, m=mode, to=to: v.vccl_alltoall(send_p, to, c, P, m, s)
             k = 10 if name == "cu" else 3
             # keep the device busy for ~50 ms first: the memory clocks of an idle
             # device ramp up slowly under copy-engine traffic alone
@@ -263,8 +270,14 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
                 torch.cuda.synchronize()
             t = statistics.median(time_region(torch, fn, k, 1)[0] for _ in range(3)) / k
             row[name] = {"us": t * 1e6, "GBps": moved / t / 1e9}
+            if name == "ce":     # the same call with plain copies only (one per block)
+                v.vccl_set_option("ce_pitched", 0)
+                tp = statistics.median(time_region(torch, fn, k, 1)[0] for _ in range(3)) / k
+                v.vccl_set_option("ce_pitched", 1)
+                row[name]["us_plain_copies"] = tp * 1e6
+                row[name]["receive_buffers"] = "slices of one allocation" if slab is not None else "separate allocations"
             if co is not None:
-                row[name].update(co.beside(lambda s, m=mode: v.vccl_alltoall(send_p, recv_p, c, P, m, s),
+                row[name].update(co.beside(lambda s, m=mode, to=to: v.vccl_alltoall(send_p, to, c, P, m, s),
                                            moved, t, reps=8))
         # What one device of P does in this exchange: its own P outgoing blocks (the other
         # ranks' blocks are the work of their devices' engines or compute units).
@@ -277,7 +290,7 @@ def sweep_p64(torch, P=64, sizes=None, with_corun=True, max_bytes_per_side=16 <<
             row[name]["one_rank_share_us"] = t * 1e6
             row[name]["one_rank_share_GBps"] = 2.0 * P * c / t / 1e9
         rows.append(row)
-    del send, recv, bufs
+    del send, recv, slab, bufs
     torch.cuda.empty_cache()
     return {"workload": f"AlltoAll sweep, P={P}, per-peer 4 KiB..4 MiB", "rows": rows}
 

@@ -470,6 +470,75 @@ def test_small_message_alltoall_on_the_copy_engines(vccl):
     assert int(vccl.vccl_get_option("ce_errors")) == 0
 
 
+@pytest.mark.parametrize("side", ["recv", "send", "both"])
+def test_pitched_copies_for_buffers_at_a_constant_stride(vccl, side):
+    """Equal-block AlltoAll on the copy engines when the rank buffers of one side are slices of
+    one allocation at a constant stride: the P blocks of a rank go as ONE pitched copy (P in
+    place of P * P).  Right bytes for either side (or both) at a constant stride, with gaps
+    between the rank buffers left untouched; the same when every pitched copy is refused and
+    its rows go as plain copies; nothing pitched when switched off or when no side qualifies."""
+    torch = require_gpu()
+    P, c, gap = 24, 4096 + 48, 256
+    send_np = [wl.payload_bytes(6300, s, P * c) for s in range(P)]
+    want = [np.full(P * c, SENTINEL, dtype=np.uint8) for _ in range(P)]
+    oracle.alltoall(send_np, want, c, threads=4)
+    st = stream_handle(torch)
+
+    def buffers(strided, fill):
+        if strided:
+            slab = torch.full((P, P * c + gap), SENTINEL, dtype=torch.uint8, device="cuda")
+            views = [slab[r, :P * c] for r in range(P)]
+        else:
+            slab = None
+            views = [torch.full((P * c + 16 * (r % 3),), SENTINEL, dtype=torch.uint8, device="cuda")[:P * c] for r in range(P)]
+        if fill is not None:
+            for r in range(P):
+                views[r].copy_(torch.from_numpy(fill[r]))
+        return slab, views
+
+    _, send = buffers(side in ("send", "both"), send_np)
+    for mode_opt, refuse, expect_pitched in ((2, 0, P), (2, 0x10000, 0), (0, 0, 0)):
+        slab, recv = buffers(side in ("recv", "both"), None)
+        before = int(vccl.vccl_get_option("ce_pitched_copies"))
+        copies0 = vccl.vccl_proxy_stats()["copies"]
+        _with_options(vccl, {"ce_pitched": mode_opt, "ce_test_refuse": refuse},
+                      lambda: vccl.vccl_alltoall(send, recv, c, P, vccl.MODE_CE, st))
+        torch.cuda.synchronize()
+        what = f"side={side} ce_pitched={mode_opt} refuse={refuse:#x}"
+        for r in range(P):
+            assert_same(to_host(recv[r]), want[r], f"{what} recv[{r}]")
+        if slab is not None:
+            assert bool((slab[:, P * c:] == SENTINEL).all()), what + ": bytes between the rank buffers"
+        assert int(vccl.vccl_get_option("ce_pitched_copies")) - before == expect_pitched, what
+        assert vccl.vccl_proxy_stats()["copies"] - copies0 == (P if expect_pitched else P * P), what
+    assert int(vccl.vccl_get_option("ce_errors")) == 0
+
+
+def test_pitched_copies_are_chosen_where_they_pay(vccl):
+    """With the default setting the library takes pitched copies for many ranks and small
+    blocks (P = 64, 4 KiB: 64 copies in place of 4096) and plain ones for large blocks or few
+    ranks; rank buffers that are not at a constant stride always go as plain copies."""
+    torch = require_gpu()
+    st = stream_handle(torch)
+    for P, c, pitched in ((64, 4096, True), (64, 64 << 10, False), (8, 4096, False)):
+        send_np = [wl.payload_bytes(6400 + P, s, P * c) for s in range(P)]
+        want = [np.full(P * c, SENTINEL, dtype=np.uint8) for _ in range(P)]
+        oracle.alltoall(send_np, want, c, threads=4)
+        send = [to_dev(torch, a) for a in send_np]
+        slab = torch.full((P, P * c), SENTINEL, dtype=torch.uint8, device="cuda")
+        recv = [slab[r] for r in range(P)]
+        before = int(vccl.vccl_get_option("ce_pitched_copies"))
+        vccl.vccl_alltoall(send, recv, c, P, vccl.MODE_CE, st)
+        torch.cuda.synchronize()
+        for r in range(P):
+            assert_same(to_host(recv[r]), want[r], f"P={P} c={c} recv[{r}]")
+        assert int(vccl.vccl_get_option("ce_pitched_copies")) - before == (P if pitched else 0), (P, c)
+    with pytest.raises(vccl.VcclError):
+        vccl.vccl_set_option("ce_pitched", 3)
+    with pytest.raises(vccl.VcclError):
+        vccl.vccl_set_option("ce_pitched_copies", 1)
+
+
 def test_many_copy_engine_operations_in_flight(vccl):
     """Several copy-engine calls queued back to back on two streams before any
     synchronisation: operation slots are recycled and every result is right."""
