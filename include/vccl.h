@@ -58,6 +58,9 @@
  *     vccl_last_error() describes the cause.
  *   - Calls may be made from several host threads; calls on different streams
  *     may overlap on the device.
+ *   - VCCL_MODE_CE calls (and vccl_p2p_send / vccl_p2p_recv) on a stream that is capturing
+ *     a graph return VCCL_ERR_UNSUPPORTED: a host thread carries each such call out once, a
+ *     replayed graph would not reach it.
  */
 #ifndef VCCL_H
 #define VCCL_H

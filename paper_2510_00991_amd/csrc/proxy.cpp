@@ -887,8 +887,20 @@ static int submit_sdma(Proxy *p, Op *op, hipStream_t stream,
                        const std::vector<std::pair<int, void *>> *receivers);
 static void publish_receivers(Proxy *p, Op *op, const std::vector<std::pair<int, void *>> &receivers);
 
+// A copy-engine call is carried out once, by a host thread, when the stream reaches it: a
+// graph that recorded the call's stream operations would replay them without the copies.
+static int refuse_capture(hipStream_t stream) {
+    if (!stream) return VCCL_OK;   // the null stream cannot capture
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &st) == hipSuccess && st != hipStreamCaptureStatusNone)
+        return fail(VCCL_ERR_UNSUPPORTED, "copy-engine calls cannot be recorded into a graph (a host thread carries "
+                                          "each call out once); use VCCL_MODE_CU on a capturing stream");
+    return VCCL_OK;
+}
+
 int proxy_submit(Proxy *p, std::vector<CeCopy> &&copies, const Options &opt, hipStream_t stream,
                  const std::vector<std::pair<int, void *>> *receivers, std::vector<CeRect> *rects) {
+    if (int rv = refuse_capture(stream)) return rv;
     if (rects && opt.ce_kind != VCCL_CE_SDMA) return fail(VCCL_ERR_ARG, "pitched copies need the 'sdma' back end");
     if (opt.ce_kind == VCCL_CE_SDMA && !p->sdma_ok)
         return fail(VCCL_ERR_UNSUPPORTED, "copy-engine back end 'sdma' is not available: %s",
@@ -1040,6 +1052,7 @@ static int submit_sdma(Proxy *p, Op *op, hipStream_t stream,
 
 int proxy_submit_remote(Proxy *p, int role, P2pShared *sh, uint8_t *mapped_buffer, uint64_t seq, const void *src,
                         uint64_t offset, uint64_t bytes, const Options &opt, hipStream_t stream) {
+    if (int rv = refuse_capture(stream)) return rv;
     if (opt.ce_kind != VCCL_CE_SDMA || !p->sdma_ok)
         return fail(VCCL_ERR_UNSUPPORTED, "cross-process SendRecv needs the 'sdma' copy-engine back end%s%s",
                     p->sdma_ok ? "" : ": ", p->sdma_ok ? "" : p->sdma_why.c_str());

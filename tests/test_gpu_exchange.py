@@ -700,6 +700,40 @@ def test_cu_path_replays_from_a_hip_graph(vccl, P, c):
             assert_same(to_host(recv[r]), want[r], f"replay {rep} recv[{r}]")
 
 
+def test_copy_engine_calls_refuse_a_capturing_stream(vccl):
+    """A copy-engine call is carried out once by a host thread, so it cannot live in a graph:
+    on a capturing stream it fails before anything is recorded, the capture itself stays
+    valid, and the compute-unit call recorded beside it replays."""
+    torch = require_gpu()
+    P, c = 4, 4096
+    send_np = [wl.payload_bytes(880, s, P * c) for s in range(P)]
+    send = [to_dev(torch, a) for a in send_np]
+    recv = [torch.full((P * c,), SENTINEL, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    vccl.vccl_alltoall(send, recv, c, P, vccl.MODE_CU, stream_handle(torch))      # eager warm-up
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        with pytest.raises(vccl.VcclError) as e:
+            vccl.vccl_alltoall(send, recv, c, P, vccl.MODE_CE, stream_handle(torch))
+        assert e.value.code == -6
+        with pytest.raises(vccl.VcclError):
+            vccl.vccl_sendrecv(send, [c] * P, [1, 0, 3, 2], recv, [c] * P, [1, 0, 3, 2], P, vccl.MODE_CE,
+                               stream_handle(torch))
+        vccl.vccl_alltoall(send, recv, c, P, vccl.MODE_CU, stream_handle(torch))
+    for r in range(P):
+        recv[r].fill_(SENTINEL)
+    torch.cuda.synchronize()
+    g.replay()
+    torch.cuda.synchronize()
+    want = [np.full(P * c, SENTINEL, dtype=np.uint8) for _ in range(P)]
+    oracle.alltoall(send_np, want, c, threads=2)
+    for r in range(P):
+        assert_same(to_host(recv[r]), want[r], f"replayed recv[{r}]")
+    vccl.vccl_alltoall(send, recv, c, P, vccl.MODE_CE, stream_handle(torch))      # outside a capture it works as ever
+    torch.cuda.synchronize()
+    assert int(vccl.vccl_get_option("ce_errors")) == 0
+
+
 @pytest.mark.parametrize("kind,sync", [("sdma", "memops"), ("sdma", "event"), ("sdma", "host"), ("hip_nocu", "memops")])
 def test_kernels_after_a_copy_engine_exchange_read_fresh_data(vccl, kind, sync):
     """Cache coherence of the copy-engine path: the receive buffers are small enough to
