@@ -180,6 +180,7 @@ static int report_earlier_ce_failure(Context &c) {
 static bool pitched_alltoall(void *const *sendbuf, void *const *recvbuf, uint64_t c, int P, const Options &opt,
                              std::vector<CeRect> &rects) {
     if (opt.ce_kind != VCCL_CE_SDMA || opt.ce_pitched == 0 || (c & 15u) || c > 0xffffffffull) return false;
+    if (opt.ce_max_engines) return false;   // the caller limits the engines; a pitched copy cannot be told which to use
     if (opt.ce_pitched == 1 && !proxy_pitched_pays(P, c)) return false;
     auto stride_of = [&](void *const *buf, uint64_t *stride) {
         const uintptr_t b0 = reinterpret_cast<uintptr_t>(buf[0]), b1 = reinterpret_cast<uintptr_t>(buf[1]);
