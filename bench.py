@@ -291,12 +291,13 @@ def main():
                                ("copy_engine", v.MODE_CE)):
                 fn = lambda sh=st, m=mode: v.vccl_sendrecv(send_p, [n] * P, to, recv_p, [n] * P, frm, P, m, sh)
                 # median of three trains: the copy engines' rate wanders from train to train
-                runs = sorted((time_region(torch, fn, 5, 2) for _ in range(3)), key=lambda t: t[0])
+                k = 20   # calls per train: the one synchronisation at its end weighs 1/20 per call
+                runs = sorted((time_region(torch, fn, k, 2) for _ in range(3)), key=lambda t: t[0])
                 w, dev = runs[1]
-                sr[name] = {"GBps": 2.0 * P * n / (w / 5) / 1e9, "ms": w / 5 * 1e3,
+                sr[name] = {"GBps": 2.0 * P * n / (w / k) / 1e9, "ms": w / k * 1e3, "calls_per_train": k,
                             # device time of the train / calls: for the kernel modes one call is one launch
-                            "device_us_per_call": dev / 5 * 1e6,
-                            "GBps_device": 2.0 * P * n / (dev / 5) / 1e9}
+                            "device_us_per_call": dev / k * 1e6,
+                            "GBps_device": 2.0 * P * n / (dev / k) / 1e9}
                 if co is not None and "corun" in legs:
                     sr[name]["corun"] = co.beside(fn, 2.0 * P * n, w / 5,
                                                   reps=args.ce_pairs if mode == v.MODE_CE else max(8, args.pairs // 2))
