@@ -514,6 +514,29 @@ def test_pitched_copies_for_buffers_at_a_constant_stride(vccl, side):
     assert int(vccl.vccl_get_option("ce_errors")) == 0
 
 
+@pytest.mark.parametrize("P,c", [(2, 16), (3, 1 << 20), (5, 65536 + 16), (64, 48)])
+def test_pitched_copies_at_the_edges_of_their_shapes(vccl, P, c):
+    """Forced pitched copies for the smallest exchange, for wide rows, for a width that is no
+    power of two and for many ranks with tiny blocks: whatever the runtime makes of a shape -
+    it may take the pitched copy or refuse it, in which case the rows go as plain copies -
+    the bytes are right and nothing is left in error."""
+    torch = require_gpu()
+    send_np = [wl.payload_bytes(6500 + P, s, P * c) for s in range(P)]
+    want = [np.full(P * c, SENTINEL, dtype=np.uint8) for _ in range(P)]
+    oracle.alltoall(send_np, want, c, threads=2)
+    send = [to_dev(torch, a) for a in send_np]
+    slab = torch.full((P, P * c + 64), SENTINEL, dtype=torch.uint8, device="cuda")
+    recv = [slab[r, :P * c] for r in range(P)]
+    before = int(vccl.vccl_get_option("ce_pitched_copies"))
+    _with_options(vccl, {"ce_pitched": 2}, lambda: vccl.vccl_alltoall(send, recv, c, P, vccl.MODE_CE, stream_handle(torch)))
+    torch.cuda.synchronize()
+    for r in range(P):
+        assert_same(to_host(recv[r]), want[r], f"P={P} c={c} recv[{r}]")
+    assert bool((slab[:, P * c:] == SENTINEL).all())
+    assert int(vccl.vccl_get_option("ce_pitched_copies")) - before in (0, P)
+    assert int(vccl.vccl_get_option("ce_errors")) == 0
+
+
 def test_pitched_copies_are_chosen_where_they_pay(vccl):
     """With the default setting the library takes pitched copies for many ranks and small
     blocks (P = 64, 4 KiB: 64 copies in place of 4096) and plain ones for large blocks or few
