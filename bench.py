@@ -266,6 +266,12 @@ def main():
             cor_cap64 = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes,
                                   wcap64 / 3, reps=args.pairs)
             cor_cap64["GBps_alone"] = algo_bytes / (wcap64 / 3) / 1e9
+            # and to 32: about the rate of the copy engines, for a comparison at equal bytes per second
+            v.vccl_set_option("cu_max_wg", 32)
+            wcap32, _ = time_region(torch, a2a_cu, 3, 1)
+            cor_cap32 = co.beside(lambda sh: v.vccl_alltoall(send, recv, c, P, v.MODE_CU, sh), algo_bytes,
+                                  wcap32 / 3, reps=args.ce_pairs)
+            cor_cap32["GBps_alone"] = algo_bytes / (wcap32 / 3) / 1e9
             v.vccl_set_option("cu_max_wg", 0)
             v.vccl_set_option("cu_unroll", 1)
             v.vccl_set_option("cu_threads", 64)
@@ -280,7 +286,8 @@ def main():
                                         "tick count (held up inside compute units), shader_clock_MHz_* = its ticks per "
                                         "real-time tick (the chip lowering its clock)",
                             "cu_path": cor_cu, "cu_path_capped_1wg_per_cu": cor_cap,
-                            "cu_path_capped_64wg": cor_cap64, "copy_engine_path": cor_ce}
+                            "cu_path_capped_64wg": cor_cap64, "cu_path_capped_32wg": cor_cap32,
+                            "copy_engine_path": cor_ce}
         if "sendrecv" in legs:
             # SendRecv ring, 8 stages x 64 MiB: rate and probe slowdown in every mode
             n = 64 << 20
