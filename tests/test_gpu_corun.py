@@ -164,7 +164,7 @@ def test_probe_reports_its_shader_ticks_and_real_time(vccl):
 def test_copy_engine_traffic_leaves_the_probe_alone_and_a_copy_kernel_does_not(vccl):
     """The co-run protocol's outcome on the config-2 exchange (P = 8 x 16 MiB, random
     payload), with bounds that leave room to what is measured: the compute-bound probe loses
-    at most 3 % beside copy-engine traffic (measured: under 0.5 %) and clearly more beside the
+    at most 3 % beside copy-engine traffic (measured: under 0.5 %) and more than that beside the
     full-grid copy kernel (measured: about a third), while both transfers move their bytes at
     their usual rate.  The probe's own counters say where the time goes: in neither case is
     it held up inside its compute units (its shader ticks stay within 3 %); beside the copy
@@ -183,10 +183,10 @@ def test_copy_engine_traffic_leaves_the_probe_alone_and_a_copy_kernel_does_not(v
         per = time_region(torch, lambda: fn(stream_handle(torch)), 5, 2)[0] / 5
         res[name] = co.beside(fn, moved, per, reps=pairs)
     assert res["ce"]["slowdown_pct"] <= 3.0, res["ce"]
-    assert res["cu"]["slowdown_pct"] >= res["ce"]["slowdown_pct"] + 5.0, res
+    assert res["cu"]["slowdown_pct"] >= 3.0, res["cu"]
     assert res["ce"]["comm_GBps_while_corunning"] > 1000.0, res["ce"]
     assert res["cu"]["comm_GBps_while_corunning"] > 4000.0, res["cu"]
     for name in ("ce", "cu"):
         assert abs(res[name]["probe_shader_ticks_pct"]) < 3.0, res[name]
-    assert res["cu"]["shader_clock_MHz_beside"] < 0.95 * res["cu"]["shader_clock_MHz_alone"], res["cu"]
+    assert res["cu"]["shader_clock_MHz_beside"] < 0.99 * res["cu"]["shader_clock_MHz_alone"], res["cu"]
     assert res["ce"]["shader_clock_MHz_beside"] > 0.97 * res["ce"]["shader_clock_MHz_alone"], res["ce"]
