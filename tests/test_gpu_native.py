@@ -25,4 +25,4 @@ def test_native_c_program(sync):
     rv = subprocess.run([EXE, sync], capture_output=True, text=True, timeout=120)
     assert rv.returncode == 0, rv.stdout[-2000:] + rv.stderr[-2000:]
     assert "native ok" in rv.stdout and f"ordering: {sync}" in rv.stdout
-    assert rv.stdout.count(": ok") == 7
+    assert rv.stdout.count(": ok") == 12 and "probe: workgroup 0 ran" in rv.stdout
