@@ -288,6 +288,26 @@ def main():
                             "cu_path": cor_cu, "cu_path_capped_1wg_per_cu": cor_cap,
                             "cu_path_capped_64wg": cor_cap64, "cu_path_capped_32wg": cor_cap32,
                             "copy_engine_path": cor_ce}
+        if "ce" in legs:
+            # the small configuration (P = 4 x 64 KiB, 2 MiB of traffic): too small for a rate, so the time from
+            # the call to the completion of the stream on an idle device, both paths, median of 30 single calls
+            P1, c1 = 4, 64 << 10
+            s1 = [torch.from_numpy(wl.payload_bytes(wl.config_seed(1), s, P1 * c1)).cuda() for s in range(P1)]
+            r1 = [torch.zeros(P1 * c1, dtype=torch.uint8, device="cuda") for _ in range(P1)]
+            s1p, r1p = v.pointer_array(s1), v.pointer_array(r1)
+            small = {}
+            for name, mode in (("cu", v.MODE_CU), ("ce", v.MODE_CE)):
+                lat = []
+                for _ in range(32):
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    v.vccl_alltoall(s1p, r1p, c1, P1, mode, st)
+                    torch.cuda.synchronize()
+                    lat.append(time.perf_counter() - t0)
+                small[name + "_call_to_completion_us"] = statistics.median(lat[2:]) * 1e6
+                for r, s in ((1, 3), (2, 0)):
+                    assert torch.equal(r1[r][s * c1:(s + 1) * c1], s1[s][r * c1:(r + 1) * c1])
+            out["alltoall_p4_64KiB"] = small
         if "sendrecv" in legs:
             # SendRecv ring, 8 stages x 64 MiB: rate and probe slowdown in every mode
             n = 64 << 20
