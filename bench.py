@@ -148,8 +148,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--legs", default="cu,ce,corun,sendrecv,sweep,moe,cpu",
-                    help="comma list of legs to run: cu (always), ce, corun, sendrecv, sweep, moe, cpu, "
+    ap.add_argument("--legs", default="cu,ce,small,corun,sendrecv,sweep,moe,cpu",
+                    help="comma list of legs to run: cu (always), ce, small, corun, sendrecv, sweep, moe, cpu, "
                          "calib (a plain 1 GiB device copy, used to scale profiler counters)")
     ap.add_argument("--ce-sync", default="default", choices=["default", "memops", "event", "host"],
                     help="ordering of the copy-engine path: the library's default for this process, stream "
@@ -161,7 +161,7 @@ def main():
                          "long, alone or not), so it gets more pairs")
     args = ap.parse_args()
     legs = set(x.strip() for x in args.legs.split(",") if x.strip())
-    unknown = legs - {"cu", "ce", "corun", "sendrecv", "sweep", "moe", "cpu", "calib"}
+    unknown = legs - {"cu", "ce", "small", "corun", "sendrecv", "sweep", "moe", "cpu", "calib"}
     if unknown:
         print(f"bench.py: unknown legs {sorted(unknown)}", file=sys.stderr)
         sys.exit(2)
@@ -288,7 +288,7 @@ def main():
                             "cu_path": cor_cu, "cu_path_capped_1wg_per_cu": cor_cap,
                             "cu_path_capped_64wg": cor_cap64, "cu_path_capped_32wg": cor_cap32,
                             "copy_engine_path": cor_ce}
-        if "ce" in legs:
+        if "small" in legs:
             # the small configuration (P = 4 x 64 KiB, 2 MiB of traffic): too small for a rate, so the time from
             # the call to the completion of the stream on an idle device, both paths, median of 30 single calls
             P1, c1 = 4, 64 << 10
